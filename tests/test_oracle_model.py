@@ -1,0 +1,268 @@
+"""Pins for the oracle's target-model forward, verify step and decode loops (CPU only).
+
+Independent references: the Llama implementation of the `transformers` library
+(same architecture, loaded with the same random weights), torch's attention and
+bfloat16 conversion, closed-form properties of rotary embedding and RMSNorm,
+and the paper's invariants (greedy CopySpec == plain greedy; rollback leaves no
+trace of rejected tokens; one guaranteed token per step).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import copyspec_oracle as orc
+import synth
+from synth import ModelShape
+
+SMALL = ModelShape("small-gqa", 2, 64, 4, 2, 16, 96, 97, 10000.0, 1e-5, "f32")
+SMALL_BF16 = ModelShape("small-gqa-bf16", 2, 64, 4, 2, 16, 96, 97, 10000.0, 1e-5, "bf16")
+
+
+@pytest.fixture(scope="module")
+def small_w():
+    return synth.model_weights(SMALL, 1234, threads=1)
+
+
+@pytest.fixture(scope="module")
+def tiny_w():
+    return synth.model_weights(synth.TINY, synth.seed_for(1), threads=4)
+
+
+def _hf_model(w):
+    from transformers import LlamaConfig, LlamaForCausalLM
+    sh = w["shape"]
+    cfg = LlamaConfig(vocab_size=sh.vocab, hidden_size=sh.d_model, intermediate_size=sh.d_ff,
+                      num_hidden_layers=sh.n_layers, num_attention_heads=sh.n_heads,
+                      num_key_value_heads=sh.n_kv_heads, head_dim=sh.head_dim,
+                      rms_norm_eps=sh.rms_eps, rope_theta=sh.rope_theta,
+                      tie_word_embeddings=False, attention_bias=False, mlp_bias=False,
+                      max_position_embeddings=4096, hidden_act="silu")
+    m = LlamaForCausalLM(cfg).double().eval()
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    sd = {"model.embed_tokens.weight": t(w["embed"]), "model.norm.weight": t(w["final_norm"]),
+          "lm_head.weight": t(w["lm_head"])}
+    names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj",
+             "wo": "self_attn.o_proj", "wg": "mlp.gate_proj", "wu": "mlp.up_proj",
+             "wd": "mlp.down_proj", "norm1": "input_layernorm", "norm2": "post_attention_layernorm"}
+    for l, lw in enumerate(w["layers"]):
+        for k, n in names.items():
+            sd[f"model.layers.{l}.{n}.weight"] = t(lw[k])
+    missing, unexpected = m.load_state_dict(sd, strict=False)
+    assert not [k for k in missing if "rotary" not in k], missing
+    assert not unexpected
+    return m
+
+
+def test_forward_matches_library_llama(small_w):
+    """Whole-model pin: same weights in an independently written Llama implementation."""
+    m = _hf_model(small_w)
+    rng = np.random.default_rng(3)
+    toks = rng.integers(0, SMALL.vocab, 37)
+    with torch.no_grad():
+        ref = m(torch.from_numpy(toks)[None]).logits[0].numpy()
+    kv = orc.KVCache(SMALL, 64)
+    got = orc.forward_block(small_w, kv, toks, store_dtype="f64")
+    # the library builds its rotary cos/sin tables in float32, which limits agreement to
+    # ~1e-6; any structural mistake (pairing, head mapping, norm, activation) gives O(1)
+    assert np.abs(got - ref).max() < 5e-6
+    # block over a non-empty cache: same logits for the tail rows
+    kv2 = orc.KVCache(SMALL, 64)
+    orc.forward_block(small_w, kv2, toks[:20], store_dtype="f64")
+    kv2.truncate(20)
+    tail = orc.forward_block(small_w, kv2, toks[20:], store_dtype="f64")
+    assert np.abs(tail - ref[20:]).max() < 5e-6
+    assert np.abs(tail - got[20:]).max() < 1e-11
+
+
+def test_block_equals_sequential_rows(small_w):
+    """Causality: an (m+1)-row block gives the logits of m+1 single-row steps."""
+    rng = np.random.default_rng(4)
+    toks = rng.integers(0, SMALL.vocab, 19)
+    kv = orc.KVCache(SMALL, 32)
+    block = orc.forward_block(small_w, kv, toks)
+    kv1 = orc.KVCache(SMALL, 32)
+    for i, t in enumerate(toks):
+        row = orc.forward_block(small_w, kv1, [t])
+        kv1.truncate(i + 1)
+        assert np.abs(row[0] - block[i]).max() < 1e-9
+    assert np.array_equal(kv.k[:, :, :19], kv1.k[:, :, :19])
+
+
+def test_attention_vs_torch_sdpa():
+    rng = np.random.default_rng(8)
+    n, R, hd = 75, 6, 16
+    L = n - R
+    q, kc, vc = rng.standard_normal((R, hd)), rng.standard_normal((n, hd)), rng.standard_normal((n, hd))
+    pos = L + np.arange(R)
+    got = orc.causal_attention(q, kc, vc, pos)
+    mask = torch.from_numpy(np.arange(n)[None, :] <= pos[:, None])
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None, None], torch.from_numpy(kc)[None, None],
+        torch.from_numpy(vc)[None, None], attn_mask=mask[None, None])[0, 0].numpy()
+    assert np.abs(got - ref).max() < 1e-12
+    # brute force, one output element at a time
+    for i in range(R):
+        s = np.array([q[i] @ kc[j] / np.sqrt(hd) for j in range(L + i + 1)])
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        assert np.abs(sum(p[j] * vc[j] for j in range(L + i + 1)) - got[i]).max() < 1e-12
+
+
+def test_rotary_properties():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((5, 3, 32))
+    y = rng.standard_normal((5, 3, 32))
+    zero = orc.rotary(x, np.zeros(5), 10000.0)
+    assert np.array_equal(zero, x)                                    # position 0 = identity
+    pos = np.array([0, 1, 7, 100, 4095])
+    rx = orc.rotary(x, pos, 10000.0)
+    assert np.allclose(np.linalg.norm(rx, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    # <rot(q,m), rot(k,n)> depends only on m - n
+    a = np.sum(orc.rotary(x, pos, 1e4) * orc.rotary(y, pos - 3 + 10, 1e4), -1)
+    b = np.sum(orc.rotary(x, pos + 50, 1e4) * orc.rotary(y, pos - 3 + 60, 1e4), -1)
+    assert np.allclose(a, b, rtol=1e-9, atol=1e-9)
+    # explicit 2x2 rotation of pair (j, j+hd/2) by pos * theta^(-2j/hd)
+    hd, j, p, th = 32, 5, 7.0, 10000.0
+    ang = p * th ** (-2 * j / hd)
+    got = orc.rotary(x[:1, :1], np.array([p]), th)[0, 0]
+    assert np.isclose(got[j], x[0, 0, j] * np.cos(ang) - x[0, 0, j + 16] * np.sin(ang))
+    assert np.isclose(got[j + 16], x[0, 0, j + 16] * np.cos(ang) + x[0, 0, j] * np.sin(ang))
+
+
+def test_rmsnorm_and_silu():
+    rng = np.random.default_rng(10)
+    x = rng.standard_normal((4, 64)) * 3
+    y = orc.rmsnorm(x, np.ones(64), 0.0)
+    assert np.allclose(np.sqrt(np.mean(y * y, -1)), 1.0)
+    g = rng.standard_normal(64)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x), (64,), torch.from_numpy(g), 1e-5).numpy()
+    assert np.abs(orc.rmsnorm(x, g, 1e-5) - ref).max() < 1e-12
+    assert np.abs(orc.silu(x) - torch.nn.functional.silu(torch.from_numpy(x)).numpy()).max() < 1e-12
+
+
+def test_round_bf16_vs_torch():
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-6, 6, 5000),
+                        np.array([0.0, 1.0, 1.00390625, 1.01171875, -3.0e38, 1e-40])])
+    ref = torch.from_numpy(x.astype(np.float32)).bfloat16().double().numpy()
+    assert np.array_equal(orc.round_bf16(x), ref)
+    bits = synth.f32_to_bf16_bits(x.astype(np.float32))
+    assert np.array_equal(synth.bf16_bits_to_f32(bits).astype(np.float64), ref)
+
+
+def test_bf16_cache_rounding_is_the_only_rounding():
+    w = synth.model_weights(SMALL_BF16, 77, threads=1)
+    toks = np.arange(12) % SMALL_BF16.vocab
+    kv = orc.KVCache(SMALL_BF16, 16)
+    orc.forward_block(w, kv, toks)
+    live = kv.k[:, :, :12]
+    assert np.array_equal(orc.round_bf16(live), live) and np.abs(live).max() > 0
+    assert np.array_equal(orc.round_bf16(kv.v[:, :, :12]), kv.v[:, :, :12])
+
+
+def test_verify_rollback_leaves_no_trace(small_w):
+    """App. B.2 / B.3 'Discussion of Truncation': rejected tokens affect neither the
+    context nor the KV state.  Dead rows are poisoned with NaN to prove they are unread."""
+    rng = np.random.default_rng(13)
+    prompt = rng.integers(0, SMALL.vocab, 25).tolist()
+    truth = orc.greedy_decode(small_w, prompt, 8)
+    for j in range(0, 5):
+        kv = orc.KVCache(SMALL, 64)
+        pending = orc.prefill(small_w, kv, prompt)
+        draft = truth[:j] + [(truth[j] + 1) % SMALL.vocab] + truth[j + 1:6]
+        tau, nxt, _ = orc.verify(small_w, kv, pending, draft)
+        assert tau == j and nxt == truth[j]                 # longest prefix, then the greedy token
+        assert kv.length == len(prompt) - 1 + j + 1
+        kv.k[:, :, kv.length:] = np.nan
+        kv.v[:, :, kv.length:] = np.nan
+        logits = orc.forward_block(small_w, kv, [nxt])
+        fresh = orc.KVCache(SMALL, 64)
+        p2 = orc.prefill(small_w, fresh, prompt + truth[:j + 1])
+        assert p2 == nxt
+        ref = orc.forward_block(small_w, fresh, [p2])
+        assert np.abs(logits - ref).max() < 1e-9
+        assert orc.argmax_first(logits[0]) == truth[j + 1]
+
+
+def test_copyspec_equals_greedy_cfg1(tiny_w):
+    """Output invariance (abstract; Sec. 3.2; App. B.2): on configuration 1 (tiny fp32
+    decoder, 512-token context with planted spans, gamma=3, k=10, 64 new tokens) the
+    CopySpec sequence is the plain greedy sequence."""
+    prompt = synth.history_cfg1()["tokens"].tolist()
+    ref = orc.greedy_decode(tiny_w, prompt, 64)
+    for policy in ("rightmost", "first"):
+        out, st = orc.copyspec_decode(tiny_w, prompt, 64, 3, 10, policy)
+        assert out == ref
+        assert st["attempts"] >= 1 and st["steps"] <= 64
+    out0, st0 = orc.copyspec_decode(tiny_w, prompt, 64, 3, 0)     # k = 0: plain decoding
+    assert out0 == ref and st0["steps"] == 64 and st0["attempts"] == 0
+
+
+def test_draft_independence(small_w):
+    """Whatever is drafted (noise, the true continuation, a true prefix with one edit),
+    the emitted sequence is the greedy one; with the true continuation every attempt is
+    fully accepted."""
+    rng = np.random.default_rng(14)
+    prompt = rng.integers(0, SMALL.vocab, 30).tolist()
+    n_new = 24
+    ref = orc.greedy_decode(small_w, prompt, n_new + 8)
+
+    def true_cont(seq, room):
+        done = len(seq) - len(prompt)
+        return ref[done:done + min(5, room)]
+
+    def noise(seq, room):
+        return rng.integers(0, SMALL.vocab, min(5, room)).tolist()
+
+    def edited(seq, room):
+        d = true_cont(seq, room)
+        if len(d) >= 3:
+            d[2] = (d[2] + 1) % SMALL.vocab
+        return d
+
+    out, st = orc.copyspec_decode(small_w, prompt, n_new, 3, 5, draft_override=true_cont)
+    assert out == ref[:n_new] and st["steps"] == 4 and st["accepted"] == 20
+    out, st = orc.copyspec_decode(small_w, prompt, n_new, 3, 5, draft_override=noise)
+    assert out == ref[:n_new]
+    out, st = orc.copyspec_decode(small_w, prompt, n_new, 3, 5, draft_override=edited)
+    assert out == ref[:n_new] and all(t == 2 for t in st["taus"][:-1])
+
+
+def test_repeat_model_accepts_everything():
+    """Closed form for the full-accept path: with attention and FFN outputs zeroed and
+    lm_head = embedding, the greedy token repeats the current token, so the history
+    becomes x,x,x,... and every attempt after the first gamma tokens accepts all k."""
+    w = synth.model_weights(SMALL, 99, threads=1)
+    for lw in w["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["wd"] = np.zeros_like(lw["wd"])
+    w["lm_head"] = w["embed"].copy()
+    w["final_norm"] = np.ones_like(w["final_norm"])
+    prompt = [3, 1, 4, 1, 5, 9, 2, 6]
+    assert orc.greedy_decode(w, prompt, 40) == [6] * 40
+    # rightmost policy: the match is always at n - 2*gamma, its source runs into the end of
+    # the history after gamma tokens, so every attempt drafts and accepts exactly gamma
+    out, st = orc.copyspec_decode(w, prompt, 40, 3, 10, "rightmost")
+    assert out == [6] * 40
+    assert set(st["taus"][:-1]) == {3} and st["attempts"] == st["steps"] - 5
+    # earliest policy: the source starts at the first run of 6s and grows with the history
+    # until the full block of k = 10 is drafted and accepted
+    out, st = orc.copyspec_decode(w, prompt, 60, 3, 10, "first")
+    assert out == [6] * 60
+    # by hand: 5 plain steps until six 6s exist (n = 13), then the source at index 10 offers
+    # min(10, n - 10) tokens: 3 (n -> 17), 7 (n -> 25), then full blocks of 10
+    assert st["taus"][:5] == [3, 7, 10, 10, 10] and st["steps"] - st["attempts"] == 5
+    assert st["accepted"] == sum(st["taus"])
+
+
+def test_one_guaranteed_token_per_step(small_w):
+    rng = np.random.default_rng(15)
+    prompt = rng.integers(0, SMALL.vocab, 20).tolist()
+    kv = orc.KVCache(SMALL, 64)
+    pending = orc.prefill(small_w, kv, prompt)
+    L = kv.length
+    tau, nxt, logits = orc.verify(small_w, kv, pending, [1, 2, 3])
+    assert logits.shape == (4, SMALL.vocab)
+    assert kv.length == L + tau + 1 and 0 <= nxt < SMALL.vocab
+    with pytest.raises(ValueError):
+        orc.forward_block(small_w, kv, list(range(64)))
