@@ -1,0 +1,246 @@
+/*
+ * copyspec.h - C ABI of libcopyspec: the CopySpec copy-and-verify step on one MI355X.
+ *
+ * CopySpec (arXiv 2502.08923) speeds up greedy decoding by looking for an earlier
+ * occurrence of the last gamma generated tokens in the context, copying the k tokens
+ * that followed it as a draft, and verifying the draft with one forward pass of the
+ * target model (Sec. 3.1-3.2, App. B).  This library is that step, as hand-written HIP
+ * kernels for gfx950, behind plain C entry points.
+ *
+ * Conventions
+ *   - Indices are 0-based.  A history is h[0..n).  gamma = match length, k = copy block
+ *     size (|S_copyspec| in Sec. 3.2, m in App. B.1), tau = number of accepted drafts
+ *     (App. B.1 calls it k; renamed to avoid the clash), L = valid KV length of a stream.
+ *   - "host" / "device" in a parameter comment says where the pointer must point.
+ *     Device pointers must be valid on the current HIP device.  `stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).  Device entry points
+ *     enqueue work on `stream` and return without synchronising unless stated.
+ *   - The caller owns every buffer it passes.  The library owns what its handles point to
+ *     (cs_model, cs_kv) and frees it in the matching *_destroy.
+ *   - Return values: CS_OK (0) or a negative cs_status.  cs_last_error() returns a
+ *     thread-local description of the most recent failure.  On an argument or capacity
+ *     error nothing has been modified.
+ *   - Calls on one handle are not re-entrant; calls that share a handle on different
+ *     streams race.
+ */
+#ifndef COPYSPEC_H
+#define COPYSPEC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cs_status {
+    CS_OK = 0,
+    CS_NO_MATCH = -1,    /* only as a position value, never as a status */
+    CS_E_ARG = -2,       /* NULL pointer, gamma < 1, k < 0, size out of range ... */
+    CS_E_CAPACITY = -3,  /* KV cache or history buffer too small for the request */
+    CS_E_DEVICE = -4,    /* a HIP call failed; text in cs_last_error() */
+    CS_E_STATE = -5,     /* handle used in a state the call does not allow */
+    CS_E_UNSUPPORTED = -6 /* shape outside what the kernels are built for */
+} cs_status;
+
+enum { CS_POLICY_RIGHTMOST = 0, CS_POLICY_FIRST = 1 };
+enum { CS_F32 = 0, CS_BF16 = 1 };
+
+const char* cs_last_error(void);
+/* Library version string (static storage). */
+const char* cs_version(void);
+
+/* ------------------------------------------------------------------------------------
+ * Match search and draft extraction  (Sec. 3.1; Sec. 3.2 first paragraph and footnote;
+ * App. B.1 "Match location p", "Chunk size m"; App. B.3 step 1)
+ *
+ *   M = { p : 0 <= p <= n - 2*gamma  and  h[p+j] == h[n-gamma+j] for all 0 <= j < gamma }
+ *
+ * The bound p <= n - 2*gamma is App. B.3 step 1c (the earlier occurrence must end before
+ * the query suffix starts).  match_pos = max M (CS_POLICY_RIGHTMOST) or min M
+ * (CS_POLICY_FIRST); src_pos = match_pos + gamma is the first token to copy;
+ * draft[i] = h[src_pos + i] for i < draft_len = min(k, n - src_pos).  If M is empty or
+ * n < 2*gamma: match_pos = src_pos = -1, draft_len = 0.  Unused draft slots are set to -1.
+ * The paper finds p with a hash map of all gamma-grams; this library scans the history,
+ * which returns the same p.
+ * ---------------------------------------------------------------------------------- */
+
+/* One history in host memory; copies it to the device, scans, waits.  Returns src_pos
+ * (>= gamma), -1 if there is no match, or a cs_status <= -2. Rightmost policy. */
+int64_t cs_find_match(const int32_t* history /*host [len]*/, int64_t len, int32_t gamma);
+
+/* As above with every output.  Any output pointer may be NULL.  draft: host [k]. */
+int cs_find_match_ex(const int32_t* history /*host [len]*/, int64_t len, int32_t gamma,
+                     int32_t k, int32_t policy, int64_t* match_pos, int64_t* src_pos,
+                     int32_t* draft /*host [k]*/, int32_t* draft_len);
+
+/* B histories resident on the device: stream b is d_hist[b*stride .. b*stride + d_len[b]).
+ * Outputs (device): d_match_pos[B] (may be NULL), d_src_pos[B] (may be NULL),
+ * d_draft[B][k], d_draft_len[B].  Requires 1 <= gamma <= 16, 0 <= k <= 256, B >= 0,
+ * stride >= every length.  B == 0 is a no-op.  Asynchronous on `stream`. */
+int cs_find_match_batch_dev(const int32_t* d_hist /*device*/, int64_t stride,
+                            const int32_t* d_len /*device [B]*/, int32_t B, int32_t gamma,
+                            int32_t k, int32_t policy, int32_t* d_match_pos, int32_t* d_src_pos,
+                            int32_t* d_draft, int32_t* d_draft_len, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Target model  (Sec. 4.1 names the families: Llama-3.1 / Qwen2.5 style decoders; the
+ * paper does not restate the architecture).  Pre-norm decoder: RMSNorm, rotary position
+ * embedding (rotate-half pairing of (j, j + head_dim/2), angle pos * theta^(-2j/head_dim)),
+ * grouped-query attention (query head g uses KV head g / (n_heads/n_kv_heads)), SwiGLU
+ * FFN, untied lm_head, no biases.
+ * ---------------------------------------------------------------------------------- */
+
+typedef struct cs_model_cfg {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab;
+    int32_t dtype;        /* CS_F32 or CS_BF16: storage type of weight matrices and KV cache */
+    float rope_theta;
+    float rms_eps;
+    int32_t max_batch;    /* most streams one verify call will carry */
+    int32_t max_k;        /* largest copy block k a verify call will carry */
+} cs_model_cfg;
+
+/* Linear weights are row-major [out_features][in_features] in cfg.dtype; norm gains are
+ * float32 [d_model].  All pointers are device pointers. */
+typedef struct cs_layer_weights {
+    const void *wq, *wk, *wv;   /* [n_heads*hd][d], [n_kv_heads*hd][d], [n_kv_heads*hd][d] */
+    const void *wo;             /* [d][n_heads*hd] */
+    const void *wg, *wu;        /* [d_ff][d] gate and up projections */
+    const void *wd;             /* [d][d_ff] */
+    const float *norm1, *norm2; /* attention and FFN RMSNorm gains */
+} cs_layer_weights;
+
+typedef struct cs_weights {
+    const void* embed;              /* [vocab][d] */
+    const void* lm_head;            /* [vocab][d] */
+    const float* final_norm;        /* [d] */
+    const cs_layer_weights* layers; /* host array [n_layers] of device pointers */
+} cs_weights;
+
+typedef struct cs_model cs_model;
+typedef struct cs_kv cs_kv;
+
+/* Copies (and re-lays-out) the weights into library-owned device memory; the caller's
+ * buffers may be freed afterwards.  Synchronous. */
+int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_model** out);
+void cs_model_destroy(cs_model*);
+
+/* KV cache for `batch` independent streams of up to `capacity` positions each, all layers.
+ * Lengths start at 0. */
+int cs_kv_create(const cs_model* m, int32_t batch, int64_t capacity, cs_kv** out);
+void cs_kv_destroy(cs_kv*);
+/* Set / read the valid length of one stream (App. B.2 truncation is exactly a smaller
+ * length: rows at and beyond it are dead and are overwritten by later steps).
+ * Both synchronise with the device. */
+int cs_kv_set_len(cs_kv*, int32_t stream_idx, int64_t len);
+int64_t cs_kv_len(cs_kv*, int32_t stream_idx);
+/* Import / export cache rows [pos0, pos0+n) of one (layer, stream): k_rows and v_rows are
+ * device buffers [n_kv_heads][n][head_dim] in cfg.dtype.  Does not change the length.
+ * Synchronous.  Used to seed a cache with given contents and to inspect it in tests. */
+int cs_kv_load(cs_kv*, int32_t layer, int32_t stream_idx, int64_t pos0, int64_t n,
+               const void* k_rows, const void* v_rows);
+int cs_kv_read(cs_kv*, int32_t layer, int32_t stream_idx, int64_t pos0, int64_t n,
+               void* k_rows, void* v_rows);
+
+/* ------------------------------------------------------------------------------------
+ * Verification  (Sec. 3.2 second paragraph; App. B.2; App. B.3 step 2)
+ *
+ * For every stream b with valid length L_b the block [pending_b, draft_b[0..m_b)] with
+ * m_b = draft_len[b] <= k is placed at positions L_b .. L_b+m_b and evaluated in one
+ * forward pass against the cache.  a_i = argmax of the logits of block row i (lowest
+ * index on ties).  tau_b = number of leading i < m_b with a_i == draft_b[i];
+ * next_b = a_tau.  Afterwards L_b = L_b + tau_b + 1: the cache holds pending_b and the
+ * accepted drafts (rows of rejected drafts are dead), and next_b is NOT in the cache: it
+ * is the next call's pending token.  Every call advances each stream by tau_b + 1 tokens.
+ *
+ * All pointers are device pointers.  d_draft is [B][k] (row stride k); slots at and
+ * beyond draft_len are ignored.  d_logits_out may be NULL; otherwise it receives
+ * float32 [B][k+1][vocab] (rows beyond m_b are unspecified).  B must equal the batch of
+ * `kv` and be <= cfg.max_batch; k <= cfg.max_k.  Returns CS_E_CAPACITY if some stream may
+ * not have room for k+1 more rows.  Asynchronous on `stream`.
+ * ---------------------------------------------------------------------------------- */
+int cs_verify(cs_model* m, cs_kv* kv, const int32_t* d_pending /*[B]*/,
+              const int32_t* d_draft /*[B][k]*/, const int32_t* d_draft_len /*[B]*/,
+              int32_t k, int32_t* d_accepted_len /*[B]*/, int32_t* d_next_token /*[B]*/,
+              float* d_logits_out, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * One whole copy-and-verify step on device-resident state  (App. B.3 steps 1, 2, 4)
+ *
+ * d_hist[b*stride .. +d_hist_len[b]) is the token sequence of stream b (prompt plus
+ * everything emitted, Sec. 3.2 third paragraph); its last token is the pending token and
+ * kv length must be d_hist_len[b] - 1.  The call searches each history (gamma, policy),
+ * drafts up to k tokens, clamps the draft to d_room[b] - 1 if d_room != NULL (room =
+ * tokens the stream may still emit), verifies, then appends draft[0..tau) and next to the
+ * history and advances d_hist_len[b] by tau+1 and d_room[b] by -(tau+1).
+ * Outputs d_accepted_len[B], d_next_token[B], d_draft_len_out[B] (may be NULL).
+ * No host synchronisation: the step can be enqueued back to back.
+ * ---------------------------------------------------------------------------------- */
+int cs_step(cs_model* m, cs_kv* kv, int32_t* d_hist, int64_t stride, int32_t* d_hist_len,
+            int32_t* d_room, int32_t gamma, int32_t k, int32_t policy,
+            int32_t* d_accepted_len, int32_t* d_next_token, int32_t* d_draft_len_out,
+            void* stream);
+
+typedef struct cs_stats {
+    int64_t steps;      /* verify calls */
+    int64_t attempts;   /* steps that carried a non-empty draft */
+    int64_t drafted;    /* draft tokens sent to verification */
+    int64_t accepted;   /* draft tokens accepted */
+} cs_stats;
+
+/* ------------------------------------------------------------------------------------
+ * Decode loops  (Sec. 3.2; App. B.3 step 4 "repeat until a stopping criterion")
+ *
+ * cs_decode: stream 0 of `kv` is reset, the prompt (host, >= 1 token) is run through the
+ * model in blocks, then cs_step repeats until exactly max_new tokens are emitted or
+ * eos_id (>= 0) is emitted (the output is cut after it).  out_tokens: host [max_new].
+ * Requires kv batch == 1 and capacity >= prompt_len + max_new + k + 1.
+ * cs_decode_greedy is plain greedy decoding through the same kernels (draft length 0);
+ * by the paper's construction both emit the same tokens.  Synchronous.
+ * ---------------------------------------------------------------------------------- */
+int cs_decode(cs_model* m, cs_kv* kv, const int32_t* prompt /*host*/, int64_t prompt_len,
+              int64_t max_new, int32_t gamma, int32_t k, int32_t policy, int32_t eos_id,
+              int32_t* out_tokens /*host*/, int64_t* n_out, cs_stats* stats /*may be NULL*/);
+int cs_decode_greedy(cs_model* m, cs_kv* kv, const int32_t* prompt /*host*/, int64_t prompt_len,
+                     int64_t max_new, int32_t eos_id, int32_t* out_tokens /*host*/,
+                     int64_t* n_out);
+
+/* Run prompt[0 .. n-1) of one stream through the model in blocks so that its cache holds
+ * them and its length is n-1 (the last prompt token stays pending).  Resets the stream's
+ * length first.  prompt: host.  Synchronous. */
+int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int32_t* prompt /*host*/,
+               int64_t prompt_len);
+
+/* ------------------------------------------------------------------------------------
+ * Single operations of the verify pass, exposed for per-kernel parity tests and timing.
+ * All pointers are device pointers; asynchronous on `stream`.
+ * ---------------------------------------------------------------------------------- */
+
+/* Y[R][N] (float32) = X[R][K] * W[N][K]^T.  dtype CS_BF16: X and W are bfloat16, products
+ * accumulate in float32 on the matrix cores; CS_F32: X and W float32.  Uses `m`'s
+ * workspace, so R <= max_batch*(max_k+1). */
+int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void* W, float* Y,
+               int32_t R, int32_t N, int32_t K, void* stream);
+
+/* Block attention of one layer over the cache (Sec. 3.2: the block is appended to the
+ * context and evaluated in one pass).  q: float32 [B][rows][n_heads][head_dim], already
+ * rotated; row i of stream b sits at position L_b + i and sees cache rows 0 .. L_b + i,
+ * which must already hold its own K/V.  out: float32 [B][rows][n_heads*head_dim].
+ * Softmax in float32 with scale 1/sqrt(head_dim).  rows <= max_k + 1. */
+int cs_op_attention(cs_model* m, cs_kv* kv, int32_t layer, const float* q, int32_t rows,
+                    float* out, void* stream);
+
+/* Greedy argmax per row fused with the accept rule (App. B.2).  logits: float32
+ * [B][k+1][V]; draft [B][k]; draft_len [B].  Outputs accepted_len[B], next_token[B] and,
+ * if not NULL, row_argmax [B][k+1]. */
+int cs_op_argmax_accept(cs_model* m, const float* logits, int32_t B, int32_t k, int32_t V,
+                        const int32_t* draft, const int32_t* draft_len, int32_t* accepted_len,
+                        int32_t* next_token, int32_t* row_argmax, void* stream);
+
+/* Select kernel variants for the following cs_model_create calls: 0 = tuned kernels where
+ * the shape allows (default), 1 = plain reference kernels everywhere. */
+void cs_set_plain_kernels(int32_t on);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COPYSPEC_H */

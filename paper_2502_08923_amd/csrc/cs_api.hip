@@ -1,0 +1,667 @@
+// C ABI of libcopyspec: handles, the verify pass, the whole step and the decode loops.
+// Host logic only; every arithmetic step runs in the kernels of the other files.
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include <vector>
+
+#include "cs_common.h"
+
+// -------------------------------------------------------------------------------------
+// errors
+// -------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+void cs_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* cs_last_error(void) { return g_err; }
+extern "C" const char* cs_version(void) { return "copyspec-gfx950 0.1"; }
+
+static int g_plain = 0;
+extern "C" void cs_set_plain_kernels(int32_t on) { g_plain = on ? 1 : 0; }
+
+// -------------------------------------------------------------------------------------
+// small kernels used only here
+// -------------------------------------------------------------------------------------
+// interleave gate and up rows in blocks of 16: dst row (f/16)*32 + 16*u + f%16
+template <typename T>
+__global__ void k_pack_gu(const T* __restrict__ wg, const T* __restrict__ wu, int F, int d,
+                          T* __restrict__ dst) {
+    const int row = blockIdx.x;               // destination row
+    const int f = (row / 32) * 16 + row % 16;
+    const T* __restrict__ src = ((row / 16) % 2 ? wu : wg) + (int64_t)f * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(int64_t)row * d + c] = src[c];
+}
+
+// V rows [KVH][n][hd] <-> transposed cache [KVH][hd][cap]
+template <typename T, int TO_CACHE>
+__global__ void k_v_transpose(T* __restrict__ cache, T* __restrict__ rows, int64_t cap, int hd,
+                              int64_t pos0, int64_t n) {
+    const int g = blockIdx.y;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n * hd;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t t = idx / hd;
+        const int d = (int)(idx % hd);
+        T* c = cache + ((int64_t)g * hd + d) * cap + pos0 + t;
+        T* r = rows + ((int64_t)g * n + t) * hd + d;
+        if (TO_CACHE) *c = *r; else *r = *c;
+    }
+}
+
+__global__ void k_pending(const int32_t* __restrict__ hist, int64_t stride,
+                          const int32_t* __restrict__ hist_len, int B, int32_t* __restrict__ pending) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) pending[b] = hist[(int64_t)b * stride + hist_len[b] - 1];
+}
+
+__global__ void k_add_i32(int32_t* p, int32_t v, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] += v;
+}
+
+__global__ void k_sum_parts(const float* __restrict__ part, int nparts, int64_t n,
+                            float* __restrict__ y) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        float a = 0.f;
+        for (int p = 0; p < nparts; ++p) a += part[p * n + i];
+        y[i] = a;
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// model
+// -------------------------------------------------------------------------------------
+static int dev_alloc(void** p, size_t bytes) {
+    *p = nullptr;
+    CS_HIP(hipMalloc(p, bytes ? bytes : 16));
+    return CS_OK;
+}
+#define DEV_ALLOC(ptr, bytes) CS_TRY(dev_alloc((void**)&(ptr), (bytes)))
+
+static void model_free(cs_model* m) {
+    if (!m) return;
+    void* ptrs[] = {m->embed, m->lm_head, m->final_norm, m->x, m->xn, m->qkv, m->q, m->gu, m->act,
+                    m->logits, m->part, m->attn_part, m->rope, m->tok, m->am_val_idx,
+                    m->row_argmax, m->draft, m->draft_len, m->match_pos, m->pending};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    if (m->layers) {
+        for (int l = 0; l < m->cfg.n_layers; ++l) {
+            cs_layer_dev& L = m->layers[l];
+            void* lp[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2};
+            for (void* p : lp)
+                if (p) (void)hipFree(p);
+        }
+        free(m->layers);
+    }
+    free(m);
+}
+
+static int model_build(cs_model* m, const cs_weights* w) {
+    const cs_model_cfg& c = m->cfg;
+    const size_t e = m->esz;
+    const int d = c.d_model, hd = c.head_dim, H = c.n_heads, KVH = c.n_kv_heads, F = c.d_ff,
+              V = c.vocab;
+    const int nq = H * hd, nkv = KVH * hd, nqkv = nq + 2 * nkv;
+    DEV_ALLOC(m->embed, (size_t)V * d * e);
+    DEV_ALLOC(m->lm_head, (size_t)V * d * e);
+    DEV_ALLOC(m->final_norm, (size_t)d * 4);
+    CS_HIP(hipMemcpy(m->embed, w->embed, (size_t)V * d * e, hipMemcpyDeviceToDevice));
+    CS_HIP(hipMemcpy(m->lm_head, w->lm_head, (size_t)V * d * e, hipMemcpyDeviceToDevice));
+    CS_HIP(hipMemcpy(m->final_norm, w->final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice));
+    for (int l = 0; l < c.n_layers; ++l) {
+        const cs_layer_weights& s = w->layers[l];
+        CS_REQUIRE(s.wq && s.wk && s.wv && s.wo && s.wg && s.wu && s.wd && s.norm1 && s.norm2,
+                   CS_E_ARG, "layer %d has a NULL weight pointer", l);
+        cs_layer_dev& L = m->layers[l];
+        DEV_ALLOC(L.wqkv, (size_t)nqkv * d * e);
+        DEV_ALLOC(L.wo, (size_t)d * nq * e);
+        DEV_ALLOC(L.wgu, (size_t)2 * F * d * e);
+        DEV_ALLOC(L.wd, (size_t)d * F * e);
+        DEV_ALLOC(L.norm1, (size_t)d * 4);
+        DEV_ALLOC(L.norm2, (size_t)d * 4);
+        char* qkv = (char*)L.wqkv;
+        CS_HIP(hipMemcpy(qkv, s.wq, (size_t)nq * d * e, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(qkv + (size_t)nq * d * e, s.wk, (size_t)nkv * d * e, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(qkv + (size_t)(nq + nkv) * d * e, s.wv, (size_t)nkv * d * e,
+                         hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.wo, s.wo, (size_t)d * nq * e, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.wd, s.wd, (size_t)d * F * e, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.norm1, s.norm1, (size_t)d * 4, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
+        if (c.dtype == CS_BF16)
+            k_pack_gu<bf16_t><<<2 * F, 256>>>((const bf16_t*)s.wg, (const bf16_t*)s.wu, F, d,
+                                             (bf16_t*)L.wgu);
+        else
+            k_pack_gu<float><<<2 * F, 256>>>((const float*)s.wg, (const float*)s.wu, F, d,
+                                            (float*)L.wgu);
+        CS_TRY(cs_launch_ok("k_pack_gu"));
+    }
+    const size_t R = (size_t)m->R_max;
+    const size_t a = m->asz;
+    const int wide = d > nq ? d : nq;
+    DEV_ALLOC(m->x, R * d * 4);
+    DEV_ALLOC(m->xn, R * wide * 4);
+    DEV_ALLOC(m->q, R * nq * 4);
+    if (!m->fast) DEV_ALLOC(m->gu, R * 2 * F * 4);
+    DEV_ALLOC(m->act, R * F * (a > 0 ? a : 4));
+    DEV_ALLOC(m->logits, R * V * 4);
+    const int widest = nqkv > d ? nqkv : d;
+    m->part_floats = (size_t)16 * R * widest;
+    DEV_ALLOC(m->part, m->part_floats * 4);
+    const int nqg_max = (int)cs_ceil_div((H / KVH) * m->rows_max, 48);
+    m->attn_part_floats =
+        (size_t)(4 * (512 + (size_t)c.max_batch * KVH * nqg_max) + 64) * 48 * (hd + 2);
+    if (m->fast) DEV_ALLOC(m->attn_part, m->attn_part_floats * 4);
+    DEV_ALLOC(m->rope, R * (hd / 2) * sizeof(float2));
+    DEV_ALLOC(m->tok, R * 4);
+    m->am_chunks = 64;
+    DEV_ALLOC(m->am_val_idx, R * m->am_chunks * 2 * 4);
+    DEV_ALLOC(m->row_argmax, R * 4);
+    DEV_ALLOC(m->draft, (size_t)c.max_batch * (c.max_k > 0 ? c.max_k : 1) * 4);
+    DEV_ALLOC(m->draft_len, (size_t)c.max_batch * 4);
+    DEV_ALLOC(m->match_pos, (size_t)c.max_batch * 4);
+    DEV_ALLOC(m->pending, (size_t)c.max_batch * 4);
+    CS_HIP(hipDeviceSynchronize());
+    return CS_OK;
+}
+
+extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_model** out) {
+    CS_REQUIRE(cfg && w && out, CS_E_ARG, "cs_model_create: NULL argument");
+    CS_REQUIRE(w->embed && w->lm_head && w->final_norm && w->layers, CS_E_ARG,
+               "cs_model_create: NULL weight pointer");
+    const cs_model_cfg& c = *cfg;
+    CS_REQUIRE(c.n_layers >= 1 && c.d_model >= 1 && c.n_heads >= 1 && c.n_kv_heads >= 1 &&
+                   c.head_dim >= 2 && c.d_ff >= 1 && c.vocab >= 1,
+               CS_E_ARG, "cs_model_create: non-positive dimension");
+    CS_REQUIRE(c.dtype == CS_F32 || c.dtype == CS_BF16, CS_E_ARG, "cs_model_create: bad dtype");
+    CS_REQUIRE(c.n_heads % c.n_kv_heads == 0, CS_E_ARG, "n_heads must be a multiple of n_kv_heads");
+    CS_REQUIRE(c.head_dim % 2 == 0 && c.head_dim <= 256 && 256 % c.head_dim == 0, CS_E_UNSUPPORTED,
+               "head_dim must be a power of two in 2..256");
+    CS_REQUIRE(c.d_ff % 16 == 0, CS_E_UNSUPPORTED, "d_ff must be a multiple of 16");
+    CS_REQUIRE(c.d_model <= 8192, CS_E_UNSUPPORTED, "d_model must be <= 8192");
+    CS_REQUIRE(c.max_batch >= 1 && c.max_k >= 0 && c.max_k <= 256, CS_E_ARG,
+               "max_batch >= 1 and 0 <= max_k <= 256 required");
+    cs_model* m = (cs_model*)calloc(1, sizeof(cs_model));
+    CS_REQUIRE(m, CS_E_DEVICE, "out of host memory");
+    m->cfg = c;
+    m->plain = g_plain;
+    m->rows_max = c.max_k + 1;
+    m->R_max = c.max_batch * m->rows_max;
+    m->esz = c.dtype == CS_BF16 ? 2 : 4;
+    const int nq = c.n_heads * c.head_dim;
+    m->fast = !m->plain && c.dtype == CS_BF16 && (c.head_dim == 64 || c.head_dim == 128) &&
+              c.d_model % 128 == 0 && c.d_ff % 128 == 0 && nq % 128 == 0;
+    m->asz = m->fast ? 2 : 4;
+    m->layers = (cs_layer_dev*)calloc(c.n_layers, sizeof(cs_layer_dev));
+    if (!m->layers) { free(m); cs_set_error("out of host memory"); return CS_E_DEVICE; }
+    const int rc = model_build(m, w);
+    if (rc != CS_OK) { model_free(m); return rc; }
+    *out = m;
+    return CS_OK;
+}
+
+extern "C" void cs_model_destroy(cs_model* m) {
+    if (m) (void)hipDeviceSynchronize();
+    model_free(m);
+}
+
+// -------------------------------------------------------------------------------------
+// KV cache
+// -------------------------------------------------------------------------------------
+extern "C" int cs_kv_create(const cs_model* m, int32_t batch, int64_t capacity, cs_kv** out) {
+    CS_REQUIRE(m && out, CS_E_ARG, "cs_kv_create: NULL argument");
+    CS_REQUIRE(batch >= 1 && batch <= m->cfg.max_batch, CS_E_ARG,
+               "cs_kv_create: batch %d outside 1..max_batch=%d", batch, m->cfg.max_batch);
+    CS_REQUIRE(capacity >= 1 && capacity < (int64_t)1 << 30, CS_E_ARG, "cs_kv_create: bad capacity");
+    cs_kv* kv = (cs_kv*)calloc(1, sizeof(cs_kv));
+    CS_REQUIRE(kv, CS_E_DEVICE, "out of host memory");
+    kv->m = m;
+    kv->B = batch;
+    kv->cap = cs_round_up(capacity, 64);
+    const cs_model_cfg& c = m->cfg;
+    const size_t bytes = (size_t)c.n_layers * batch * c.n_kv_heads * kv->cap * c.head_dim * m->esz;
+    kv->h_len_ub = (int64_t*)calloc(batch, sizeof(int64_t));
+    int rc = CS_OK;
+    if (!kv->h_len_ub) { cs_set_error("out of host memory"); rc = CS_E_DEVICE; }
+    if (rc == CS_OK) rc = dev_alloc(&kv->k, bytes);
+    if (rc == CS_OK) rc = dev_alloc(&kv->v, bytes);
+    if (rc == CS_OK) rc = dev_alloc((void**)&kv->d_len, (size_t)batch * 4);
+    // dead rows must hold finite numbers (they are multiplied by zero probabilities)
+    if (rc == CS_OK && hipMemset(kv->k, 0, bytes) != hipSuccess) rc = CS_E_DEVICE;
+    if (rc == CS_OK && hipMemset(kv->v, 0, bytes) != hipSuccess) rc = CS_E_DEVICE;
+    if (rc == CS_OK && hipMemset(kv->d_len, 0, (size_t)batch * 4) != hipSuccess) rc = CS_E_DEVICE;
+    if (rc == CS_OK && hipDeviceSynchronize() != hipSuccess) rc = CS_E_DEVICE;
+    if (rc != CS_OK) {
+        if (g_err[0] == 0) cs_set_error("cs_kv_create: device allocation failed");
+        cs_kv_destroy(kv);
+        return rc;
+    }
+    *out = kv;
+    return CS_OK;
+}
+
+extern "C" void cs_kv_destroy(cs_kv* kv) {
+    if (!kv) return;
+    (void)hipDeviceSynchronize();
+    if (kv->k) (void)hipFree(kv->k);
+    if (kv->v) (void)hipFree(kv->v);
+    if (kv->d_len) (void)hipFree(kv->d_len);
+    free(kv->h_len_ub);
+    free(kv);
+}
+
+extern "C" int cs_kv_set_len(cs_kv* kv, int32_t b, int64_t len) {
+    CS_REQUIRE(kv, CS_E_ARG, "cs_kv_set_len: NULL handle");
+    CS_REQUIRE(b >= 0 && b < kv->B, CS_E_ARG, "cs_kv_set_len: stream %d out of range", b);
+    CS_REQUIRE(len >= 0 && len <= kv->cap, CS_E_CAPACITY, "cs_kv_set_len: length %lld > capacity",
+               (long long)len);
+    const int32_t v = (int32_t)len;
+    CS_HIP(hipDeviceSynchronize());
+    CS_HIP(hipMemcpy(kv->d_len + b, &v, 4, hipMemcpyHostToDevice));
+    kv->h_len_ub[b] = len;
+    return CS_OK;
+}
+
+static int kv_sync_lengths(cs_kv* kv) {
+    std::vector<int32_t> h(kv->B);
+    CS_HIP(hipDeviceSynchronize());
+    CS_HIP(hipMemcpy(h.data(), kv->d_len, (size_t)kv->B * 4, hipMemcpyDeviceToHost));
+    for (int b = 0; b < kv->B; ++b) kv->h_len_ub[b] = h[b];
+    return CS_OK;
+}
+
+extern "C" int64_t cs_kv_len(cs_kv* kv, int32_t b) {
+    CS_REQUIRE(kv, CS_E_ARG, "cs_kv_len: NULL handle");
+    CS_REQUIRE(b >= 0 && b < kv->B, CS_E_ARG, "cs_kv_len: stream %d out of range", b);
+    CS_TRY(kv_sync_lengths(kv));
+    return kv->h_len_ub[b];
+}
+
+static int kv_io(cs_kv* kv, int layer, int b, int64_t pos0, int64_t n, void* k_rows, void* v_rows,
+                 bool to_cache) {
+    CS_REQUIRE(kv && k_rows && v_rows, CS_E_ARG, "cs_kv_load/read: NULL argument");
+    const cs_model_cfg& c = kv->m->cfg;
+    CS_REQUIRE(layer >= 0 && layer < c.n_layers && b >= 0 && b < kv->B, CS_E_ARG,
+               "cs_kv_load/read: layer or stream out of range");
+    CS_REQUIRE(pos0 >= 0 && n >= 0 && pos0 + n <= kv->cap, CS_E_CAPACITY,
+               "cs_kv_load/read: rows [%lld, %lld) exceed capacity %lld", (long long)pos0,
+               (long long)(pos0 + n), (long long)kv->cap);
+    if (n == 0) return CS_OK;
+    const size_t e = kv->m->esz;
+    const int hd = c.head_dim, KVH = c.n_kv_heads;
+    const int64_t item = ((int64_t)layer * kv->B + b) * KVH;
+    char* kc = (char*)kv->k + (item * kv->cap + pos0) * hd * e;
+    if (to_cache)
+        CS_HIP(hipMemcpy2D(kc, (size_t)kv->cap * hd * e, k_rows, (size_t)n * hd * e, (size_t)n * hd * e,
+                           KVH, hipMemcpyDeviceToDevice));
+    else
+        CS_HIP(hipMemcpy2D(k_rows, (size_t)n * hd * e, kc, (size_t)kv->cap * hd * e, (size_t)n * hd * e,
+                           KVH, hipMemcpyDeviceToDevice));
+    char* vc = (char*)kv->v + item * hd * kv->cap * e;
+    dim3 grid((unsigned)(cs_ceil_div(n * hd, 256) < 1024 ? cs_ceil_div(n * hd, 256) : 1024), KVH);
+    if (c.dtype == CS_BF16) {
+        if (to_cache) k_v_transpose<bf16_t, 1><<<grid, 256>>>((bf16_t*)vc, (bf16_t*)v_rows, kv->cap, hd, pos0, n);
+        else k_v_transpose<bf16_t, 0><<<grid, 256>>>((bf16_t*)vc, (bf16_t*)v_rows, kv->cap, hd, pos0, n);
+    } else {
+        if (to_cache) k_v_transpose<float, 1><<<grid, 256>>>((float*)vc, (float*)v_rows, kv->cap, hd, pos0, n);
+        else k_v_transpose<float, 0><<<grid, 256>>>((float*)vc, (float*)v_rows, kv->cap, hd, pos0, n);
+    }
+    CS_TRY(cs_launch_ok("k_v_transpose"));
+    CS_HIP(hipDeviceSynchronize());
+    return CS_OK;
+}
+
+extern "C" int cs_kv_load(cs_kv* kv, int32_t layer, int32_t b, int64_t pos0, int64_t n,
+                          const void* k_rows, const void* v_rows) {
+    return kv_io(kv, layer, b, pos0, n, (void*)k_rows, (void*)v_rows, true);
+}
+extern "C" int cs_kv_read(cs_kv* kv, int32_t layer, int32_t b, int64_t pos0, int64_t n, void* k_rows,
+                          void* v_rows) {
+    return kv_io(kv, layer, b, pos0, n, k_rows, v_rows, false);
+}
+
+// -------------------------------------------------------------------------------------
+// match search entry points
+// -------------------------------------------------------------------------------------
+static int check_scan_args(int gamma, int k, int policy) {
+    CS_REQUIRE(gamma >= 1 && gamma <= 16, CS_E_ARG, "gamma must be in 1..16 (got %d)", gamma);
+    CS_REQUIRE(k >= 0 && k <= 256, CS_E_ARG, "k must be in 0..256 (got %d)", k);
+    CS_REQUIRE(policy == CS_POLICY_RIGHTMOST || policy == CS_POLICY_FIRST, CS_E_ARG,
+               "unknown match policy %d", policy);
+    return CS_OK;
+}
+
+extern "C" int cs_find_match_batch_dev(const int32_t* d_hist, int64_t stride, const int32_t* d_len,
+                                       int32_t B, int32_t gamma, int32_t k, int32_t policy,
+                                       int32_t* d_match_pos, int32_t* d_src_pos, int32_t* d_draft,
+                                       int32_t* d_draft_len, void* stream) {
+    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_REQUIRE(B >= 0, CS_E_ARG, "B must be >= 0");
+    if (B == 0) return CS_OK;
+    CS_REQUIRE(d_hist && d_len && d_draft_len && (d_draft || k == 0), CS_E_ARG,
+               "cs_find_match_batch_dev: NULL pointer");
+    CS_REQUIRE(stride >= 1 && stride < (int64_t)1 << 31, CS_E_ARG, "stride out of range");
+    return cs_scan_launch(d_hist, stride, d_len, B, gamma, k, policy, stride, d_match_pos, d_src_pos,
+                          d_draft, d_draft_len, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int cs_find_match_ex(const int32_t* history, int64_t len, int32_t gamma, int32_t k,
+                                int32_t policy, int64_t* match_pos, int64_t* src_pos, int32_t* draft,
+                                int32_t* draft_len) {
+    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_REQUIRE(len >= 0 && len < (int64_t)1 << 31, CS_E_ARG, "history length out of range");
+    CS_REQUIRE(history || len == 0, CS_E_ARG, "cs_find_match: NULL history");
+    int32_t out[3] = {-1, -1, 0};
+    std::vector<int32_t> hdraft((size_t)(k > 0 ? k : 1), -1);
+    if (len >= 2 * (int64_t)gamma) {
+        const int64_t stride = cs_round_up(len, 4);
+        int32_t* d = nullptr;
+        const size_t words = (size_t)stride + 4 + (size_t)(k > 0 ? k : 1);
+        CS_HIP(hipMalloc(&d, words * 4));
+        int32_t* d_len = d + stride;
+        int32_t* d_out = d_len + 1;         // match, src, draft_len
+        int32_t* d_draft = d_out + 3;
+        const int32_t n32 = (int32_t)len;
+        int rc = CS_OK;
+        if (hipMemcpy(d, history, (size_t)len * 4, hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(d_len, &n32, 4, hipMemcpyHostToDevice) != hipSuccess) {
+            cs_set_error("cs_find_match: copy to device failed");
+            rc = CS_E_DEVICE;
+        }
+        if (rc == CS_OK)
+            rc = cs_scan_launch(d, stride, d_len, 1, gamma, k, policy, len, d_out, d_out + 1, d_draft,
+                                d_out + 2, nullptr, nullptr);
+        if (rc == CS_OK && (hipMemcpy(out, d_out, 12, hipMemcpyDeviceToHost) != hipSuccess ||
+                            (k > 0 && hipMemcpy(hdraft.data(), d_draft, (size_t)k * 4,
+                                                hipMemcpyDeviceToHost) != hipSuccess))) {
+            cs_set_error("cs_find_match: copy from device failed");
+            rc = CS_E_DEVICE;
+        }
+        (void)hipFree(d);
+        if (rc != CS_OK) return rc;
+    }
+    if (match_pos) *match_pos = out[0];
+    if (src_pos) *src_pos = out[1];
+    if (draft_len) *draft_len = out[2];
+    if (draft)
+        for (int i = 0; i < k; ++i) draft[i] = hdraft[i];
+    return CS_OK;
+}
+
+extern "C" int64_t cs_find_match(const int32_t* history, int64_t len, int32_t gamma) {
+    int64_t src = -1;
+    const int rc = cs_find_match_ex(history, len, gamma, 0, CS_POLICY_RIGHTMOST, nullptr, &src,
+                                    nullptr, nullptr);
+    return rc == CS_OK ? src : (int64_t)rc;
+}
+
+// -------------------------------------------------------------------------------------
+// verify pass
+// -------------------------------------------------------------------------------------
+static int64_t kv_max_ub(const cs_kv* kv) {
+    int64_t mx = 0;
+    for (int b = 0; b < kv->B; ++b) mx = kv->h_len_ub[b] > mx ? kv->h_len_ub[b] : mx;
+    return mx;
+}
+
+// every stream must have room for `rows` more rows; refreshes the host bounds if needed
+static int kv_check_room(cs_kv* kv, int rows) {
+    if (kv_max_ub(kv) + rows > kv->cap) CS_TRY(kv_sync_lengths(kv));
+    CS_REQUIRE(kv_max_ub(kv) + rows <= kv->cap, CS_E_CAPACITY,
+               "KV cache full: length %lld + %d rows > capacity %lld", (long long)kv_max_ub(kv), rows,
+               (long long)kv->cap);
+    return CS_OK;
+}
+
+// m->tok holds the block tokens; runs all layers; leaves the final-normed rows in m->xn
+static int forward_layers(cs_model* m, cs_kv* kv, int rows, hipStream_t s) {
+    const cs_model_cfg& c = m->cfg;
+    const int B = kv->B, R = B * rows;
+    const int d = c.d_model, nq = c.n_heads * c.head_dim, nqkv = nq + 2 * c.n_kv_heads * c.head_dim;
+    const int64_t len_ub = kv_max_ub(kv);
+    CS_TRY(cs_rope_table_launch(m, kv->d_len, B, rows, s));
+    CS_TRY(cs_embed_launch(m, m->tok, R, s));
+    int np_prev = 0, np = 1;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const cs_layer_dev& L = m->layers[l];
+        CS_TRY(cs_addnorm_launch(m, m->part, np_prev, L.norm1, m->xn, R, s));
+        CS_TRY(cs_gemm_launch(m, m->xn, L.wqkv, m->part, R, nqkv, d, CS_GEMM_STORE, 1, &np, s));
+        CS_TRY(cs_rope_append_launch(m, kv, l, m->part, np, rows, s));
+        CS_TRY(cs_attention_launch(m, kv, l, rows, len_ub, s));
+        CS_TRY(cs_gemm_launch(m, m->xn, L.wo, m->part, R, d, nq, CS_GEMM_STORE, 1, &np, s));
+        CS_TRY(cs_addnorm_launch(m, m->part, np, L.norm2, m->xn, R, s));
+        if (m->fast) {
+            CS_TRY(cs_gemm_launch(m, m->xn, L.wgu, nullptr, R, 2 * c.d_ff, d, CS_GEMM_SWIGLU, 0,
+                                  nullptr, s));
+        } else {
+            CS_TRY(cs_gemm_launch(m, m->xn, L.wgu, m->gu, R, 2 * c.d_ff, d, CS_GEMM_STORE, 0, nullptr, s));
+            CS_TRY(cs_swiglu_launch(m, R, s));
+        }
+        CS_TRY(cs_gemm_launch(m, m->act, L.wd, m->part, R, d, c.d_ff, CS_GEMM_STORE, 1, &np_prev, s));
+    }
+    return cs_addnorm_launch(m, m->part, np_prev, m->final_norm, m->xn, R, s);
+}
+
+static int verify_impl(cs_model* m, cs_kv* kv, const int32_t* d_pending, const int32_t* d_draft,
+                       const int32_t* d_draft_len, int k, int32_t* d_accepted, int32_t* d_next,
+                       float* d_logits_out, int32_t* hist, int64_t hist_stride, int32_t* hist_len,
+                       int32_t* room, hipStream_t s) {
+    const int rows = k + 1, B = kv->B, R = B * rows, V = m->cfg.vocab;
+    CS_TRY(kv_check_room(kv, rows));
+    CS_TRY(cs_tokens_launch(m, d_pending, d_draft, d_draft_len, B, k, s));
+    CS_TRY(forward_layers(m, kv, rows, s));
+    CS_TRY(cs_gemm_launch(m, m->xn, m->lm_head, m->logits, R, V, m->cfg.d_model, CS_GEMM_STORE, 0,
+                          nullptr, s));
+    CS_TRY(cs_argmax_accept_launch(m, m->logits, B, k, V, d_draft, d_draft_len, d_accepted, d_next,
+                                   nullptr, kv->d_len, hist, hist_stride, hist_len, room, s));
+    if (d_logits_out)
+        CS_HIP(hipMemcpyAsync(d_logits_out, m->logits, (size_t)R * V * 4, hipMemcpyDeviceToDevice, s));
+    for (int b = 0; b < B; ++b) kv->h_len_ub[b] += rows;
+    return CS_OK;
+}
+
+static int check_verify_args(cs_model* m, cs_kv* kv, int k) {
+    CS_REQUIRE(m && kv, CS_E_ARG, "NULL model or kv handle");
+    CS_REQUIRE(kv->m == m, CS_E_STATE, "kv cache belongs to a different model");
+    CS_REQUIRE(k >= 0 && k <= m->cfg.max_k, CS_E_ARG, "k=%d outside 0..max_k=%d", k, m->cfg.max_k);
+    return CS_OK;
+}
+
+extern "C" int cs_verify(cs_model* m, cs_kv* kv, const int32_t* d_pending, const int32_t* d_draft,
+                         const int32_t* d_draft_len, int32_t k, int32_t* d_accepted_len,
+                         int32_t* d_next_token, float* d_logits_out, void* stream) {
+    CS_TRY(check_verify_args(m, kv, k));
+    CS_REQUIRE(d_pending && d_draft_len && d_accepted_len && d_next_token && (d_draft || k == 0),
+               CS_E_ARG, "cs_verify: NULL pointer");
+    return verify_impl(m, kv, d_pending, d_draft, d_draft_len, k, d_accepted_len, d_next_token,
+                       d_logits_out, nullptr, 0, nullptr, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int cs_step(cs_model* m, cs_kv* kv, int32_t* d_hist, int64_t stride, int32_t* d_hist_len,
+                       int32_t* d_room, int32_t gamma, int32_t k, int32_t policy,
+                       int32_t* d_accepted_len, int32_t* d_next_token, int32_t* d_draft_len_out,
+                       void* stream) {
+    CS_TRY(check_verify_args(m, kv, k));
+    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_REQUIRE(d_hist && d_hist_len && d_accepted_len && d_next_token, CS_E_ARG, "cs_step: NULL pointer");
+    CS_REQUIRE(stride >= 1 && stride < (int64_t)1 << 31, CS_E_ARG, "stride out of range");
+    hipStream_t s = (hipStream_t)stream;
+    const int B = kv->B;
+    CS_TRY(kv_check_room(kv, k + 1));
+    // the history may grow by k+1 tokens: same bound as the cache (length = kv length + 1)
+    CS_REQUIRE(kv_max_ub(kv) + 1 + k + 1 <= stride, CS_E_CAPACITY,
+               "history buffer (stride %lld) may overflow", (long long)stride);
+    if (k > 0) {
+        CS_TRY(cs_scan_launch(d_hist, stride, d_hist_len, B, gamma, k, policy, kv_max_ub(kv) + 1,
+                              m->match_pos, nullptr, m->draft, m->draft_len, d_room, s));
+    } else {
+        CS_TRY(cs_fill_i32_launch(m->draft_len, 0, B, s));
+    }
+    k_pending<<<(unsigned)cs_ceil_div(B, 64), 64, 0, s>>>(d_hist, stride, d_hist_len, B, m->pending);
+    CS_TRY(cs_launch_ok("k_pending"));
+    if (d_draft_len_out)
+        CS_HIP(hipMemcpyAsync(d_draft_len_out, m->draft_len, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+    return verify_impl(m, kv, m->pending, m->draft, m->draft_len, k, d_accepted_len, d_next_token,
+                       nullptr, d_hist, stride, d_hist_len, d_room, s);
+}
+
+// -------------------------------------------------------------------------------------
+// prefill and decode loops
+// -------------------------------------------------------------------------------------
+extern "C" int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int32_t* prompt,
+                          int64_t prompt_len) {
+    CS_REQUIRE(m && kv && prompt, CS_E_ARG, "cs_prefill: NULL argument");
+    CS_REQUIRE(kv->m == m, CS_E_STATE, "kv cache belongs to a different model");
+    CS_REQUIRE(kv->B == 1 && stream_idx == 0, CS_E_UNSUPPORTED,
+               "cs_prefill supports single-stream caches only");
+    CS_REQUIRE(prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
+    CS_REQUIRE(prompt_len - 1 <= kv->cap, CS_E_CAPACITY, "prompt longer than the cache");
+    for (int64_t i = 0; i < prompt_len; ++i)
+        CS_REQUIRE(prompt[i] >= 0 && prompt[i] < m->cfg.vocab, CS_E_ARG,
+                   "prompt token %lld out of vocabulary", (long long)i);
+    CS_TRY(cs_kv_set_len(kv, 0, 0));
+    const int64_t body = prompt_len - 1;
+    const int chunk = m->rows_max;
+    for (int64_t c0 = 0; c0 < body; c0 += chunk) {
+        const int rows = (int)(body - c0 < chunk ? body - c0 : chunk);
+        CS_HIP(hipMemcpyAsync(m->tok, prompt + c0, (size_t)rows * 4, hipMemcpyHostToDevice, nullptr));
+        CS_TRY(forward_layers(m, kv, rows, nullptr));
+        k_add_i32<<<1, 64, 0, nullptr>>>(kv->d_len, rows, 1);
+        CS_TRY(cs_launch_ok("k_add_i32"));
+        kv->h_len_ub[0] += rows;
+    }
+    CS_HIP(hipDeviceSynchronize());
+    return CS_OK;
+}
+
+static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t prompt_len,
+                       int64_t max_new, int gamma, int k, int policy, int eos_id, int32_t* out_tokens,
+                       int64_t* n_out, cs_stats* stats) {
+    CS_REQUIRE(out_tokens && n_out, CS_E_ARG, "cs_decode: NULL output");
+    CS_REQUIRE(max_new >= 0, CS_E_ARG, "max_new must be >= 0");
+    CS_TRY(check_verify_args(m, kv, k));
+    CS_REQUIRE(kv->B == 1, CS_E_UNSUPPORTED, "cs_decode needs a single-stream cache");
+    CS_REQUIRE(prompt && prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
+    CS_REQUIRE(prompt_len + max_new + k + 1 <= kv->cap, CS_E_CAPACITY,
+               "cache capacity %lld < prompt_len + max_new + k + 1", (long long)kv->cap);
+    cs_stats st = {0, 0, 0, 0};
+    *n_out = 0;
+    CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));
+    const int64_t stride = cs_round_up(prompt_len + max_new + k + 2, 4);
+    int32_t* d = nullptr;
+    CS_HIP(hipMalloc(&d, (size_t)(stride + 8) * 4));
+    int32_t* d_len = d + stride;          // [0] hist_len, [1] room, [2] accepted, [3] next, [4] draft_len
+    int32_t init[5] = {(int32_t)prompt_len, (int32_t)max_new, 0, 0, 0};
+    int rc = CS_OK;
+    if (hipMemcpy(d, prompt, (size_t)prompt_len * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(d_len, init, sizeof(init), hipMemcpyHostToDevice) != hipSuccess) {
+        cs_set_error("cs_decode: copy to device failed");
+        rc = CS_E_DEVICE;
+    }
+    int64_t emitted = 0;
+    bool stop = false;
+    while (rc == CS_OK && emitted < max_new && !stop) {
+        rc = cs_step(m, kv, d, stride, d_len, d_len + 1, gamma, k, policy, d_len + 2, d_len + 3,
+                     d_len + 4, nullptr);
+        if (rc != CS_OK) break;
+        int32_t h[5];
+        if (hipMemcpy(h, d_len, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) {
+            cs_set_error("cs_decode: copy from device failed");
+            rc = CS_E_DEVICE;
+            break;
+        }
+        const int tau = h[2], got = tau + 1;
+        kv->h_len_ub[0] = h[0] - 1;       // true length: everything but the pending token
+        if (hipMemcpy(out_tokens + emitted, d + (h[0] - got), (size_t)got * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess) {
+            cs_set_error("cs_decode: copy from device failed");
+            rc = CS_E_DEVICE;
+            break;
+        }
+        st.steps += 1;
+        if (h[4] > 0) { st.attempts += 1; st.drafted += h[4]; st.accepted += tau; }
+        for (int i = 0; i < got; ++i) {
+            if (eos_id >= 0 && out_tokens[emitted + i] == eos_id) {
+                emitted += i + 1;
+                stop = true;
+                break;
+            }
+        }
+        if (!stop) emitted += got;
+    }
+    (void)hipFree(d);
+    if (rc != CS_OK) return rc;
+    *n_out = emitted;
+    if (stats) *stats = st;
+    return CS_OK;
+}
+
+extern "C" int cs_decode(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t prompt_len,
+                         int64_t max_new, int32_t gamma, int32_t k, int32_t policy, int32_t eos_id,
+                         int32_t* out_tokens, int64_t* n_out, cs_stats* stats) {
+    CS_TRY(check_scan_args(gamma, k, policy));
+    return decode_impl(m, kv, prompt, prompt_len, max_new, gamma, k, policy, eos_id, out_tokens, n_out,
+                       stats);
+}
+
+extern "C" int cs_decode_greedy(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t prompt_len,
+                                int64_t max_new, int32_t eos_id, int32_t* out_tokens, int64_t* n_out) {
+    return decode_impl(m, kv, prompt, prompt_len, max_new, 1, 0, CS_POLICY_RIGHTMOST, eos_id,
+                       out_tokens, n_out, nullptr);
+}
+
+// -------------------------------------------------------------------------------------
+// single operations
+// -------------------------------------------------------------------------------------
+extern "C" int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void* W, float* Y, int32_t R,
+                          int32_t N, int32_t K, void* stream) {
+    CS_REQUIRE(m && X && W && Y, CS_E_ARG, "cs_op_gemm: NULL argument");
+    CS_REQUIRE(R >= 0 && N >= 1 && K >= 1, CS_E_ARG, "cs_op_gemm: bad shape");
+    hipStream_t s = (hipStream_t)stream;
+    if (R == 0) return CS_OK;
+    if (dtype == CS_F32) return cs_gemm_plain_launch(CS_F32, (const float*)X, W, Y, R, N, K, s);
+    CS_REQUIRE(dtype == CS_BF16, CS_E_ARG, "cs_op_gemm: bad dtype");
+    CS_REQUIRE(m->fast, CS_E_STATE, "cs_op_gemm(bf16) needs a model that runs the bf16 kernels");
+    if ((size_t)R * N > m->part_floats)   // too large for the workspace: no K split, straight to Y
+        return cs_gemm_launch(m, X, W, Y, R, N, K, CS_GEMM_STORE, 0, nullptr, s);
+    int np = 1;
+    CS_TRY(cs_gemm_launch(m, X, W, m->part, R, N, K, CS_GEMM_STORE, 1, &np, s));
+    const int64_t n = (int64_t)R * N;
+    k_sum_parts<<<(unsigned)(cs_ceil_div(n, 256) < 2048 ? cs_ceil_div(n, 256) : 2048), 256, 0, s>>>(
+        m->part, np, n, Y);
+    return cs_launch_ok("k_sum_parts");
+}
+
+extern "C" int cs_op_attention(cs_model* m, cs_kv* kv, int32_t layer, const float* q, int32_t rows,
+                               float* out, void* stream) {
+    CS_REQUIRE(m && kv && q && out, CS_E_ARG, "cs_op_attention: NULL argument");
+    CS_REQUIRE(kv->m == m, CS_E_STATE, "kv cache belongs to a different model");
+    CS_REQUIRE(layer >= 0 && layer < m->cfg.n_layers, CS_E_ARG, "layer out of range");
+    CS_REQUIRE(rows >= 1 && rows <= m->rows_max, CS_E_ARG, "rows outside 1..max_k+1");
+    hipStream_t s = (hipStream_t)stream;
+    CS_TRY(kv_check_room(kv, rows));
+    const int64_t n = (int64_t)kv->B * rows * m->cfg.n_heads * m->cfg.head_dim;
+    CS_TRY(cs_convert_launch(q, 0, m->q, m->fast, n, s));
+    CS_TRY(cs_attention_launch(m, kv, layer, rows, kv_max_ub(kv), s));
+    return cs_convert_launch(m->xn, m->fast, out, 0, n, s);
+}
+
+extern "C" int cs_op_argmax_accept(cs_model* m, const float* logits, int32_t B, int32_t k, int32_t V,
+                                   const int32_t* draft, const int32_t* draft_len,
+                                   int32_t* accepted_len, int32_t* next_token, int32_t* row_argmax,
+                                   void* stream) {
+    CS_REQUIRE(m && logits && draft_len && accepted_len && next_token && (draft || k == 0), CS_E_ARG,
+               "cs_op_argmax_accept: NULL argument");
+    CS_REQUIRE(B >= 1 && k >= 0 && V >= 1 && B * (k + 1) <= m->R_max, CS_E_ARG,
+               "cs_op_argmax_accept: B*(k+1) exceeds the model's max_batch*(max_k+1)");
+    return cs_argmax_accept_launch(m, logits, B, k, V, draft, draft_len, accepted_len, next_token,
+                                   row_argmax, nullptr, nullptr, 0, nullptr, nullptr,
+                                   (hipStream_t)stream);
+}

@@ -1,0 +1,169 @@
+// Internal declarations shared by the translation units of libcopyspec (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/copyspec.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define CS_WAVE 64
+
+// ---- error plumbing -----------------------------------------------------------------
+void cs_set_error(const char* fmt, ...);
+
+#define CS_HIP(call)                                                                      \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) {                                                           \
+            cs_set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, \
+                         __LINE__);                                                       \
+            return CS_E_DEVICE;                                                           \
+        }                                                                                 \
+    } while (0)
+
+#define CS_REQUIRE(cond, code, ...)      \
+    do {                                 \
+        if (!(cond)) {                   \
+            cs_set_error(__VA_ARGS__);   \
+            return (code);               \
+        }                                \
+    } while (0)
+
+#define CS_TRY(expr)              \
+    do {                          \
+        int rc_ = (expr);         \
+        if (rc_ != CS_OK) return rc_; \
+    } while (0)
+
+static inline int cs_launch_ok(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        cs_set_error("launch of %s failed: %s", what, hipGetErrorString(e));
+        return CS_E_DEVICE;
+    }
+    return CS_OK;
+}
+
+static inline int64_t cs_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t cs_round_up(int64_t a, int64_t b) { return cs_ceil_div(a, b) * b; }
+
+// ---- handles ------------------------------------------------------------------------
+struct cs_layer_dev {
+    void* wqkv;    // [(H+2KVH)*hd][d]   rows: q heads, k heads, v heads
+    void* wo;      // [d][H*hd]
+    void* wgu;     // [2F][d]; row (f/16)*32 + 16*u + f%16 holds gate (u=0) or up (u=1) of f
+    void* wd;      // [d][F]
+    float* norm1;
+    float* norm2;
+};
+
+struct cs_model {
+    cs_model_cfg cfg;
+    int plain;          // 1: plain kernels everywhere
+    int fast;           // 1: bf16 MFMA kernels are in use (activations are bf16)
+    int R_max;          // max_batch * (max_k + 1)
+    int rows_max;       // max_k + 1
+    size_t esz;         // bytes per weight / cache element
+    size_t asz;         // bytes per activation element handed to a GEMM
+    void* embed;
+    void* lm_head;
+    float* final_norm;
+    cs_layer_dev* layers;   // host array
+    // workspace (device)
+    float* x;           // [R][d] residual stream
+    void* xn;           // [R][max(d, H*hd)] GEMM input (normed rows / attention output)
+    float* qkv;         // [R][(H+2KVH)*hd]
+    void* q;            // [R][H][hd] rotated queries
+    float* gu;          // [R][2F]  (plain path only)
+    void* act;          // [R][F]
+    float* logits;      // [R][V]
+    float* part;        // split-K partial sums
+    size_t part_floats;
+    float* attn_part;   // attention split partials
+    size_t attn_part_floats;
+    float2* rope;       // [R][hd/2] (cos, sin) of every block row's position
+    int32_t* tok;       // [R] token of every block row
+    int32_t* am_val_idx;// argmax partials: [R][chunks] (float bits, idx) pairs
+    int32_t* row_argmax;// [R]
+    int32_t* draft;     // [B][max_k]   (cs_step scratch)
+    int32_t* draft_len; // [B]
+    int32_t* match_pos; // [B]
+    int32_t* pending;   // [B]
+    int am_chunks;
+};
+
+struct cs_kv {
+    const cs_model* m;
+    int B;
+    int64_t cap;        // positions per stream (multiple of 64)
+    void* k;            // [layer][B][KVH][cap][hd]
+    void* v;            // [layer][B][KVH][hd][cap]   (token index contiguous)
+    int32_t* d_len;     // device [B]
+    int64_t* h_len_ub;  // host [B] upper bound of each length
+};
+
+// ---- kernels' host launchers (defined in the .hip files) ------------------------------
+// scan
+int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B,
+                   int gamma, int k, int policy, int64_t max_len, int32_t* d_match_pos,
+                   int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
+                   const int32_t* d_room, hipStream_t s);
+
+// elementwise / small
+int cs_embed_launch(const cs_model* m, const int32_t* tok, int R, hipStream_t s);
+int cs_rope_table_launch(const cs_model* m, const int32_t* kv_len, int B, int rows, hipStream_t s);
+// x[r] += sum of nparts partial tiles (part[p][r][:]) and, if xn_out, xn_out[r] = rmsnorm(x[r])*gain
+int cs_addnorm_launch(const cs_model* m, const float* part, int nparts,
+                      const float* gain, void* xn_out, int R, hipStream_t s);
+int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* qkv, int nparts,
+                          int rows, hipStream_t s);
+int cs_swiglu_launch(const cs_model* m, int R, hipStream_t s);
+int cs_tokens_launch(const cs_model* m, const int32_t* pending, const int32_t* draft,
+                     const int32_t* draft_len, int B, int k, hipStream_t s);
+int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k, int V,
+                            const int32_t* draft, const int32_t* draft_len, int32_t* accepted,
+                            int32_t* next_tok, int32_t* row_argmax_out, int32_t* kv_len,
+                            int32_t* hist, int64_t hist_stride, int32_t* hist_len,
+                            int32_t* room, hipStream_t s);
+
+// GEMM: Y = X * W^T.  mode 0: float32 result [R][N] written to Y (nparts_out tells how many
+// split-K partial tiles were written, each [R_stride][N]); mode 1: SwiGLU epilogue into
+// m->act (W is the interleaved gate/up matrix).
+enum { CS_GEMM_STORE = 0, CS_GEMM_SWIGLU = 1 };
+int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, int R, int N, int K,
+                   int mode, int allow_split, int* nparts_out, hipStream_t s);
+int cs_gemm_plain_launch(int dtype, const float* X, const void* W, float* Y, int R, int N, int K,
+                         hipStream_t s);
+
+// attention: reads m->q, writes m->xn (GEMM-input type) as [R][H*hd]
+int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
+                        hipStream_t s);
+
+// conversion helpers
+int cs_convert_launch(const void* src, int src_bf16, void* dst, int dst_bf16, int64_t n,
+                      hipStream_t s);
+int cs_fill_i32_launch(int32_t* p, int32_t v, int64_t n, hipStream_t s);
+
+// ---- device helpers -----------------------------------------------------------------
+__device__ __forceinline__ float cs_ld(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float cs_ld(const bf16_t* p, int64_t i) { return (float)p[i]; }
+__device__ __forceinline__ void cs_st(float* p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void cs_st(bf16_t* p, int64_t i, float v) { p[i] = (bf16_t)v; }
+
+__device__ __forceinline__ float cs_wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float cs_wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}

@@ -1,0 +1,387 @@
+// Small kernels of the verify pass: block tokens + rotary table, embedding gather,
+// residual-add + RMSNorm, rotary + KV append, SwiGLU, greedy argmax + accept rule + KV
+// length update + history append (Sec. 3.2, App. B.2, App. B.3 step 2).
+#include "cs_common.h"
+
+// -------------------------------------------------------------------------------------
+// block tokens and rotary table
+//   row r = b*(k+1) + i : token = pending[b] (i == 0) or draft[b][i-1] (i <= draft_len[b])
+//   rope[r][j] = (cos, sin)(pos * theta^(-2j/hd)),  pos = kv_len[b] + i, in float64
+// -------------------------------------------------------------------------------------
+__global__ void k_tokens(const int32_t* __restrict__ pending, const int32_t* __restrict__ draft,
+                         const int32_t* __restrict__ draft_len, int k, int V,
+                         int32_t* __restrict__ tok) {
+    const int b = blockIdx.x;
+    const int rows = k + 1;
+    for (int i = threadIdx.x; i < rows; i += blockDim.x) {
+        int t = 0;
+        if (i == 0) t = pending[b];
+        else if (i - 1 < draft_len[b]) t = draft[(int64_t)b * k + i - 1];
+        if (t < 0 || t >= V) t = 0;   // an out-of-vocabulary draft can never be accepted
+        tok[b * rows + i] = t;
+    }
+}
+
+__global__ void k_rope_table(const int32_t* __restrict__ kv_len, int rows, int half, int hd,
+                             double theta, float2* __restrict__ rope) {
+    const int r = blockIdx.x;
+    const int b = r / rows, i = r % rows;
+    const double pos = (double)(kv_len[b] + i);
+    for (int j = threadIdx.x; j < half; j += blockDim.x) {
+        const double inv = pow(theta, -2.0 * (double)j / (double)hd);
+        double sn, cs;
+        sincos(pos * inv, &sn, &cs);
+        rope[(int64_t)r * half + j] = make_float2((float)cs, (float)sn);
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// embedding gather: x[r][:] = embed[tok[r]][:]
+// -------------------------------------------------------------------------------------
+template <typename WT>
+__global__ void k_embed(const WT* __restrict__ embed, const int32_t* __restrict__ tok, int d,
+                        float* __restrict__ x) {
+    const int r = blockIdx.x;
+    const WT* __restrict__ e = embed + (int64_t)tok[r] * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) x[(int64_t)r * d + c] = cs_ld(e, c);
+}
+
+// -------------------------------------------------------------------------------------
+// x[r] += sum_p part[p][r][:]   then   xn[r] = x[r] * rsqrt(mean(x[r]^2) + eps) * gain
+// The split-K partial tiles of the preceding projection are reduced here, in a fixed
+// order, so the result does not depend on scheduling.
+// -------------------------------------------------------------------------------------
+#define NORM_THREADS 256
+#define NORM_MAXPT 32
+template <typename OutT>
+__global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
+                                                          const float* __restrict__ part,
+                                                          int nparts, int64_t part_stride, int d,
+                                                          float eps, const float* __restrict__ gain,
+                                                          OutT* __restrict__ xn) {
+    const int r = blockIdx.x;
+    float v[NORM_MAXPT];
+    float ss = 0.f;
+#pragma unroll
+    for (int u = 0; u < NORM_MAXPT; ++u) {
+        const int c = threadIdx.x + u * NORM_THREADS;
+        v[u] = 0.f;
+        if (c < d) {
+            float a = x[(int64_t)r * d + c];
+            for (int p = 0; p < nparts; ++p) a += part[p * part_stride + (int64_t)r * d + c];
+            if (nparts > 0) x[(int64_t)r * d + c] = a;
+            v[u] = a;
+            ss += a * a;
+        }
+    }
+    if (!xn) return;
+    ss = cs_wave_sum(ss);
+    __shared__ float wsum[NORM_THREADS / CS_WAVE];
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NORM_THREADS / CS_WAVE; ++w) tot += wsum[w];
+    const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int u = 0; u < NORM_MAXPT; ++u) {
+        const int c = threadIdx.x + u * NORM_THREADS;
+        if (c < d) cs_st(xn, (int64_t)r * d + c, v[u] * scale * gain[c]);
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// rotary + KV append.  qkv[r] = sum_p part[p][r][:] holds q heads, k heads, v heads.
+// q -> rotated, stored [R][H][hd] (QT); k -> rotated, rounded to the cache type, stored at
+// cache row kv_len[b]+i; v -> stored transposed (token index contiguous).
+// -------------------------------------------------------------------------------------
+template <typename WT, typename QT>
+__global__ void k_rope_append(const float* __restrict__ qkv, int nparts, int64_t part_stride,
+                              const float2* __restrict__ rope, const int32_t* __restrict__ kv_len,
+                              int rows, int H, int KVH, int hd, int64_t cap, WT* __restrict__ kc,
+                              WT* __restrict__ vc, QT* __restrict__ q) {
+    const int r = blockIdx.x;
+    const int b = r / rows, i = r % rows;
+    const int half = hd / 2;
+    const int nq = (H + 2 * KVH) * hd;
+    const int64_t pos = (int64_t)kv_len[b] + i;
+    const int npairs = (H + 2 * KVH) * half;
+    for (int t = threadIdx.x; t < npairs; t += blockDim.x) {
+        const int head = t / half, j = t % half;
+        const int64_t i0 = (int64_t)r * nq + (int64_t)head * hd + j;
+        float a = 0.f, c = 0.f;
+        for (int p = 0; p < nparts; ++p) {
+            a += qkv[p * part_stride + i0];
+            c += qkv[p * part_stride + i0 + half];
+        }
+        if (head < H + KVH) {
+            const float2 cs = rope[(int64_t)r * half + j];
+            const float ra = a * cs.x - c * cs.y;
+            const float rc = c * cs.x + a * cs.y;
+            a = ra; c = rc;
+        }
+        if (head < H) {
+            cs_st(q, ((int64_t)r * H + head) * hd + j, a);
+            cs_st(q, ((int64_t)r * H + head) * hd + j + half, c);
+        } else if (head < H + KVH) {
+            const int g = head - H;
+            WT* __restrict__ row = kc + (((int64_t)b * KVH + g) * cap + pos) * hd;
+            cs_st(row, j, a);
+            cs_st(row, j + half, c);
+        } else {
+            const int g = head - H - KVH;
+            WT* __restrict__ base = vc + ((int64_t)b * KVH + g) * hd * cap;
+            cs_st(base, (int64_t)j * cap + pos, a);
+            cs_st(base, (int64_t)(j + half) * cap + pos, c);
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// SwiGLU on the interleaved gate/up projection (plain path): row layout of gu matches the
+// packed weight: index (f/16)*32 + 16*u + f%16.
+// -------------------------------------------------------------------------------------
+template <typename AT>
+__global__ void k_swiglu(const float* __restrict__ gu, int F, AT* __restrict__ act) {
+    const int r = blockIdx.y;
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= F) return;
+    const int64_t base = (int64_t)r * 2 * F + (f / 16) * 32 + (f % 16);
+    const float g = gu[base], u = gu[base + 16];
+    cs_st(act, (int64_t)r * F + f, g / (1.0f + expf(-g)) * u);
+}
+
+// -------------------------------------------------------------------------------------
+// greedy argmax (lowest index on ties) in two stages + accept rule + state update
+// -------------------------------------------------------------------------------------
+#define AM_THREADS 256
+__device__ __forceinline__ void am_take(float& bv, int& bi, float v, int i) {
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+__global__ __launch_bounds__(AM_THREADS) void k_argmax_partial(const float* __restrict__ logits,
+                                                               int V, int Vc, int vec_ok,
+                                                               int32_t* __restrict__ out) {
+    const int r = blockIdx.y, c = blockIdx.x, nch = gridDim.x;
+    const float* __restrict__ row = logits + (int64_t)r * V;
+    const int lo = c * Vc, hi = min(V, lo + Vc);
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    if (vec_ok) {
+        for (int i = lo + (int)threadIdx.x * 4; i < hi; i += AM_THREADS * 4) {
+            if (i + 3 < hi) {
+                const float4 v = *reinterpret_cast<const float4*>(row + i);
+                if (v.x > bv) { bv = v.x; bi = i; }
+                if (v.y > bv) { bv = v.y; bi = i + 1; }
+                if (v.z > bv) { bv = v.z; bi = i + 2; }
+                if (v.w > bv) { bv = v.w; bi = i + 3; }
+            } else {
+                for (int u = i; u < hi; ++u)
+                    if (row[u] > bv) { bv = row[u]; bi = u; }
+            }
+        }
+    } else {
+        for (int i = lo + (int)threadIdx.x; i < hi; i += AM_THREADS)
+            if (row[i] > bv) { bv = row[i]; bi = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        am_take(bv, bi, ov, oi);
+    }
+    __shared__ float sv[AM_THREADS / CS_WAVE];
+    __shared__ int si[AM_THREADS / CS_WAVE];
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < AM_THREADS / CS_WAVE; ++w) am_take(bv, bi, sv[w], si[w]);
+        out[((int64_t)r * nch + c) * 2] = __float_as_int(bv);
+        out[((int64_t)r * nch + c) * 2 + 1] = bi;
+    }
+}
+
+// One wave per stream.  a_i = argmax of row i; tau = leading agreement with the draft;
+// next = a_tau; the KV length grows by tau+1 (App. B.2: truncation past the accepted rows);
+// the accepted drafts and the free token are appended to the history (App. B.3 step 2d).
+__global__ __launch_bounds__(64) void k_accept(const int32_t* __restrict__ part, int nch, int k,
+                                               const int32_t* __restrict__ draft,
+                                               const int32_t* __restrict__ draft_len,
+                                               int32_t* __restrict__ accepted,
+                                               int32_t* __restrict__ next_tok,
+                                               int32_t* __restrict__ row_argmax,
+                                               int32_t* __restrict__ row_argmax_out,
+                                               int32_t* __restrict__ kv_len,
+                                               int32_t* __restrict__ hist, int64_t hist_stride,
+                                               int32_t* __restrict__ hist_len,
+                                               int32_t* __restrict__ room) {
+    const int b = blockIdx.x;
+    const int rows = k + 1;
+    const int lane = threadIdx.x;
+    for (int i = 0; i < rows; ++i) {
+        const int r = b * rows + i;
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int c = lane; c < nch; c += 64)
+            am_take(bv, bi, __int_as_float(part[((int64_t)r * nch + c) * 2]),
+                    part[((int64_t)r * nch + c) * 2 + 1]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            am_take(bv, bi, ov, oi);
+        }
+        if (lane == 0) {
+            if (bi == 0x7fffffff) bi = 0;
+            row_argmax[r] = bi;
+            if (row_argmax_out) row_argmax_out[r] = bi;
+        }
+    }
+    __syncthreads();
+    if (lane == 0) {
+        const int m = min(draft_len[b], k);
+        int tau = 0;
+        while (tau < m && row_argmax[b * rows + tau] == draft[(int64_t)b * k + tau]) ++tau;
+        const int nxt = row_argmax[b * rows + tau];
+        accepted[b] = tau;
+        next_tok[b] = nxt;
+        if (kv_len) kv_len[b] += tau + 1;
+        if (hist) {
+            const int n = hist_len[b];
+            int32_t* __restrict__ h = hist + (int64_t)b * hist_stride;
+            for (int i = 0; i < tau; ++i) h[n + i] = draft[(int64_t)b * k + i];
+            h[n + tau] = nxt;
+            hist_len[b] = n + tau + 1;
+            if (room) room[b] -= tau + 1;
+        }
+    }
+}
+
+template <typename S, typename D>
+__global__ void k_convert(const S* __restrict__ src, D* __restrict__ dst, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        cs_st(dst, i, cs_ld(src, i));
+}
+
+__global__ void k_fill_i32(int32_t* p, int32_t v, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// -------------------------------------------------------------------------------------
+// host launchers
+// -------------------------------------------------------------------------------------
+int cs_tokens_launch(const cs_model* m, const int32_t* pending, const int32_t* draft,
+                     const int32_t* draft_len, int B, int k, hipStream_t s) {
+    k_tokens<<<B, 64, 0, s>>>(pending, draft, draft_len, k, m->cfg.vocab, m->tok);
+    return cs_launch_ok("k_tokens");
+}
+
+int cs_rope_table_launch(const cs_model* m, const int32_t* kv_len, int B, int rows, hipStream_t s) {
+    k_rope_table<<<B * rows, 64, 0, s>>>(kv_len, rows, m->cfg.head_dim / 2, m->cfg.head_dim,
+                                         (double)m->cfg.rope_theta, m->rope);
+    return cs_launch_ok("k_rope_table");
+}
+
+int cs_embed_launch(const cs_model* m, const int32_t* tok, int R, hipStream_t s) {
+    if (m->cfg.dtype == CS_BF16)
+        k_embed<bf16_t><<<R, 256, 0, s>>>((const bf16_t*)m->embed, tok, m->cfg.d_model, m->x);
+    else
+        k_embed<float><<<R, 256, 0, s>>>((const float*)m->embed, tok, m->cfg.d_model, m->x);
+    return cs_launch_ok("k_embed");
+}
+
+int cs_addnorm_launch(const cs_model* m, const float* part, int nparts,
+                      const float* gain, void* xn_out, int R, hipStream_t s) {
+    const int d = m->cfg.d_model;
+    const int64_t ps = (int64_t)R * d;
+    if (xn_out && m->fast)
+        k_addnorm<bf16_t><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
+                                                     (bf16_t*)xn_out);
+    else
+        k_addnorm<float><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
+                                                    (float*)xn_out);
+    return cs_launch_ok("k_addnorm");
+}
+
+int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* qkv, int nparts,
+                          int rows, hipStream_t s) {
+    const cs_model_cfg& c = m->cfg;
+    const int R = kv->B * rows;
+    const int64_t per_layer = (int64_t)kv->B * c.n_kv_heads * kv->cap * c.head_dim;
+    const int64_t ps = (int64_t)R * (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const float2* rope = m->rope;
+    if (c.dtype == CS_BF16) {
+        bf16_t* kc = (bf16_t*)kv->k + layer * per_layer;
+        bf16_t* vc = (bf16_t*)kv->v + layer * per_layer;
+        if (m->fast)
+            k_rope_append<bf16_t, bf16_t><<<R, 256, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
+                                                           c.n_heads, c.n_kv_heads, c.head_dim,
+                                                           kv->cap, kc, vc, (bf16_t*)m->q);
+        else
+            k_rope_append<bf16_t, float><<<R, 256, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
+                                                          c.n_heads, c.n_kv_heads, c.head_dim,
+                                                          kv->cap, kc, vc, (float*)m->q);
+    } else {
+        float* kc = (float*)kv->k + layer * per_layer;
+        float* vc = (float*)kv->v + layer * per_layer;
+        k_rope_append<float, float><<<R, 256, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
+                                                     c.n_heads, c.n_kv_heads, c.head_dim, kv->cap,
+                                                     kc, vc, (float*)m->q);
+    }
+    return cs_launch_ok("k_rope_append");
+}
+
+int cs_swiglu_launch(const cs_model* m, int R, hipStream_t s) {
+    const int F = m->cfg.d_ff;
+    dim3 grid((unsigned)cs_ceil_div(F, 256), R);
+    if (m->fast) k_swiglu<bf16_t><<<grid, 256, 0, s>>>(m->gu, F, (bf16_t*)m->act);
+    else k_swiglu<float><<<grid, 256, 0, s>>>(m->gu, F, (float*)m->act);
+    return cs_launch_ok("k_swiglu");
+}
+
+int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k, int V,
+                            const int32_t* draft, const int32_t* draft_len, int32_t* accepted,
+                            int32_t* next_tok, int32_t* row_argmax_out, int32_t* kv_len,
+                            int32_t* hist, int64_t hist_stride, int32_t* hist_len,
+                            int32_t* room, hipStream_t s) {
+    const int R = B * (k + 1);
+    int nch = (int)cs_ceil_div(V, 16384);
+    if (nch < 1) nch = 1;
+    if (nch > m->am_chunks) nch = m->am_chunks;
+    const int Vc = (int)cs_round_up(cs_ceil_div(V, nch), 4);
+    nch = (int)cs_ceil_div(V, Vc);
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(logits) & 15) == 0) && (V % 4 == 0);
+    dim3 grid(nch, R);
+    k_argmax_partial<<<grid, AM_THREADS, 0, s>>>(logits, V, Vc, vec_ok, m->am_val_idx);
+    CS_TRY(cs_launch_ok("k_argmax_partial"));
+    k_accept<<<B, 64, 0, s>>>(m->am_val_idx, nch, k, draft, draft_len, accepted, next_tok,
+                              m->row_argmax, row_argmax_out, kv_len, hist, hist_stride, hist_len,
+                              room);
+    return cs_launch_ok("k_accept");
+}
+
+int cs_convert_launch(const void* src, int src_bf16, void* dst, int dst_bf16, int64_t n,
+                      hipStream_t s) {
+    if (n <= 0) return CS_OK;
+    const int blocks = (int)(cs_ceil_div(n, 256) < 4096 ? cs_ceil_div(n, 256) : 4096);
+    if (src_bf16 && !dst_bf16)
+        k_convert<bf16_t, float><<<blocks, 256, 0, s>>>((const bf16_t*)src, (float*)dst, n);
+    else if (!src_bf16 && dst_bf16)
+        k_convert<float, bf16_t><<<blocks, 256, 0, s>>>((const float*)src, (bf16_t*)dst, n);
+    else if (src_bf16)
+        k_convert<bf16_t, bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)src, (bf16_t*)dst, n);
+    else
+        k_convert<float, float><<<blocks, 256, 0, s>>>((const float*)src, (float*)dst, n);
+    return cs_launch_ok("k_convert");
+}
+
+int cs_fill_i32_launch(int32_t* p, int32_t v, int64_t n, hipStream_t s) {
+    if (n <= 0) return CS_OK;
+    const int blocks = (int)(cs_ceil_div(n, 256) < 1024 ? cs_ceil_div(n, 256) : 1024);
+    k_fill_i32<<<blocks, 256, 0, s>>>(p, v, n);
+    return cs_launch_ok("k_fill_i32");
+}

@@ -1,0 +1,143 @@
+// gamma-gram match scan and draft gather (Sec. 3.1-3.2, App. B.1, App. B.3 step 1).
+//
+// The paper keeps a hash map of all gamma-grams; on a GPU a linear scan of the int32
+// history returns the same position at 4 bytes per token, streamed once.  The scan is
+// HBM-bound: every thread loads 16 bytes (4 tokens) per step, compares them with the first
+// token of the query suffix, and only on a hit (rare for real vocabularies) checks the
+// other gamma-1 tokens.  Each workgroup reduces its chunk to one position; a second tiny
+// kernel reduces the chunks of a stream, applies the policy and copies the draft.
+#include "cs_common.h"
+
+#define SCAN_THREADS 256
+#define SCAN_CHUNK 4096   // candidate positions per workgroup
+
+__device__ __forceinline__ bool rest_matches(const int32_t* __restrict__ h, int p, int n, int gamma) {
+    for (int j = 1; j < gamma; ++j)
+        if (h[p + j] != h[n - gamma + j]) return false;
+    return true;
+}
+
+// chunk_best[b][c] = best candidate in chunk c (max for rightmost, min for first), -1 if none
+template <int POLICY>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict__ hist,
+                                                       int64_t stride,
+                                                       const int32_t* __restrict__ len, int gamma,
+                                                       int vec_ok, int32_t* __restrict__ chunk_best,
+                                                       int nchunks) {
+    const int b = blockIdx.y;
+    const int c = blockIdx.x;
+    const int n = len[b];
+    const int32_t* __restrict__ h = hist + (int64_t)b * stride;
+    const int cnt = n - 2 * gamma + 1;            // candidate starts are 0 .. cnt-1
+    const int begin = c * SCAN_CHUNK;
+    const int NONE = POLICY == CS_POLICY_RIGHTMOST ? -1 : 0x7fffffff;
+    int best = NONE;
+    if (begin < cnt) {
+        const int end = min(cnt, begin + SCAN_CHUNK);
+        const int s0 = h[n - gamma];
+        for (int p = begin + (int)threadIdx.x * 4; p < end; p += SCAN_THREADS * 4) {
+            int t[4];
+            if (vec_ok && p + 3 < n) {
+                const int4 v = *reinterpret_cast<const int4*>(h + p);
+                t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] = (p + i < n) ? h[p + i] : ~s0;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int pp = p + i;
+                if (pp < end && t[i] == s0 && rest_matches(h, pp, n, gamma)) {
+                    if (POLICY == CS_POLICY_RIGHTMOST) best = max(best, pp);
+                    else best = min(best, pp);
+                }
+            }
+        }
+    }
+    // workgroup reduction: wave shuffle, then LDS across the 4 waves
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const int other = __shfl_xor(best, o, 64);
+        best = POLICY == CS_POLICY_RIGHTMOST ? max(best, other) : min(best, other);
+    }
+    __shared__ int wave_best[SCAN_THREADS / CS_WAVE];
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int r = wave_best[0];
+#pragma unroll
+        for (int w = 1; w < SCAN_THREADS / CS_WAVE; ++w)
+            r = POLICY == CS_POLICY_RIGHTMOST ? max(r, wave_best[w]) : min(r, wave_best[w]);
+        if (r == NONE) r = -1;
+        chunk_best[(int64_t)b * nchunks + c] = r;
+    }
+}
+
+// One wave per stream: reduce the chunk results, then copy the draft (App. B.1 "Chunk").
+__global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist, int64_t stride,
+                                               const int32_t* __restrict__ len, int gamma, int k,
+                                               int policy, const int32_t* __restrict__ chunk_best,
+                                               int nchunks, const int32_t* __restrict__ room,
+                                               int32_t* __restrict__ match_pos,
+                                               int32_t* __restrict__ src_pos,
+                                               int32_t* __restrict__ draft,
+                                               int32_t* __restrict__ draft_len) {
+    const int b = blockIdx.x;
+    const int n = len[b];
+    const int32_t* __restrict__ h = hist + (int64_t)b * stride;
+    int best = -1;
+    for (int c = threadIdx.x; c < nchunks; c += 64) {
+        const int v = chunk_best[(int64_t)b * nchunks + c];
+        if (v >= 0) {
+            if (policy == CS_POLICY_RIGHTMOST) best = max(best, v);
+            else best = best < 0 ? v : min(best, v);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const int other = __shfl_xor(best, o, 64);
+        if (policy == CS_POLICY_RIGHTMOST) best = max(best, other);
+        else best = best < 0 ? other : (other < 0 ? best : min(best, other));
+    }
+    const int src = best < 0 ? -1 : best + gamma;
+    int dl = best < 0 ? 0 : min(k, n - src);
+    if (room) dl = min(dl, max(room[b] - 1, 0));   // never draft past the emission budget
+    if (threadIdx.x == 0) {
+        if (match_pos) match_pos[b] = best;
+        if (src_pos) src_pos[b] = src;
+        draft_len[b] = dl;
+    }
+    for (int i = threadIdx.x; i < k; i += 64) draft[(int64_t)b * k + i] = i < dl ? h[src + i] : -1;
+}
+
+// library-owned scratch for the per-chunk results; grown on demand (synchronises then)
+static int32_t* g_chunk_best = nullptr;
+static size_t g_chunk_best_n = 0;
+
+int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B, int gamma,
+                   int k, int policy, int64_t max_len, int32_t* d_match_pos, int32_t* d_src_pos,
+                   int32_t* d_draft, int32_t* d_draft_len, const int32_t* d_room, hipStream_t s) {
+    if (B == 0) return CS_OK;
+    const int nchunks = (int)cs_ceil_div(max_len > 0 ? max_len : 1, SCAN_CHUNK);
+    const size_t need = (size_t)B * nchunks;
+    if (need > g_chunk_best_n) {
+        CS_HIP(hipDeviceSynchronize());
+        if (g_chunk_best) CS_HIP(hipFree(g_chunk_best));
+        g_chunk_best = nullptr;
+        g_chunk_best_n = 0;
+        CS_HIP(hipMalloc(&g_chunk_best, need * sizeof(int32_t)));
+        g_chunk_best_n = need;
+    }
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(d_hist) & 15) == 0) && (stride % 4 == 0);
+    dim3 grid(nchunks, B);
+    if (policy == CS_POLICY_RIGHTMOST)
+        k_scan<CS_POLICY_RIGHTMOST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
+                                                                 g_chunk_best, nchunks);
+    else
+        k_scan<CS_POLICY_FIRST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
+                                                             g_chunk_best, nchunks);
+    CS_TRY(cs_launch_ok("k_scan"));
+    k_gather<<<B, 64, 0, s>>>(d_hist, stride, d_len, gamma, k, policy, g_chunk_best, nchunks, d_room,
+                              d_match_pos, d_src_pos, d_draft, d_draft_len);
+    return cs_launch_ok("k_gather");
+}
