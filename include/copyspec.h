@@ -236,6 +236,31 @@ int cs_op_argmax_accept(cs_model* m, const float* logits, int32_t B, int32_t k, 
                         const int32_t* draft, const int32_t* draft_len, int32_t* accepted_len,
                         int32_t* next_token, int32_t* row_argmax, void* stream);
 
+/* Asynchronous variant of cs_kv_set_len for all streams at once: lengths are copied from
+ * the device array d_len[B] on `stream`; len_upper_bound (host) must be >= every one of
+ * them and <= capacity.  Lets a benchmark or a serving loop rewind the cache without a
+ * host round trip. */
+int cs_kv_set_len_dev(cs_kv*, const int32_t* d_len /*device [B]*/, int64_t len_upper_bound,
+                      void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Instrumentation: per-kernel-class device timing with HIP events recorded on the stream
+ * the kernels run on.  cs_profile_enable(mask) selects classes (0 = off, the default);
+ * cs_profile_read synchronises the device and returns the summed duration and the number
+ * of launches of one class since the last cs_profile_reset.
+ * ---------------------------------------------------------------------------------- */
+enum {
+    CS_PROF_SCAN = 1,      /* match scan kernel */
+    CS_PROF_GEMM = 2,      /* every projection GEMM */
+    CS_PROF_ATTN = 4,      /* block attention kernel (without the split merge) */
+    CS_PROF_ATTN_MERGE = 8,
+    CS_PROF_ARGMAX = 16,   /* vocabulary argmax kernel */
+    CS_PROF_LMHEAD = 32    /* the lm_head GEMM alone */
+};
+void cs_profile_enable(int32_t class_mask);
+void cs_profile_reset(void);
+int cs_profile_read(int32_t cls, double* total_ms, int64_t* launches);
+
 /* Select kernel variants for the following cs_model_create calls: 0 = tuned kernels where
  * the shape allows (default), 1 = plain reference kernels everywhere. */
 void cs_set_plain_kernels(int32_t on);

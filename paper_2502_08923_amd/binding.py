@@ -26,8 +26,11 @@ EXPORTS = [
     "cs_model_create", "cs_model_destroy", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
     "cs_decode_greedy", "cs_prefill", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
-    "cs_set_plain_kernels",
+    "cs_set_plain_kernels", "cs_kv_set_len_dev", "cs_profile_enable", "cs_profile_reset",
+    "cs_profile_read",
 ]
+
+CS_PROF = {"scan": 1, "gemm": 2, "attn": 4, "attn_merge": 8, "argmax": 16, "lm_head": 32}
 
 
 class CopySpecError(RuntimeError):
@@ -97,6 +100,11 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_op_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp]
     lib.cs_op_attention.argtypes = [vp, vp, i32, vp, i32, vp, vp]
     lib.cs_op_argmax_accept.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.cs_kv_set_len_dev.argtypes = [vp, vp, i64, vp]
+    lib.cs_profile_enable.argtypes = [i32]
+    lib.cs_profile_enable.restype = None
+    lib.cs_profile_reset.restype = None
+    lib.cs_profile_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.cs_set_plain_kernels.argtypes = [i32]
     lib.cs_set_plain_kernels.restype = None
     for name in EXPORTS:
@@ -262,6 +270,11 @@ class KV:
             _check(int(r))
         return int(r)
 
+    def set_len_dev(self, d_len: torch.Tensor, upper_bound: int, stream=None):
+        _dev_i32(d_len, "d_len")
+        _check(load_library().cs_kv_set_len_dev(self.handle, d_len.data_ptr(), upper_bound,
+                                                _stream(stream)))
+
     def load(self, layer: int, stream_idx: int, pos0: int, k_rows, v_rows):
         bf16 = self.model.dtype == CS_BF16
         k = _to_dev(k_rows, bf16, self.model.device)
@@ -401,3 +414,25 @@ def cs_op_argmax_accept(model: Model, logits: torch.Tensor, draft: torch.Tensor,
                                               draft_len.data_ptr(), acc.data_ptr(), nxt.data_ptr(),
                                               am.data_ptr(), _stream(stream)))
     return acc, nxt, am
+
+
+# ----------------------------------------------------------------------------------------
+# instrumentation
+# ----------------------------------------------------------------------------------------
+
+def cs_profile_enable(classes: Sequence[str] = ()):
+    mask = 0
+    for c in classes:
+        mask |= CS_PROF[c]
+    load_library().cs_profile_enable(mask)
+
+
+def cs_profile_reset():
+    load_library().cs_profile_reset()
+
+
+def cs_profile_read(cls: str):
+    """Returns (total_ms, launches) of one kernel class since the last reset."""
+    ms, n = C.c_double(), C.c_int64()
+    _check(load_library().cs_profile_read(CS_PROF[cls], C.byref(ms), C.byref(n)))
+    return ms.value, n.value

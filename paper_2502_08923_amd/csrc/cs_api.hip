@@ -26,6 +26,55 @@ static int g_plain = 0;
 extern "C" void cs_set_plain_kernels(int32_t on) { g_plain = on ? 1 : 0; }
 
 // -------------------------------------------------------------------------------------
+// instrumentation
+// -------------------------------------------------------------------------------------
+struct prof_slot { int cls; hipEvent_t a, b; };
+static std::vector<prof_slot> g_prof;
+static size_t g_prof_used = 0;
+static int g_prof_mask = 0;
+
+int cs_prof_begin(int cls, hipStream_t s) {
+    if (!(g_prof_mask & cls)) return -1;
+    if (g_prof_used == g_prof.size()) {
+        if (g_prof.size() >= 200000) return -1;
+        prof_slot ps;
+        ps.cls = cls;
+        if (hipEventCreate(&ps.a) != hipSuccess || hipEventCreate(&ps.b) != hipSuccess) return -1;
+        g_prof.push_back(ps);
+    }
+    prof_slot& ps = g_prof[g_prof_used];
+    ps.cls = cls;
+    (void)hipEventRecord(ps.a, s);
+    return (int)g_prof_used++;
+}
+
+void cs_prof_end(int slot, hipStream_t s) {
+    if (slot >= 0) (void)hipEventRecord(g_prof[slot].b, s);
+}
+
+extern "C" void cs_profile_enable(int32_t mask) { g_prof_mask = mask; }
+extern "C" void cs_profile_reset(void) {
+    (void)hipDeviceSynchronize();
+    g_prof_used = 0;
+}
+extern "C" int cs_profile_read(int32_t cls, double* total_ms, int64_t* launches) {
+    CS_REQUIRE(total_ms && launches, CS_E_ARG, "cs_profile_read: NULL output");
+    CS_HIP(hipDeviceSynchronize());
+    double tot = 0.0;
+    int64_t n = 0;
+    for (size_t i = 0; i < g_prof_used; ++i) {
+        if (g_prof[i].cls != cls) continue;
+        float ms = 0.f;
+        CS_HIP(hipEventElapsedTime(&ms, g_prof[i].a, g_prof[i].b));
+        tot += ms;
+        ++n;
+    }
+    *total_ms = tot;
+    *launches = n;
+    return CS_OK;
+}
+
+// -------------------------------------------------------------------------------------
 // small kernels used only here
 // -------------------------------------------------------------------------------------
 // interleave gate and up rows in blocks of 16: dst row (f/16)*32 + 16*u + f%16
@@ -269,6 +318,16 @@ extern "C" int cs_kv_set_len(cs_kv* kv, int32_t b, int64_t len) {
     return CS_OK;
 }
 
+extern "C" int cs_kv_set_len_dev(cs_kv* kv, const int32_t* d_len, int64_t ub, void* stream) {
+    CS_REQUIRE(kv && d_len, CS_E_ARG, "cs_kv_set_len_dev: NULL argument");
+    CS_REQUIRE(ub >= 0 && ub <= kv->cap, CS_E_CAPACITY, "cs_kv_set_len_dev: bound %lld > capacity",
+               (long long)ub);
+    CS_HIP(hipMemcpyAsync(kv->d_len, d_len, (size_t)kv->B * 4, hipMemcpyDeviceToDevice,
+                          (hipStream_t)stream));
+    for (int b = 0; b < kv->B; ++b) kv->h_len_ub[b] = ub;
+    return CS_OK;
+}
+
 static int kv_sync_lengths(cs_kv* kv) {
     std::vector<int32_t> h(kv->B);
     CS_HIP(hipDeviceSynchronize());
@@ -457,8 +516,10 @@ static int verify_impl(cs_model* m, cs_kv* kv, const int32_t* d_pending, const i
     CS_TRY(kv_check_room(kv, rows));
     CS_TRY(cs_tokens_launch(m, d_pending, d_draft, d_draft_len, B, k, s));
     CS_TRY(forward_layers(m, kv, rows, s));
+    const int pl = cs_prof_begin(CS_PROF_LMHEAD, s);
     CS_TRY(cs_gemm_launch(m, m->xn, m->lm_head, m->logits, R, V, m->cfg.d_model, CS_GEMM_STORE, 0,
                           nullptr, s));
+    cs_prof_end(pl, s);
     CS_TRY(cs_argmax_accept_launch(m, m->logits, B, k, V, d_draft, d_draft_len, d_accepted, d_next,
                                    nullptr, kv->d_len, hist, hist_stride, hist_len, room, s));
     if (d_logits_out)

@@ -348,15 +348,19 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const bf16_t* kc = (const bf16_t*)kv->k + layer * per_layer;
     const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
     dim3 grid(nsplit * nqg, KVH, B);
+    const int pa = cs_prof_begin(CS_PROF_ATTN, s);
     if (hd == 128)
         k_attn_mfma<128><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
                                               kv->cap, Tw, nqg, nwaves, po, pml);
     else
         k_attn_mfma<64><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
                                              kv->cap, Tw, nqg, nwaves, po, pml);
+    cs_prof_end(pa, s);
     CS_TRY(cs_launch_ok("k_attn_mfma"));
     dim3 mgrid(QR, KVH, B);
+    const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
     k_attn_merge<bf16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, kv->d_len, rows, H, KVH, hd, Tw,
                                                            nqg, nwaves, (bf16_t*)m->xn);
+    cs_prof_end(pm, s);
     return cs_launch_ok("k_attn_merge");
 }

@@ -54,6 +54,10 @@ static inline int cs_launch_ok(const char* what) {
 static inline int64_t cs_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t cs_round_up(int64_t a, int64_t b) { return cs_ceil_div(a, b) * b; }
 
+// ---- event timing of kernel classes (no-ops unless enabled) ----------------------------
+int cs_prof_begin(int cls, hipStream_t s);          // returns a slot index or -1
+void cs_prof_end(int slot, hipStream_t s);
+
 // ---- handles ------------------------------------------------------------------------
 struct cs_layer_dev {
     void* wqkv;    // [(H+2KVH)*hd][d]   rows: q heads, k heads, v heads

@@ -356,7 +356,9 @@ int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k
     nch = (int)cs_ceil_div(V, Vc);
     const int vec_ok = ((reinterpret_cast<uintptr_t>(logits) & 15) == 0) && (V % 4 == 0);
     dim3 grid(nch, R);
+    const int pa = cs_prof_begin(CS_PROF_ARGMAX, s);
     k_argmax_partial<<<grid, AM_THREADS, 0, s>>>(logits, V, Vc, vec_ok, m->am_val_idx);
+    cs_prof_end(pa, s);
     CS_TRY(cs_launch_ok("k_argmax_partial"));
     k_accept<<<B, 64, 0, s>>>(m->am_val_idx, nch, k, draft, draft_len, accepted, next_tok,
                               m->row_argmax, row_argmax_out, kv_len, hist, hist_stride, hist_len,

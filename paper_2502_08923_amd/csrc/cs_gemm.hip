@@ -186,10 +186,12 @@ static int launch_mfma(const bf16_t* X, const bf16_t* W, float* Y, bf16_t* act, 
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     dim3 grid((unsigned)cs_ceil_div(N, 64 * MT), (unsigned)cs_ceil_div(K, Ks),
               (unsigned)cs_ceil_div(R, 16 * NT));
+    const int pg = cs_prof_begin(CS_PROF_GEMM, s);
     if (mode == CS_GEMM_STORE)
         k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, 256, 0, s>>>(X, W, Y, act, R, N, K, Ks);
     else
         k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, 256, 0, s>>>(X, W, Y, act, R, N, K, Ks);
+    cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_mfma");
 }
 

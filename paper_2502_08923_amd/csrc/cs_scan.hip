@@ -130,12 +130,14 @@ int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, 
     }
     const int vec_ok = ((reinterpret_cast<uintptr_t>(d_hist) & 15) == 0) && (stride % 4 == 0);
     dim3 grid(nchunks, B);
+    const int ps = cs_prof_begin(CS_PROF_SCAN, s);
     if (policy == CS_POLICY_RIGHTMOST)
         k_scan<CS_POLICY_RIGHTMOST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
                                                                  g_chunk_best, nchunks);
     else
         k_scan<CS_POLICY_FIRST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
                                                              g_chunk_best, nchunks);
+    cs_prof_end(ps, s);
     CS_TRY(cs_launch_ok("k_scan"));
     k_gather<<<B, 64, 0, s>>>(d_hist, stride, d_len, gamma, k, policy, g_chunk_best, nchunks, d_room,
                               d_match_pos, d_src_pos, d_draft, d_draft_len);
