@@ -155,41 +155,44 @@ def bench_scan(cs, torch, synth, log):
 
 
 def cpu_baseline(st, args):
-    """The CPU oracle timed on a bounded sample of the same workload: one of the B streams,
-    `cpu_layers` decoder layers at full width and full context, the scan, the lm_head, the
-    argmax and the accept rule; the layer time is scaled to the full depth and the stream
-    time to the full batch."""
-    import numpy as np
+    """The CPU oracle timed on a bounded sample of the same workload: `cpu_streams` of the B
+    streams, `cpu_layers` decoder layers at full width and full context, plus the scan, the
+    lm_head, the argmax and the accept rule; the layer time is scaled to the full depth and
+    the stream time to the full batch."""
     import synth
     from oracle import copyspec_oracle as orc
     sh = st["shape"]
-    nl = args.cpu_layers
+    nl, ns = min(args.cpu_layers, sh.n_layers), min(args.cpu_streams, st["B"])
     sub = sh.with_layers(nl)
     w = synth.model_weights(sub, synth.seed_for(4), threads=8)
     L, k = st["L"], st["k"]
-    okv = orc.KVCache(sub, L + k + 1)
-    for layer in range(nl):
-        kr, vr = synth.random_kv(sub, L, synth.seed_for(4), layer, 0)
-        okv.load(layer, kr, vr)
-    okv.truncate(L)
-    h = st["hists"][0]
-    t0 = time.perf_counter()
-    _, _, draft = orc.find_match_np(h, st["gamma"], k)
-    t_scan = time.perf_counter() - t0
-    # layers (return_hidden skips the lm_head) and lm_head timed separately
-    t0 = time.perf_counter()
-    hidden = orc.forward_block(w, okv, [int(h[-1])] + draft, return_hidden=True)
-    t_layers = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    logits = hidden @ orc._f64(w["lm_head"]).T
-    am = [orc.argmax_first(r) for r in logits]
-    orc.accept_prefix(am, draft)
-    t_head = time.perf_counter() - t0
-    t_stream = t_scan + t_layers / nl * sh.n_layers + t_head
+    t_scan = t_layers = t_head = 0.0
+    for b in range(ns):
+        okv = orc.KVCache(sub, L + k + 1)
+        for layer in range(nl):
+            kr, vr = synth.random_kv(sub, L, synth.seed_for(4), layer, b)
+            okv.load(layer, kr, vr)
+        okv.truncate(L)
+        h = st["hists"][b]
+        t0 = time.perf_counter()
+        _, _, draft = orc.find_match_np(h, st["gamma"], k)
+        t_scan += time.perf_counter() - t0
+        # layers (return_hidden skips the lm_head) and lm_head timed separately
+        t0 = time.perf_counter()
+        hidden = orc.forward_block(w, okv, [int(h[-1])] + draft, return_hidden=True)
+        t_layers += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        logits = hidden @ orc._f64(w["lm_head"]).T
+        am = [orc.argmax_first(r) for r in logits]
+        orc.accept_prefix(am, draft)
+        t_head += time.perf_counter() - t0
+        del okv
+    t_stream = (t_scan + t_layers / nl * sh.n_layers + t_head) / ns
     t_step = t_stream * st["B"]
-    return {"value": st["B"] * k / t_step, "unit": "tokens/s", "cores": int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count()),
+    return {"value": st["B"] * k / t_step, "unit": "tokens/s",
+            "cores": int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count()),
             "kind": "oracle",
-            "sample": f"1 of {st['B']} streams, {nl} of {sh.n_layers} layers + lm_head + scan at "
+            "sample": f"{ns} of {st['B']} streams, {nl} of {sh.n_layers} layers + lm_head + scan at "
                       f"full width and context (L={L}); measured {t_scan + t_layers + t_head:.1f}s "
                       f"(scan {t_scan * 1e3:.1f} ms, layers {t_layers:.1f}s, head {t_head:.1f}s), "
                       f"scaled to {sh.n_layers} layers x {st['B']} streams"}
@@ -207,7 +210,8 @@ def main():
     ap.add_argument("--gamma", type=int, default=3)
     ap.add_argument("--doc", type=int, default=2048)
     ap.add_argument("--hist", type=int, default=16384)
-    ap.add_argument("--cpu-layers", type=int, default=1)
+    ap.add_argument("--cpu-layers", type=int, default=16)
+    ap.add_argument("--cpu-streams", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-scan", action="store_true")
     args = ap.parse_args()

@@ -234,7 +234,8 @@ extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_
     CS_REQUIRE(c.head_dim % 2 == 0 && c.head_dim <= 256 && 256 % c.head_dim == 0, CS_E_UNSUPPORTED,
                "head_dim must be a power of two in 2..256");
     CS_REQUIRE(c.d_ff % 16 == 0, CS_E_UNSUPPORTED, "d_ff must be a multiple of 16");
-    CS_REQUIRE(c.d_model <= 8192, CS_E_UNSUPPORTED, "d_model must be <= 8192");
+    CS_REQUIRE(c.d_model <= 8192 && c.d_model % 4 == 0, CS_E_UNSUPPORTED,
+               "d_model must be a multiple of 4 and <= 8192");
     CS_REQUIRE(c.max_batch >= 1 && c.max_k >= 0 && c.max_k <= 256, CS_E_ARG,
                "max_batch >= 1 and 0 <= max_k <= 256 required");
     cs_model* m = (cs_model*)calloc(1, sizeof(cs_model));

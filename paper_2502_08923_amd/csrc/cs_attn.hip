@@ -18,6 +18,8 @@
 // four lanes that hold a query row, and O is only rescaled when some maximum moved.
 // The token range of a stream is split over waves; a merge kernel combines the partial
 // (max, sum, O) triples.
+#include <type_traits>
+
 #include "cs_common.h"
 
 // -------------------------------------------------------------------------------------
@@ -111,108 +113,133 @@ __global__ __launch_bounds__(PA_THREADS) void k_attn_plain(const QT* __restrict_
 // -------------------------------------------------------------------------------------
 #define FA_NT 3            // 16-row query tiles per wave  (48 query rows)
 #define FA_QROWS (16 * FA_NT)
+#define FA_RESCALE_LOG2 8.0f
+#define FA_OPAD 4          // LDS row padding (floats) of the in-workgroup merge buffers
 
-// Partial layout: po[item][wave][qrow][HD] float, pml[item][wave][qrow][2] = (max2, sum)
-// where item = (b*KVH + kvh)*nqg + qg and max2 is in base-2 scaled units.
+template <int HD>
+struct fa_kbuf { bf16x8 k[2][HD / 32]; };
+template <int HD>
+struct fa_vbuf { bf16x8 v[HD / 16]; };
+
+// Partial layout: po[item][split][qrow][HD] float, pml[item][split][qrow][2] = (max2, sum)
+// where item = (b*KVH + kvh)*nqg + qg, split = workgroup index along the token axis and max2
+// is the reference maximum in base-2 scaled units.  A split whose token range is empty
+// writes (max2 = -inf, 0, 0).
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                                                    const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc,
                                                    const int32_t* __restrict__ kv_len, int rows,
                                                    int H, int KVH, int64_t cap, int Tw, int nqg,
-                                                   int nwaves, float* __restrict__ po,
+                                                   int nsplit, float* __restrict__ po,
                                                    float* __restrict__ pml) {
     constexpr int KS = HD / 32;      // MFMA k-steps over the head dimension
     constexpr int MT = HD / 16;      // 16-row tiles of O^T
-    constexpr int HQ = HD / 4;       // head-dim elements per lane group
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int OROW = HD + FA_OPAD;
+    constexpr int QROW = HD * 2 + 16;                 // bytes per query row in LDS (padded)
+    constexpr int MERGE_BYTES = 2 * FA_QROWS * OROW * 4 + 2 * FA_QROWS * 2 * 4;
+    constexpr int Q_BYTES = FA_QROWS * QROW;
+    // the query tile (read during the main loop) and the merge buffers (used after it)
+    // share the same LDS
+    __shared__ __attribute__((aligned(16))) unsigned char smem[MERGE_BYTES > Q_BYTES ? MERGE_BYTES : Q_BYTES];
+    float* s_o = reinterpret_cast<float*>(smem);                          // [2][FA_QROWS*OROW]
+    float* s_ml = reinterpret_cast<float*>(smem) + 2 * FA_QROWS * OROW;   // [2][FA_QROWS*2]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
     const int qg = blockIdx.x % nqg;
-    const int wg = (blockIdx.x / nqg) * 4 + wave;       // wave index along the token axis
+    const int split = blockIdx.x / nqg;
+    const int wg = split * 4 + wave;                    // wave index along the token axis
     const int kvh = blockIdx.y, b = blockIdx.z;
     const int G = H / KVH;
     const int QR = G * rows;
     const int L = kv_len[b];
     const int n_tok = L + rows;
-    const int t_begin = wg * Tw;
-    if (t_begin >= n_tok) return;                       // merge kernel skips these waves too
-    const int t_end = min(n_tok, t_begin + Tw);
+    const int t_begin = min(wg * Tw, n_tok);
+    const int t_end = min(n_tok, t_begin + Tw);         // empty range for waves past the end
+    // blocks that lie completely inside the old cache need neither mask nor clean-up
+    const int t_split = max(t_begin, min(t_end, (L / 32) * 32));
     const bf16_t* __restrict__ K = kc + ((int64_t)b * KVH + kvh) * cap * HD;
     const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
 
-    // query rows of this wave: global qrow n = qg*48 + nt*16 + c  <->  block row n / G, head n % G
-    bf16x8 qb[FA_NT][KS];
+    // stage the query tile: global qrow n = qg*48 + local row  <->  block row n / G, head n % G
+    for (int idx = tid; idx < FA_QROWS * (HD / 8); idx += 256) {
+        const int row = idx / (HD / 8), seg = idx % (HD / 8);
+        const int n = qg * FA_QROWS + row;
+        bf16x8 v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        if (n < QR) {
+            const int i = n / G, gq = n % G;
+            v = *reinterpret_cast<const bf16x8*>(
+                q + (((int64_t)(b * rows + i)) * H + kvh * G + gq) * HD + seg * 8);
+        }
+        *reinterpret_cast<bf16x8*>(smem + row * QROW + seg * 16) = v;
+    }
     int qi[FA_NT];               // block row index of the lane's query row (for the causal mask)
 #pragma unroll
     for (int nt = 0; nt < FA_NT; ++nt) {
         const int n = qg * FA_QROWS + nt * 16 + c;
-        const bool ok = n < QR;
-        const int i = ok ? n / G : 0, gq = ok ? n % G : 0;
-        qi[nt] = ok ? i : -1;
-        const bf16_t* qp = q + (((int64_t)(b * rows + i)) * H + kvh * G + gq) * HD + g * HQ;
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-            qb[nt][s] = ok ? *reinterpret_cast<const bf16x8*>(qp + s * 8)
-                           : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        qi[nt] = n < QR ? n / G : -1;
     }
+    __syncthreads();
 
-    f32x4 oacc[MT][FA_NT];
+    f32x4 oacc[MT][FA_NT], lacc[FA_NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int nt = 0; nt < FA_NT; ++nt) {
+        lacc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int nt = 0; nt < FA_NT; ++nt) oacc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float m_run[FA_NT], l_lane[FA_NT];
+        for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    float m_run[FA_NT];
 #pragma unroll
-    for (int nt = 0; nt < FA_NT; ++nt) { m_run[nt] = -INFINITY; l_lane[nt] = 0.f; }
+    for (int nt = 0; nt < FA_NT; ++nt) m_run[nt] = -INFINITY;
 
     const float scale2 = 1.4426950408889634f / sqrtf((float)HD);
+    const bf16_t one = (bf16_t)1.0f;
+    const bf16x8 ones = (bf16x8){one, one, one, one, one, one, one, one};
 
     // K tile a, MFMA row m=c  <->  token t0 + 8*(c/4) + 4a + c%4
     const int ktok0 = 8 * (c >> 2) + (c & 3);
-    bf16x8 kn[2][KS], vn[MT];
-    auto load_kv = [&](int t0) {
+    auto load_k = [&](fa_kbuf<HD>& buf, int t0, int limit) {
+        if (t0 >= limit) return;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
-            const bf16_t* kp = K + (int64_t)(t0 + ktok0 + 4 * a) * HD + g * HQ;
+            // the four lanes of a token row read 64 contiguous bytes per k-step
+            const bf16_t* kp = K + (int64_t)(t0 + ktok0 + 4 * a) * HD + g * 8;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) kn[a][s] = *reinterpret_cast<const bf16x8*>(kp + s * 8);
+            for (int s = 0; s < KS; ++s) buf.k[a][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
         }
+    };
+    auto load_v = [&](fa_vbuf<HD>& buf, int t0, int limit) {
+        if (t0 >= limit) return;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            vn[mt] = *reinterpret_cast<const bf16x8*>(V + (int64_t)(mt * 16 + c) * cap + t0 + 8 * g);
+            buf.v[mt] = *reinterpret_cast<const bf16x8*>(V + (int64_t)(mt * 16 + c) * cap + t0 + 8 * g);
     };
 
-    load_kv(t_begin);
-    for (int t0 = t_begin; t0 < t_end; t0 += 32) {
-        bf16x8 kr[2][KS], vr[MT];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kr[a][s] = kn[a][s];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) vr[mt] = vn[mt];
-        if (t0 + 32 < t_end) load_kv(t0 + 32);
-
+    auto compute = [&](fa_kbuf<HD>& kb, fa_vbuf<HD>& vb, int t0, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         // scores: lane (c, g) gets tokens t0 + 8g + (4a + j) of query row nt*16 + c
         f32x4 sacc[2][FA_NT];
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            f32x4 z0 = (f32x4){0.f, 0.f, 0.f, 0.f}, z1 = z0;
 #pragma unroll
-            for (int nt = 0; nt < FA_NT; ++nt) {
-                f32x4 z = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[a][s], qb[nt][s], z, 0, 0, 0);
-                sacc[a][nt] = z;
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 qb = *reinterpret_cast<const bf16x8*>(
+                    smem + (nt * 16 + c) * QROW + s * 64 + g * 16);
+                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb.k[0][s], qb, z0, 0, 0, 0);
+                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb.k[1][s], qb, z1, 0, 0, 0);
             }
-        const bool tail = t0 + 32 > L;       // block touches the new rows or the dead region
-        if (tail) {
+            sacc[0][nt] = z0;
+            sacc[1][nt] = z1;
+        }
+        if (TAIL) {
             // dead cache rows may hold anything: zero their V so that 0 * garbage stays 0
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if (t0 + 8 * g + j >= n_tok) vr[mt][j] = (bf16_t)0.f;
+                    if (t0 + 8 * g + j >= n_tok) vb.v[mt][j] = (bf16_t)0.f;
         }
         bool moved = false;
         float alpha[FA_NT];
@@ -224,87 +251,181 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    float s = sacc[a][nt][j] * scale2;
-                    if (tail && (t0 + 8 * g + 4 * a + j > L + qi[nt])) s = -INFINITY;
+                    float s = sacc[a][nt][j];
+                    if (TAIL && (t0 + 8 * g + 4 * a + j > L + qi[nt])) s = -INFINITY;
                     sv[4 * a + j] = s;
                 }
-            float mx = sv[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
+            float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
+            mx = fmaxf(fmaxf(mx, sv[3]), sv[4]);
+            mx = fmaxf(fmaxf(mx, sv[5]), fmaxf(sv[6], sv[7]));
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[nt], mx);
+            mx *= scale2;                       // scale2 > 0: scaling commutes with the max
+            // The reference maximum only follows the true one when it is left behind by more
+            // than 2^8: probabilities stay below 256, O and the row sum stay consistent, and
+            // the rescale of O (the expensive part) runs a handful of times per wave.
+            const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;
+            const float m_new = up ? mx : m_run[nt];
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            alpha[nt] = __builtin_amdgcn_exp2f(m_run[nt] - m_safe);
-            moved |= (m_new > m_run[nt]);
+            alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - m_safe) : 1.0f;
+            moved |= up;
             m_run[nt] = m_new;
-            float ls = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float p = __builtin_amdgcn_exp2f(sv[j] - m_safe);
-                ls += p;
-                pb[nt][j] = (bf16_t)p;
-            }
-            l_lane[nt] = l_lane[nt] * alpha[nt] + ls;
+            for (int j = 0; j < 8; ++j)
+                pb[nt][j] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(sv[j], scale2, -m_safe));
         }
         if (__any(moved)) {
+            // rare path (see above); the empty asm statements keep the register-file copies
+            // that the multiply needs inside this branch
 #pragma unroll
-            for (int nt = 0; nt < FA_NT; ++nt)
+            for (int nt = 0; nt < FA_NT; ++nt) {
+                asm volatile("" : "+a"(lacc[nt]));
+                lacc[nt] *= alpha[nt];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] *= alpha[nt];
+                for (int mt = 0; mt < MT; ++mt) {
+                    asm volatile("" : "+a"(oacc[mt][nt]));
+                    oacc[mt][nt] *= alpha[nt];
+                }
+            }
         }
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            // row sums of the rounded probabilities on the matrix core: ones^T * P^T
+            lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[nt], lacc[nt], 0, 0, 0);
 #pragma unroll
-            for (int nt = 0; nt < FA_NT; ++nt)
-                oacc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vr[mt], pb[nt], oacc[mt][nt], 0, 0, 0);
-    }
+            for (int mt = 0; mt < MT; ++mt)
+                oacc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb.v[mt], pb[nt], oacc[mt][nt], 0, 0, 0);
+        }
+        // keep the accumulators in the accumulation registers between blocks, so that the
+        // vector registers stay free for the K/V stages (no register-file shuffling per block)
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            asm volatile("" : "+a"(lacc[nt]));
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+a"(oacc[mt][nt]));
+        }
+    };
+    const std::integral_constant<bool, false> main_tag;
+    const std::integral_constant<bool, true> tail_tag;
 
-    // partial result of this wave
+    // two register stages: the next 32-token block (16 KB per wave) is in flight while the
+    // current one is being multiplied
+    {
+        fa_kbuf<HD> k0, k1;
+        fa_vbuf<HD> v0, v1;
+        const int e = t_split;
+        load_k(k0, t_begin, e);
+        load_v(v0, t_begin, e);
+        for (int t0 = t_begin; t0 < e; t0 += 64) {
+            load_k(k1, t0 + 32, e);  load_v(v1, t0 + 32, e);  compute(k0, v0, t0, main_tag);
+            if (t0 + 32 >= e) break;
+            load_k(k0, t0 + 64, e);  load_v(v0, t0 + 64, e);  compute(k1, v1, t0 + 32, main_tag);
+        }
+    }
+    // the few blocks that touch the new rows or the dead region: masked, not pipelined
+    for (int t0 = t_split; t0 < t_end; t0 += 32) {
+        fa_kbuf<HD> kt;
+        fa_vbuf<HD> vt;
+        load_k(kt, t0, t_end);
+        load_v(vt, t0, t_end);
+        compute(kt, vt, t0, tail_tag);
+    }
+    __syncthreads();             // every wave is done with the query tile: LDS changes hands
+
+    float l_tot[FA_NT];
+#pragma unroll
+    for (int nt = 0; nt < FA_NT; ++nt) l_tot[nt] = lacc[nt][0];
+
+    // merge the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
+    auto put = [&](int slot) {
+        float* so = s_o + slot * FA_QROWS * OROW;
+        float* sm = s_ml + slot * FA_QROWS * 2;
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            const int n = nt * 16 + c;
+            if (g == 0) { sm[n * 2] = m_run[nt]; sm[n * 2 + 1] = l_tot[nt]; }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                *reinterpret_cast<f32x4*>(&so[n * OROW + mt * 16 + 4 * g]) = oacc[mt][nt];
+        }
+    };
+    auto take = [&](int slot) {
+        const float* so = s_o + slot * FA_QROWS * OROW;
+        const float* sm = s_ml + slot * FA_QROWS * 2;
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            const int n = nt * 16 + c;
+            const float mb = sm[n * 2], lb = sm[n * 2 + 1];
+            const float M = fmaxf(m_run[nt], mb);
+            const float Ms = (M == -INFINITY) ? 0.f : M;
+            const float sa = __builtin_amdgcn_exp2f(m_run[nt] - Ms);
+            const float sb = __builtin_amdgcn_exp2f(mb - Ms);
+            m_run[nt] = M;
+            l_tot[nt] = l_tot[nt] * sa + lb * sb;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const f32x4 ob = *reinterpret_cast<const f32x4*>(&so[n * OROW + mt * 16 + 4 * g]);
+                oacc[mt][nt] = oacc[mt][nt] * sa + ob * sb;
+            }
+        }
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) take(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave != 0) return;
+    take(0);
+
     const int64_t item = ((int64_t)b * KVH + kvh) * nqg + qg;
-    float* __restrict__ o_out = po + (item * nwaves + wg) * FA_QROWS * HD;
-    float* __restrict__ ml_out = pml + (item * nwaves + wg) * FA_QROWS * 2;
+    float* __restrict__ o_out = po + (item * nsplit + split) * FA_QROWS * HD;
+    float* __restrict__ ml_out = pml + (item * nsplit + split) * FA_QROWS * 2;
 #pragma unroll
     for (int nt = 0; nt < FA_NT; ++nt) {
-        float l = l_lane[nt];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
         const int n = nt * 16 + c;
-        if (g == 0) { ml_out[n * 2] = m_run[nt]; ml_out[n * 2 + 1] = l; }
+        if (g == 0) { ml_out[n * 2] = m_run[nt]; ml_out[n * 2 + 1] = l_tot[nt]; }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
             *reinterpret_cast<f32x4*>(o_out + (int64_t)n * HD + mt * 16 + 4 * g) = oacc[mt][nt];
     }
 }
 
-// out[r][h*HD + d] = sum_w 2^(m_w - M) O_w[d] / sum_w 2^(m_w - M) l_w
+// out[r][h*HD + d] = sum_s 2^(m_s - M) O_s[d] / sum_s 2^(m_s - M) l_s  over the splits
+#define FA_MAX_SPLIT 64
 template <typename OT>
-__global__ void k_attn_merge(const float* __restrict__ po, const float* __restrict__ pml,
-                             const int32_t* __restrict__ kv_len, int rows, int H, int KVH, int HD,
-                             int Tw, int nqg, int nwaves, OT* __restrict__ out) {
+__global__ void k_attn_merge(const float* __restrict__ po, const float* __restrict__ pml, int rows,
+                             int H, int KVH, int HD, int nqg, int nsplit, OT* __restrict__ out) {
     const int n = blockIdx.x;                 // query row within the KV head: i*G + gq
     const int kvh = blockIdx.y, b = blockIdx.z;
     const int G = H / KVH;
     const int i = n / G, gq = n % G;
     const int qg = n / FA_QROWS, nl = n % FA_QROWS;
-    const int n_tok = kv_len[b] + rows;
-    const int nvalid = min(nwaves, (n_tok + Tw - 1) / Tw);
     const int64_t item = ((int64_t)b * KVH + kvh) * nqg + qg;
-    const float* __restrict__ ml = pml + item * nwaves * FA_QROWS * 2;
-    const float* __restrict__ o = po + item * nwaves * FA_QROWS * HD;
-    float M = -INFINITY;
-    for (int w = 0; w < nvalid; ++w) M = fmaxf(M, ml[((int64_t)w * FA_QROWS + nl) * 2]);
-    for (int d = threadIdx.x; d < HD; d += blockDim.x) {
-        float num = 0.f, den = 0.f;
-        for (int w = 0; w < nvalid; ++w) {
-            const float mw = ml[((int64_t)w * FA_QROWS + nl) * 2];
-            if (mw == -INFINITY) continue;
-            const float sc = __builtin_amdgcn_exp2f(mw - M);
-            den += sc * ml[((int64_t)w * FA_QROWS + nl) * 2 + 1];
-            num += sc * o[((int64_t)w * FA_QROWS + nl) * HD + d];
+    const float* __restrict__ ml = pml + (item * nsplit * FA_QROWS + nl) * 2;
+    const float* __restrict__ o = po + (item * nsplit * FA_QROWS + nl) * HD;
+    __shared__ float wgt[FA_MAX_SPLIT];
+    __shared__ float den_s;
+    if (threadIdx.x == 0) {
+        float M = -INFINITY;
+        for (int w = 0; w < nsplit; ++w) M = fmaxf(M, ml[(int64_t)w * FA_QROWS * 2]);
+        float den = 0.f;
+        for (int w = 0; w < nsplit; ++w) {
+            const float mw = ml[(int64_t)w * FA_QROWS * 2];
+            const float sc = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+            wgt[w] = sc;
+            den += sc * ml[(int64_t)w * FA_QROWS * 2 + 1];
         }
-        const int r = b * rows + i;
-        cs_st(out, ((int64_t)r * H + kvh * G + gq) * HD + d, num / den);
+        den_s = den;
+    }
+    __syncthreads();
+    const float inv = 1.0f / den_s;
+    const int r = b * rows + i;
+    for (int d = threadIdx.x; d < HD; d += blockDim.x) {
+        float num = 0.f;
+#pragma unroll 8
+        for (int w = 0; w < nsplit; ++w) num += wgt[w] * o[(int64_t)w * FA_QROWS * HD + d];
+        cs_st(out, ((int64_t)r * H + kvh * G + gq) * HD + d, num * inv);
     }
 }
 
@@ -331,36 +452,37 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const int QR = G * rows;
     const int nqg = (int)cs_ceil_div(QR, FA_QROWS);
     const int64_t n_tok_ub = len_ub + rows;
-    // about two workgroups per compute unit, at least 128 tokens per wave
-    int nsplit = (int)cs_ceil_div(512, (int64_t)B * KVH * nqg);
+    // The kernel keeps one wave per SIMD (register budget), so one workgroup fills a compute
+    // unit: aim at one workgroup per compute unit, at least 128 tokens per wave.
+    int nsplit = (int)cs_ceil_div(256, (int64_t)B * KVH * nqg);
     const int max_split = (int)cs_ceil_div(n_tok_ub, 4 * 128);
     if (nsplit > max_split) nsplit = max_split;
+    if (nsplit > FA_MAX_SPLIT) nsplit = FA_MAX_SPLIT;
     if (nsplit < 1) nsplit = 1;
-    int Tw = (int)cs_round_up(cs_ceil_div(n_tok_ub, (int64_t)nsplit * 4), 32);
-    int nwaves = (int)cs_ceil_div(n_tok_ub, Tw);
-    nsplit = (int)cs_ceil_div(nwaves, 4);
-    nwaves = nsplit * 4;
-    const size_t need = (size_t)B * KVH * nqg * nwaves * FA_QROWS * (hd + 2);
+    const int Tw = (int)cs_round_up(cs_ceil_div(n_tok_ub, (int64_t)nsplit * 4), 32);
+    nsplit = (int)cs_ceil_div(n_tok_ub, (int64_t)Tw * 4);
+    const size_t items = (size_t)B * KVH * nqg * nsplit;
+    const size_t need = items * FA_QROWS * (hd + 2);
     CS_REQUIRE(need <= m->attn_part_floats, CS_E_CAPACITY,
                "attention workspace too small (%zu > %zu floats)", need, m->attn_part_floats);
     float* po = m->attn_part;
-    float* pml = m->attn_part + (size_t)B * KVH * nqg * nwaves * FA_QROWS * hd;
+    float* pml = m->attn_part + items * FA_QROWS * hd;
     const bf16_t* kc = (const bf16_t*)kv->k + layer * per_layer;
     const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
     dim3 grid(nsplit * nqg, KVH, B);
     const int pa = cs_prof_begin(CS_PROF_ATTN, s);
     if (hd == 128)
         k_attn_mfma<128><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
-                                              kv->cap, Tw, nqg, nwaves, po, pml);
+                                              kv->cap, Tw, nqg, nsplit, po, pml);
     else
         k_attn_mfma<64><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
-                                             kv->cap, Tw, nqg, nwaves, po, pml);
+                                             kv->cap, Tw, nqg, nsplit, po, pml);
     cs_prof_end(pa, s);
     CS_TRY(cs_launch_ok("k_attn_mfma"));
     dim3 mgrid(QR, KVH, B);
     const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
-    k_attn_merge<bf16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, kv->d_len, rows, H, KVH, hd, Tw,
-                                                           nqg, nwaves, (bf16_t*)m->xn);
+    k_attn_merge<bf16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
+                                                           (bf16_t*)m->xn);
     cs_prof_end(pm, s);
     return cs_launch_ok("k_attn_merge");
 }

@@ -51,8 +51,8 @@ __global__ void k_embed(const WT* __restrict__ embed, const int32_t* __restrict_
 // The split-K partial tiles of the preceding projection are reduced here, in a fixed
 // order, so the result does not depend on scheduling.
 // -------------------------------------------------------------------------------------
-#define NORM_THREADS 256
-#define NORM_MAXPT 32
+#define NORM_THREADS 1024
+#define NORM_MAXV 2          // float4 vectors per thread: d <= 4 * 2 * 1024
 template <typename OutT>
 __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
                                                           const float* __restrict__ part,
@@ -60,18 +60,25 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
                                                           float eps, const float* __restrict__ gain,
                                                           OutT* __restrict__ xn) {
     const int r = blockIdx.x;
-    float v[NORM_MAXPT];
+    const int nvec = d >> 2;                 // d is a multiple of 4 (checked on the host)
+    float4 v[NORM_MAXV];
     float ss = 0.f;
 #pragma unroll
-    for (int u = 0; u < NORM_MAXPT; ++u) {
+    for (int u = 0; u < NORM_MAXV; ++u) {
         const int c = threadIdx.x + u * NORM_THREADS;
-        v[u] = 0.f;
-        if (c < d) {
-            float a = x[(int64_t)r * d + c];
-            for (int p = 0; p < nparts; ++p) a += part[p * part_stride + (int64_t)r * d + c];
-            if (nparts > 0) x[(int64_t)r * d + c] = a;
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < nvec) {
+            const int64_t off = (int64_t)r * d + 4 * c;
+            float4 a = *reinterpret_cast<const float4*>(x + off);
+            // all partial tiles are fetched before the first add: the loads are independent
+#pragma unroll 8
+            for (int p = 0; p < nparts; ++p) {
+                const float4 t = *reinterpret_cast<const float4*>(part + p * part_stride + off);
+                a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+            }
+            if (nparts > 0) *reinterpret_cast<float4*>(x + off) = a;
             v[u] = a;
-            ss += a * a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
         }
     }
     if (!xn) return;
@@ -84,9 +91,16 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
     for (int w = 0; w < NORM_THREADS / CS_WAVE; ++w) tot += wsum[w];
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
 #pragma unroll
-    for (int u = 0; u < NORM_MAXPT; ++u) {
+    for (int u = 0; u < NORM_MAXV; ++u) {
         const int c = threadIdx.x + u * NORM_THREADS;
-        if (c < d) cs_st(xn, (int64_t)r * d + c, v[u] * scale * gain[c]);
+        if (c < nvec) {
+            const float4 gn = *reinterpret_cast<const float4*>(gain + 4 * c);
+            const int64_t off = (int64_t)r * d + 4 * c;
+            cs_st(xn, off + 0, v[u].x * scale * gn.x);
+            cs_st(xn, off + 1, v[u].y * scale * gn.y);
+            cs_st(xn, off + 2, v[u].z * scale * gn.z);
+            cs_st(xn, off + 3, v[u].w * scale * gn.w);
+        }
     }
 }
 
@@ -96,20 +110,22 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
 // cache row kv_len[b]+i; v -> stored transposed (token index contiguous).
 // -------------------------------------------------------------------------------------
 template <typename WT, typename QT>
-__global__ void k_rope_append(const float* __restrict__ qkv, int nparts, int64_t part_stride,
-                              const float2* __restrict__ rope, const int32_t* __restrict__ kv_len,
-                              int rows, int H, int KVH, int hd, int64_t cap, WT* __restrict__ kc,
-                              WT* __restrict__ vc, QT* __restrict__ q) {
-    const int r = blockIdx.x;
+__global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qkv, int nparts,
+                                                    int64_t part_stride,
+                                                    const float2* __restrict__ rope,
+                                                    const int32_t* __restrict__ kv_len, int rows,
+                                                    int H, int KVH, int hd, int64_t cap,
+                                                    WT* __restrict__ kc, WT* __restrict__ vc,
+                                                    QT* __restrict__ q) {
+    const int r = blockIdx.y, head = blockIdx.x;     // head: q heads, then k heads, then v heads
     const int b = r / rows, i = r % rows;
     const int half = hd / 2;
     const int nq = (H + 2 * KVH) * hd;
     const int64_t pos = (int64_t)kv_len[b] + i;
-    const int npairs = (H + 2 * KVH) * half;
-    for (int t = threadIdx.x; t < npairs; t += blockDim.x) {
-        const int head = t / half, j = t % half;
+    for (int j = threadIdx.x; j < half; j += 64) {
         const int64_t i0 = (int64_t)r * nq + (int64_t)head * hd + j;
         float a = 0.f, c = 0.f;
+#pragma unroll 8
         for (int p = 0; p < nparts; ++p) {
             a += qkv[p * part_stride + i0];
             c += qkv[p * part_stride + i0 + half];
@@ -314,21 +330,22 @@ int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* 
     const int64_t per_layer = (int64_t)kv->B * c.n_kv_heads * kv->cap * c.head_dim;
     const int64_t ps = (int64_t)R * (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
     const float2* rope = m->rope;
+    dim3 rgrid(c.n_heads + 2 * c.n_kv_heads, R);
     if (c.dtype == CS_BF16) {
         bf16_t* kc = (bf16_t*)kv->k + layer * per_layer;
         bf16_t* vc = (bf16_t*)kv->v + layer * per_layer;
         if (m->fast)
-            k_rope_append<bf16_t, bf16_t><<<R, 256, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
+            k_rope_append<bf16_t, bf16_t><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                            c.n_heads, c.n_kv_heads, c.head_dim,
                                                            kv->cap, kc, vc, (bf16_t*)m->q);
         else
-            k_rope_append<bf16_t, float><<<R, 256, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
+            k_rope_append<bf16_t, float><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                           c.n_heads, c.n_kv_heads, c.head_dim,
                                                           kv->cap, kc, vc, (float*)m->q);
     } else {
         float* kc = (float*)kv->k + layer * per_layer;
         float* vc = (float*)kv->v + layer * per_layer;
-        k_rope_append<float, float><<<R, 256, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
+        k_rope_append<float, float><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                      c.n_heads, c.n_kv_heads, c.head_dim, kv->cap,
                                                      kc, vc, (float*)m->q);
     }
