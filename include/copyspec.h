@@ -216,8 +216,9 @@ int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int32_t* prompt
  * ---------------------------------------------------------------------------------- */
 
 /* Y[R][N] (float32) = X[R][K] * W[N][K]^T.  dtype CS_BF16: X and W are bfloat16, products
- * accumulate in float32 on the matrix cores; CS_F32: X and W float32.  Uses `m`'s
- * workspace, so R <= max_batch*(max_k+1). */
+ * accumulate in float32 on the matrix cores (needs a model that runs the bf16 kernels,
+ * N % 16 == 0, K % 128 == 0; W is first re-laid-out into the kernel's tiled weight format in
+ * a temporary, and the call waits for completion); CS_F32: X and W float32. */
 int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void* W, float* Y,
                int32_t R, int32_t N, int32_t K, void* stream);
 

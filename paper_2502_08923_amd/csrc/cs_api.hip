@@ -162,8 +162,9 @@ static int model_build(cs_model* m, const cs_weights* w) {
     DEV_ALLOC(m->lm_head, (size_t)V * d * e);
     DEV_ALLOC(m->final_norm, (size_t)d * 4);
     CS_HIP(hipMemcpy(m->embed, w->embed, (size_t)V * d * e, hipMemcpyDeviceToDevice));
-    CS_HIP(hipMemcpy(m->lm_head, w->lm_head, (size_t)V * d * e, hipMemcpyDeviceToDevice));
     CS_HIP(hipMemcpy(m->final_norm, w->final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice));
+    if (m->fast) CS_TRY(cs_tile_weights_launch(w->lm_head, nullptr, V, d, 0, V, 0, m->lm_head, nullptr));
+    else CS_HIP(hipMemcpy(m->lm_head, w->lm_head, (size_t)V * d * e, hipMemcpyDeviceToDevice));
     for (int l = 0; l < c.n_layers; ++l) {
         const cs_layer_weights& s = w->layers[l];
         CS_REQUIRE(s.wq && s.wk && s.wv && s.wo && s.wg && s.wu && s.wd && s.norm1 && s.norm2,
@@ -176,14 +177,24 @@ static int model_build(cs_model* m, const cs_weights* w) {
         DEV_ALLOC(L.norm1, (size_t)d * 4);
         DEV_ALLOC(L.norm2, (size_t)d * 4);
         char* qkv = (char*)L.wqkv;
+        CS_HIP(hipMemcpy(L.norm1, s.norm1, (size_t)d * 4, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
+        if (m->fast) {
+            // the q, k and v blocks become row ranges of one tiled matrix
+            CS_TRY(cs_tile_weights_launch(s.wq, nullptr, nq, d, 0, nqkv, 0, qkv, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wk, nullptr, nkv, d, 0, nqkv, nq, qkv, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wv, nullptr, nkv, d, 0, nqkv, nq + nkv, qkv, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wo, nullptr, d, nq, 0, d, 0, L.wo, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wg, s.wu, 2 * F, d, 1, 2 * F, 0, L.wgu, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wd, nullptr, d, F, 0, d, 0, L.wd, nullptr));
+            continue;
+        }
         CS_HIP(hipMemcpy(qkv, s.wq, (size_t)nq * d * e, hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(qkv + (size_t)nq * d * e, s.wk, (size_t)nkv * d * e, hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(qkv + (size_t)(nq + nkv) * d * e, s.wv, (size_t)nkv * d * e,
                          hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(L.wo, s.wo, (size_t)d * nq * e, hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(L.wd, s.wd, (size_t)d * F * e, hipMemcpyDeviceToDevice));
-        CS_HIP(hipMemcpy(L.norm1, s.norm1, (size_t)d * 4, hipMemcpyDeviceToDevice));
-        CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
         if (c.dtype == CS_BF16)
             k_pack_gu<bf16_t><<<2 * F, 256>>>((const bf16_t*)s.wg, (const bf16_t*)s.wu, F, d,
                                              (bf16_t*)L.wgu);
@@ -247,7 +258,7 @@ extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_
     m->esz = c.dtype == CS_BF16 ? 2 : 4;
     const int nq = c.n_heads * c.head_dim;
     m->fast = !m->plain && c.dtype == CS_BF16 && (c.head_dim == 64 || c.head_dim == 128) &&
-              c.d_model % 128 == 0 && c.d_ff % 128 == 0 && nq % 128 == 0;
+              c.d_model % 128 == 0 && c.d_ff % 128 == 0 && nq % 128 == 0 && c.vocab % 16 == 0;
     m->asz = m->fast ? 2 : 4;
     m->layers = (cs_layer_dev*)calloc(c.n_layers, sizeof(cs_layer_dev));
     if (!m->layers) { free(m); cs_set_error("out of host memory"); return CS_E_DEVICE; }
@@ -691,14 +702,30 @@ extern "C" int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void*
     if (dtype == CS_F32) return cs_gemm_plain_launch(CS_F32, (const float*)X, W, Y, R, N, K, s);
     CS_REQUIRE(dtype == CS_BF16, CS_E_ARG, "cs_op_gemm: bad dtype");
     CS_REQUIRE(m->fast, CS_E_STATE, "cs_op_gemm(bf16) needs a model that runs the bf16 kernels");
-    if ((size_t)R * N > m->part_floats)   // too large for the workspace: no K split, straight to Y
-        return cs_gemm_launch(m, X, W, Y, R, N, K, CS_GEMM_STORE, 0, nullptr, s);
+    // the tuned kernel reads W in its tiled layout: re-lay it out into a temporary first
+    void* wt = nullptr;
+    CS_HIP(hipMalloc(&wt, (size_t)N * K * 2));
+    int rc = cs_tile_weights_launch(W, nullptr, N, K, 0, N, 0, wt, s);
     int np = 1;
-    CS_TRY(cs_gemm_launch(m, X, W, m->part, R, N, K, CS_GEMM_STORE, 1, &np, s));
-    const int64_t n = (int64_t)R * N;
-    k_sum_parts<<<(unsigned)(cs_ceil_div(n, 256) < 2048 ? cs_ceil_div(n, 256) : 2048), 256, 0, s>>>(
-        m->part, np, n, Y);
-    return cs_launch_ok("k_sum_parts");
+    if (rc == CS_OK) {
+        if ((size_t)R * N > m->part_floats) {   // too large for the workspace: no K split
+            rc = cs_gemm_launch(m, X, wt, Y, R, N, K, CS_GEMM_STORE, 0, nullptr, s);
+        } else {
+            rc = cs_gemm_launch(m, X, wt, m->part, R, N, K, CS_GEMM_STORE, 1, &np, s);
+            if (rc == CS_OK) {
+                const int64_t n = (int64_t)R * N;
+                k_sum_parts<<<(unsigned)(cs_ceil_div(n, 256) < 2048 ? cs_ceil_div(n, 256) : 2048), 256, 0,
+                              s>>>(m->part, np, n, Y);
+                rc = cs_launch_ok("k_sum_parts");
+            }
+        }
+    }
+    if (hipStreamSynchronize(s) != hipSuccess && rc == CS_OK) {
+        cs_set_error("cs_op_gemm: synchronize failed");
+        rc = CS_E_DEVICE;
+    }
+    (void)hipFree(wt);
+    return rc;
 }
 
 extern "C" int cs_op_attention(cs_model* m, cs_kv* kv, int32_t layer, const float* q, int32_t rows,

@@ -308,18 +308,27 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     const std::integral_constant<bool, false> main_tag;
     const std::integral_constant<bool, true> tail_tag;
 
-    // two register stages: the next 32-token block (16 KB per wave) is in flight while the
-    // current one is being multiplied
+    // register stages: K is fetched two 32-token blocks ahead, V one block ahead, so about
+    // 24 KB per wave are in flight while one block is being multiplied
     {
-        fa_kbuf<HD> k0, k1;
+        fa_kbuf<HD> k0, k1, k2;
         fa_vbuf<HD> v0, v1;
         const int e = t_split;
         load_k(k0, t_begin, e);
         load_v(v0, t_begin, e);
-        for (int t0 = t_begin; t0 < e; t0 += 64) {
-            load_k(k1, t0 + 32, e);  load_v(v1, t0 + 32, e);  compute(k0, v0, t0, main_tag);
+        load_k(k1, t_begin + 32, e);
+        for (int t0 = t_begin; t0 < e; t0 += 192) {
+            load_v(v1, t0 + 32, e);  load_k(k2, t0 + 64, e);   compute(k0, v0, t0, main_tag);
             if (t0 + 32 >= e) break;
-            load_k(k0, t0 + 64, e);  load_v(v0, t0 + 64, e);  compute(k1, v1, t0 + 32, main_tag);
+            load_v(v0, t0 + 64, e);  load_k(k0, t0 + 96, e);   compute(k1, v1, t0 + 32, main_tag);
+            if (t0 + 64 >= e) break;
+            load_v(v1, t0 + 96, e);  load_k(k1, t0 + 128, e);  compute(k2, v0, t0 + 64, main_tag);
+            if (t0 + 96 >= e) break;
+            load_v(v0, t0 + 128, e); load_k(k2, t0 + 160, e);  compute(k0, v1, t0 + 96, main_tag);
+            if (t0 + 128 >= e) break;
+            load_v(v1, t0 + 160, e); load_k(k0, t0 + 192, e);  compute(k1, v0, t0 + 128, main_tag);
+            if (t0 + 160 >= e) break;
+            load_v(v0, t0 + 192, e); load_k(k1, t0 + 224, e);  compute(k2, v1, t0 + 160, main_tag);
         }
     }
     // the few blocks that touch the new rows or the dead region: masked, not pipelined

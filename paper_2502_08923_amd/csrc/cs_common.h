@@ -146,6 +146,10 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
 int cs_gemm_plain_launch(int dtype, const float* X, const void* W, float* Y, int R, int N, int K,
                          hipStream_t s);
 
+// bf16 weights of the tuned GEMM live in MFMA fragment order (see cs_gemm.hip)
+int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int rowmap, int N_total,
+                           int n_off, void* dst, hipStream_t s);
+
 // attention: reads m->q, writes m->xn (GEMM-input type) as [R][H*hd]
 int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
                         hipStream_t s);

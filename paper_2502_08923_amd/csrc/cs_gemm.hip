@@ -43,104 +43,147 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const XT* __restrict__ X,
 // -------------------------------------------------------------------------------------
 // tuned bf16 kernel
 // -------------------------------------------------------------------------------------
-#define GEMM_KC 128                  // K elements per pipeline stage
+#define GEMM_KC 128                       // K elements per pipeline stage
 #define GEMM_LDS_ROW (GEMM_KC * 2 + 16)   // bytes per X row in LDS (padded)
+#define GEMM_DEPTH 4                      // W stages in flight per consumer wave
+#define GEMM_THREADS 384                  // 4 consumer waves + 2 producer waves
 
-// MT: 16-row W tiles per wave.  NT: 16-row X tiles per workgroup.
+// The workgroup is specialised by wave.  Waves 0..3 (consumers) stream W: each owns MT
+// 16-row tiles, keeps GEMM_DEPTH K-chunks of them in flight in registers and multiplies.
+// Waves 4 and 5 (producers) stage the X block of every chunk (half of its rows each)
+// through registers into a double-buffered LDS tile.  The hardware counts outstanding loads per wave and retires
+// them in order, so a wave that waits for a near X load would also drain its far W loads;
+// giving X its own wave keeps the W stream deep.  One barrier per chunk hands the LDS
+// buffers over.
+// MT: 16-row W tiles per consumer wave.  NT: 16-row X tiles per workgroup.
 // grid.x: W row tiles of 64*MT, grid.y: K splits, grid.z: X row blocks of 16*NT.
 template <int MT, int NT, int MODE>
-__global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t* __restrict__ X,
-                                                   const bf16_t* __restrict__ W,
-                                                   float* __restrict__ Y, bf16_t* __restrict__ act,
-                                                   int R, int N, int K, int Ks) {
+__global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const bf16_t* __restrict__ X,
+                                                            const bf16_t* __restrict__ W,
+                                                            float* __restrict__ Y,
+                                                            bf16_t* __restrict__ act, int R, int N,
+                                                            int K, int Ks) {
     __shared__ __attribute__((aligned(16))) unsigned char xs[2][16 * NT * GEMM_LDS_ROW];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int lrow = lane & 15, g = lane >> 4;
-    const int n_wave = (blockIdx.x * 4 + wave) * MT * 16;       // first W row of this wave
     const int k_begin = blockIdx.y * Ks;
     const int k_end = min(K, k_begin + Ks);
     const int nchunks = (k_end - k_begin) / GEMM_KC;
     const int r_base = blockIdx.z * 16 * NT;
 
-    // per-lane W row pointers (rows past N are clamped; their results are never stored)
-    const bf16_t* wrow[MT];
+    if (wave >= 4) {
+        // ---------------- producers: X chunks -> LDS ----------------
+        // lane -> 16-byte segment (lane & 15) of rows row0 + 4*i, i < ROWS4; the two producer
+        // waves split the 16*NT rows in halves
+        constexpr int ROWS4 = 2 * NT;
+        const int seg = lane & 15, row0 = (lane >> 4) + (wave - 4) * 8 * NT;
+        const bf16_t* xbase = X + (int64_t)(r_base + row0) * K + k_begin + seg * 8;
+        const int64_t xstep = (int64_t)4 * K;
+        const int rows_left = R - r_base - row0;          // row 4*i is valid iff 4*i < rows_left
+        const int dst0 = row0 * GEMM_LDS_ROW + seg * 16;
+        bf16x8 xr[2][ROWS4];
+        // chunk indices are clamped instead of guarded: a surplus load re-reads the last chunk
+        // and a surplus store lands in the buffer nobody reads any more, so the loop body is
+        // branch-free and the compiler's load counters stay exact
+        const int last = nchunks - 1;
+        auto load_x = [&](bf16x8* dst, int c) {
+            c = c < last ? c : last;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        int n = n_wave + mt * 16 + lrow;
-        n = n < N ? n : N - 1;
-        wrow[mt] = W + (int64_t)n * K + g * 32;
-    }
-    // X staging: thread handles NT 16-byte segments per chunk
-    int xr_row[NT];
-    const bf16_t* xsrc[NT];
+            for (int i = 0; i < ROWS4; ++i)
+                dst[i] = (4 * i < rows_left)
+                             ? *reinterpret_cast<const bf16x8*>(xbase + i * xstep + c * GEMM_KC)
+                             : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        };
+        auto store_x = [&](const bf16x8* src, int buf) {
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
-        const int idx = i * 256 + tid;
-        xr_row[i] = idx >> 4;
-        const int r = r_base + xr_row[i];
-        xsrc[i] = (r < R) ? X + (int64_t)r * K + (idx & 15) * 8 : nullptr;
+            for (int i = 0; i < ROWS4; ++i)
+                *reinterpret_cast<bf16x8*>(&xs[buf][dst0 + i * 4 * GEMM_LDS_ROW]) = src[i];
+        };
+        load_x(xr[0], 0);
+        load_x(xr[1], 1);
+        store_x(xr[0], 0);
+        load_x(xr[0], 2);
+        __syncthreads();
+        int c = 0;
+        for (; c + 1 < nchunks; c += 2) {
+            // chunk c+1 lives in xr[1], chunk c+2 in xr[0]
+            store_x(xr[1], 1);
+            load_x(xr[1], c + 3);
+            __syncthreads();
+            store_x(xr[0], 0);
+            load_x(xr[0], c + 4);
+            __syncthreads();
+        }
+        if (c < nchunks) __syncthreads();
+        return;
     }
 
+    // ---------------- consumers: W stream + MFMA ----------------
+    const int lrow = lane & 15, g = lane >> 4;
+    const int n_wave = (blockIdx.x * 4 + wave) * MT * 16;       // first W row of this wave
+    // W is stored in MFMA fragment order, K-chunk major: W_t[k/128][n/16][(k%128)/32][lane][8].
+    // The 16-byte piece `lane` of a 1 KB block is exactly that lane's A operand, so every wave
+    // load reads 8 whole cache lines, and all workgroups working on the same K chunk read one
+    // contiguous slab of N*256 bytes, which spreads evenly over the HBM channels (a row-major
+    // W with its power-of-two row pitch makes concurrent workgroups hit the same channels).
+    // (row tiles past N are clamped; their results are never stored)
+    const bf16_t* wtile[MT];
+    const int n_tiles = N >> 4;
+    const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;     // elements per K chunk slab
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int t = (n_wave >> 4) + mt;
+        t = t < n_tiles ? t : n_tiles - 1;
+        wtile[mt] = W + (k_begin / GEMM_KC) * chunk_stride + (int64_t)t * 4 * 512 + lane * 8;
+    }
     f32x4 acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    bf16x8 a_next[MT][4];
-    bf16x8 xr[NT];
-    auto load_w = [&](int kk) {
+    bf16x8 a[GEMM_DEPTH][MT][4];
+    const int last = nchunks - 1;
+    auto load_w = [&](bf16x8 (*dst)[4], int c) {
+        c = c < last ? c : last;               // clamped, see the producer
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                a_next[mt][s] = *reinterpret_cast<const bf16x8*>(wrow[mt] + kk + s * 8);
+                dst[mt][s] = *reinterpret_cast<const bf16x8*>(wtile[mt] + c * chunk_stride + s * 512);
     };
-    auto load_x = [&](int kk) {
-#pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            if (xsrc[i]) xr[i] = *reinterpret_cast<const bf16x8*>(xsrc[i] + kk);
-            else xr[i] = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-        }
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NT; ++i)
-            *reinterpret_cast<bf16x8*>(&xs[buf][xr_row[i] * GEMM_LDS_ROW + ((i * 256 + tid) & 15) * 16]) = xr[i];
-    };
-
-    if (nchunks > 0) {
-        load_w(k_begin);
-        load_x(k_begin);
-        store_x(0);
-    }
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        bf16x8 a_cur[MT][4];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) a_cur[mt][s] = a_next[mt][s];
-        const bool more = c + 1 < nchunks;
-        if (more) {
-            load_w(k_begin + (c + 1) * GEMM_KC);
-            load_x(k_begin + (c + 1) * GEMM_KC);
-        }
-        const unsigned char* xb = xs[c & 1];
+    auto compute = [&](bf16x8 (*src)[4], int buf) {
+        const unsigned char* xb = xs[buf];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                    xb + (nt * 16 + lrow) * GEMM_LDS_ROW + g * 64 + s * 16);
+                const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(
+                    xb + (nt * 16 + lrow) * GEMM_LDS_ROW + s * 64 + g * 16);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_cur[mt][s], b, acc[mt][nt], 0, 0, 0);
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(src[mt][s], bfrag, acc[mt][nt], 0, 0, 0);
             }
         }
-        if (more) store_x((c + 1) & 1);
-        __syncthreads();
+    };
+#pragma unroll
+    for (int u = 0; u < GEMM_DEPTH; ++u) load_w(a[u], u);
+    __syncthreads();
+    int c = 0;
+    for (; c + GEMM_DEPTH <= nchunks; c += GEMM_DEPTH) {      // branch-free groups of DEPTH chunks
+#pragma unroll
+        for (int u = 0; u < GEMM_DEPTH; ++u) {
+            compute(a[u], u & 1);
+            load_w(a[u], c + u + GEMM_DEPTH);
+            __syncthreads();
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < GEMM_DEPTH - 1; ++u) {                // remainder, data already in a[u]
+        if (c + u < nchunks) {
+            compute(a[u], u & 1);
+            __syncthreads();
+        }
     }
 
     // epilogue.  acc[mt][nt][j] = Y[row r_base + nt*16 + lrow][col n_wave + mt*16 + 4g + j]
@@ -188,14 +231,52 @@ static int launch_mfma(const bf16_t* X, const bf16_t* W, float* Y, bf16_t* act, 
               (unsigned)cs_ceil_div(R, 16 * NT));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
     if (mode == CS_GEMM_STORE)
-        k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, 256, 0, s>>>(X, W, Y, act, R, N, K, Ks);
+        k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks);
     else
-        k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, 256, 0, s>>>(X, W, Y, act, R, N, K, Ks);
+        k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks);
     cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_mfma");
 }
 
 static bool mfma_shape_ok(int N, int K) { return K % GEMM_KC == 0 && N % 16 == 0; }
+
+// dst[k/128][n/16][(k%128)/32][lane l][8]: lane l (row n%16 = l%16, k-group l/16) holds the 8
+// elements W[n][(k/32)*32 + (l/16)*8 ..].  N_total/n_off place a block of rows inside a taller
+// matrix (the fused q,k,v projection).  rowmap 0: source row = n.  rowmap 1: rows alternate
+// 16 gate rows (src) / 16 up rows (src2).
+__global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restrict__ src2, int N, int K,
+                         int rowmap, int N_total, int n_off, bf16_t* __restrict__ dst) {
+    const int64_t nvec = (int64_t)N * K / 8;
+    const int n_tiles = N >> 4, nt_total = N_total >> 4;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec;
+         v += (int64_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(v & 63);
+        const int s = (int)((v >> 6) & 3);
+        const int64_t tile = v >> 8;
+        const int nt = (int)(tile % n_tiles);
+        const int kc = (int)(tile / n_tiles);
+        const int n = nt * 16 + (lane & 15);
+        const int k = kc * 128 + s * 32 + (lane >> 4) * 8;
+        const bf16_t* sp = src + (int64_t)n * K;
+        if (rowmap == 1) {
+            const int f = (n >> 5) * 16 + (n & 15);
+            sp = (((n >> 4) & 1) ? src2 : src) + (int64_t)f * K;
+        }
+        const int64_t o = ((((int64_t)kc * nt_total + (n_off >> 4) + nt) * 4 + s) * 64 + lane) * 8;
+        *reinterpret_cast<bf16x8*>(dst + o) = *reinterpret_cast<const bf16x8*>(sp + k);
+    }
+}
+
+int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int rowmap, int N_total,
+                           int n_off, void* dst, hipStream_t s) {
+    CS_REQUIRE(mfma_shape_ok(N, K) && N_total % 16 == 0 && n_off % 16 == 0, CS_E_UNSUPPORTED,
+               "cannot tile a %d x %d matrix", N, K);
+    const int64_t nvec = (int64_t)N * K / 8;
+    const int blocks = (int)(cs_ceil_div(nvec, 256) < 8192 ? cs_ceil_div(nvec, 256) : 8192);
+    k_tile_w<<<blocks, 256, 0, s>>>((const bf16_t*)src, (const bf16_t*)src2, N, K, rowmap, N_total, n_off,
+                                    (bf16_t*)dst);
+    return cs_launch_ok("k_tile_w");
+}
 
 int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, int R, int N, int K,
                    int mode, int allow_split, int* nparts_out, hipStream_t s) {
@@ -210,12 +291,8 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
                 (const float*)X, (const float*)W, Y, R, N, K);
         return cs_launch_ok("k_gemm_plain");
     }
-    if (!mfma_shape_ok(N, K) || (mode == CS_GEMM_SWIGLU && N % 32 != 0)) {
-        CS_REQUIRE(mode == CS_GEMM_STORE, CS_E_UNSUPPORTED, "SwiGLU projection needs d_ff %% 16 == 0");
-        k_gemm_plain<bf16_t, bf16_t><<<(unsigned)cs_ceil_div(N, 4), 256, 0, s>>>(
-            (const bf16_t*)X, (const bf16_t*)W, Y, R, N, K);
-        return cs_launch_ok("k_gemm_plain");
-    }
+    CS_REQUIRE(mfma_shape_ok(N, K) && (mode != CS_GEMM_SWIGLU || N % 32 == 0), CS_E_UNSUPPORTED,
+               "bf16 GEMM needs N %% 16 == 0 and K %% 128 == 0 (N=%d K=%d)", N, K);
     // Split K until there are about two workgroups per compute unit, keeping at least four
     // K chunks per split so the load pipeline has something to overlap.
     const int MT = 2;
