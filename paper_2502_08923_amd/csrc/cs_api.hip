@@ -702,10 +702,13 @@ extern "C" int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void*
     if (dtype == CS_F32) return cs_gemm_plain_launch(CS_F32, (const float*)X, W, Y, R, N, K, s);
     CS_REQUIRE(dtype == CS_BF16, CS_E_ARG, "cs_op_gemm: bad dtype");
     CS_REQUIRE(m->fast, CS_E_STATE, "cs_op_gemm(bf16) needs a model that runs the bf16 kernels");
-    // the tuned kernel reads W in its tiled layout: re-lay it out into a temporary first
+    // the tuned kernel reads W in its tiled fp16 layout and X as fp16: convert into temporaries
     void* wt = nullptr;
-    CS_HIP(hipMalloc(&wt, (size_t)N * K * 2));
+    CS_HIP(hipMalloc(&wt, (size_t)N * K * 2 + (size_t)R * K * 2));
+    void* xt = (char*)wt + (size_t)N * K * 2;
     int rc = cs_tile_weights_launch(W, nullptr, N, K, 0, N, 0, wt, s);
+    if (rc == CS_OK) rc = cs_convert_launch(X, CS_T_BF16, xt, CS_T_F16, (int64_t)R * K, s);
+    X = xt;
     int np = 1;
     if (rc == CS_OK) {
         if ((size_t)R * N > m->part_floats) {   // too large for the workspace: no K split
@@ -737,9 +740,9 @@ extern "C" int cs_op_attention(cs_model* m, cs_kv* kv, int32_t layer, const floa
     hipStream_t s = (hipStream_t)stream;
     CS_TRY(kv_check_room(kv, rows));
     const int64_t n = (int64_t)kv->B * rows * m->cfg.n_heads * m->cfg.head_dim;
-    CS_TRY(cs_convert_launch(q, 0, m->q, m->fast, n, s));
+    CS_TRY(cs_convert_launch(q, CS_T_F32, m->q, m->fast ? CS_T_BF16 : CS_T_F32, n, s));
     CS_TRY(cs_attention_launch(m, kv, layer, rows, kv_max_ub(kv), s));
-    return cs_convert_launch(m->xn, m->fast, out, 0, n, s);
+    return cs_convert_launch(m->xn, m->fast ? CS_T_F16 : CS_T_F32, out, CS_T_F32, n, s);
 }
 
 extern "C" int cs_op_argmax_accept(cs_model* m, const float* logits, int32_t B, int32_t k, int32_t V,

@@ -490,8 +490,8 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     CS_TRY(cs_launch_ok("k_attn_mfma"));
     dim3 mgrid(QR, KVH, B);
     const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
-    k_attn_merge<bf16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
-                                                           (bf16_t*)m->xn);
+    k_attn_merge<f16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
+                                                          (f16_t*)m->xn);
     cs_prof_end(pm, s);
     return cs_launch_ok("k_attn_merge");
 }

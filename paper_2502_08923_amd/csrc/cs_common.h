@@ -11,6 +11,9 @@
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16_t;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define CS_WAVE 64
@@ -71,7 +74,7 @@ struct cs_layer_dev {
 struct cs_model {
     cs_model_cfg cfg;
     int plain;          // 1: plain kernels everywhere
-    int fast;           // 1: bf16 MFMA kernels are in use (activations are bf16)
+    int fast;           // 1: the MFMA kernels are in use (GEMM inputs are fp16, q is bf16)
     int R_max;          // max_batch * (max_k + 1)
     int rows_max;       // max_k + 1
     size_t esz;         // bytes per weight / cache element
@@ -155,7 +158,9 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
                         hipStream_t s);
 
 // conversion helpers
-int cs_convert_launch(const void* src, int src_bf16, void* dst, int dst_bf16, int64_t n,
+// element type codes for cs_convert_launch
+enum { CS_T_F32 = 0, CS_T_BF16 = 1, CS_T_F16 = 2 };
+int cs_convert_launch(const void* src, int src_type, void* dst, int dst_type, int64_t n,
                       hipStream_t s);
 int cs_fill_i32_launch(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 
@@ -164,6 +169,8 @@ __device__ __forceinline__ float cs_ld(const float* p, int64_t i) { return p[i];
 __device__ __forceinline__ float cs_ld(const bf16_t* p, int64_t i) { return (float)p[i]; }
 __device__ __forceinline__ void cs_st(float* p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void cs_st(bf16_t* p, int64_t i, float v) { p[i] = (bf16_t)v; }
+__device__ __forceinline__ float cs_ld(const f16_t* p, int64_t i) { return (float)p[i]; }
+__device__ __forceinline__ void cs_st(f16_t* p, int64_t i, float v) { p[i] = (f16_t)v; }
 
 __device__ __forceinline__ float cs_wave_sum(float v) {
 #pragma unroll

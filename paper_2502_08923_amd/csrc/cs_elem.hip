@@ -315,8 +315,8 @@ int cs_addnorm_launch(const cs_model* m, const float* part, int nparts,
     const int d = m->cfg.d_model;
     const int64_t ps = (int64_t)R * d;
     if (xn_out && m->fast)
-        k_addnorm<bf16_t><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
-                                                     (bf16_t*)xn_out);
+        k_addnorm<f16_t><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
+                                                    (f16_t*)xn_out);
     else
         k_addnorm<float><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
                                                     (float*)xn_out);
@@ -355,8 +355,7 @@ int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* 
 int cs_swiglu_launch(const cs_model* m, int R, hipStream_t s) {
     const int F = m->cfg.d_ff;
     dim3 grid((unsigned)cs_ceil_div(F, 256), R);
-    if (m->fast) k_swiglu<bf16_t><<<grid, 256, 0, s>>>(m->gu, F, (bf16_t*)m->act);
-    else k_swiglu<float><<<grid, 256, 0, s>>>(m->gu, F, (float*)m->act);
+    k_swiglu<float><<<grid, 256, 0, s>>>(m->gu, F, (float*)m->act);   // plain path only
     return cs_launch_ok("k_swiglu");
 }
 
@@ -383,18 +382,20 @@ int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k
     return cs_launch_ok("k_accept");
 }
 
-int cs_convert_launch(const void* src, int src_bf16, void* dst, int dst_bf16, int64_t n,
+template <typename S>
+static void convert_from(const S* src, void* dst, int dst_type, int64_t n, int blocks, hipStream_t s) {
+    if (dst_type == CS_T_F32) k_convert<S, float><<<blocks, 256, 0, s>>>(src, (float*)dst, n);
+    else if (dst_type == CS_T_BF16) k_convert<S, bf16_t><<<blocks, 256, 0, s>>>(src, (bf16_t*)dst, n);
+    else k_convert<S, f16_t><<<blocks, 256, 0, s>>>(src, (f16_t*)dst, n);
+}
+
+int cs_convert_launch(const void* src, int src_type, void* dst, int dst_type, int64_t n,
                       hipStream_t s) {
     if (n <= 0) return CS_OK;
     const int blocks = (int)(cs_ceil_div(n, 256) < 4096 ? cs_ceil_div(n, 256) : 4096);
-    if (src_bf16 && !dst_bf16)
-        k_convert<bf16_t, float><<<blocks, 256, 0, s>>>((const bf16_t*)src, (float*)dst, n);
-    else if (!src_bf16 && dst_bf16)
-        k_convert<float, bf16_t><<<blocks, 256, 0, s>>>((const float*)src, (bf16_t*)dst, n);
-    else if (src_bf16)
-        k_convert<bf16_t, bf16_t><<<blocks, 256, 0, s>>>((const bf16_t*)src, (bf16_t*)dst, n);
-    else
-        k_convert<float, float><<<blocks, 256, 0, s>>>((const float*)src, (float*)dst, n);
+    if (src_type == CS_T_F32) convert_from((const float*)src, dst, dst_type, n, blocks, s);
+    else if (src_type == CS_T_BF16) convert_from((const bf16_t*)src, dst, dst_type, n, blocks, s);
+    else convert_from((const f16_t*)src, dst, dst_type, n, blocks, s);
     return cs_launch_ok("k_convert");
 }
 

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const XT* __restrict__ X,
 }
 
 // -------------------------------------------------------------------------------------
-// tuned bf16 kernel
+// tuned kernel (fp16 operands, fp32 accumulation)
 // -------------------------------------------------------------------------------------
 #define GEMM_KC 128                       // K elements per pipeline stage
 #define GEMM_LDS_ROW (GEMM_KC * 2 + 16)   // bytes per X row in LDS (padded)
@@ -58,10 +58,10 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const XT* __restrict__ X,
 // MT: 16-row W tiles per consumer wave.  NT: 16-row X tiles per workgroup.
 // grid.x: W row tiles of 64*MT, grid.y: K splits, grid.z: X row blocks of 16*NT.
 template <int MT, int NT, int MODE>
-__global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const bf16_t* __restrict__ X,
-                                                            const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restrict__ X,
+                                                            const f16_t* __restrict__ W,
                                                             float* __restrict__ Y,
-                                                            bf16_t* __restrict__ act, int R, int N,
+                                                            f16_t* __restrict__ act, int R, int N,
                                                             int K, int Ks) {
     __shared__ __attribute__((aligned(16))) unsigned char xs[2][16 * NT * GEMM_LDS_ROW];
     const int tid = threadIdx.x;
@@ -77,27 +77,27 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const bf16_t* __rest
         // waves split the 16*NT rows in halves
         constexpr int ROWS4 = 2 * NT;
         const int seg = lane & 15, row0 = (lane >> 4) + (wave - 4) * 8 * NT;
-        const bf16_t* xbase = X + (int64_t)(r_base + row0) * K + k_begin + seg * 8;
+        const f16_t* xbase = X + (int64_t)(r_base + row0) * K + k_begin + seg * 8;
         const int64_t xstep = (int64_t)4 * K;
         const int rows_left = R - r_base - row0;          // row 4*i is valid iff 4*i < rows_left
         const int dst0 = row0 * GEMM_LDS_ROW + seg * 16;
-        bf16x8 xr[2][ROWS4];
+        f16x8 xr[2][ROWS4];
         // chunk indices are clamped instead of guarded: a surplus load re-reads the last chunk
         // and a surplus store lands in the buffer nobody reads any more, so the loop body is
         // branch-free and the compiler's load counters stay exact
         const int last = nchunks - 1;
-        auto load_x = [&](bf16x8* dst, int c) {
+        auto load_x = [&](f16x8* dst, int c) {
             c = c < last ? c : last;
 #pragma unroll
             for (int i = 0; i < ROWS4; ++i)
                 dst[i] = (4 * i < rows_left)
-                             ? *reinterpret_cast<const bf16x8*>(xbase + i * xstep + c * GEMM_KC)
-                             : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+                             ? *reinterpret_cast<const f16x8*>(xbase + i * xstep + c * GEMM_KC)
+                             : (f16x8){0, 0, 0, 0, 0, 0, 0, 0};
         };
-        auto store_x = [&](const bf16x8* src, int buf) {
+        auto store_x = [&](const f16x8* src, int buf) {
 #pragma unroll
             for (int i = 0; i < ROWS4; ++i)
-                *reinterpret_cast<bf16x8*>(&xs[buf][dst0 + i * 4 * GEMM_LDS_ROW]) = src[i];
+                *reinterpret_cast<f16x8*>(&xs[buf][dst0 + i * 4 * GEMM_LDS_ROW]) = src[i];
         };
         load_x(xr[0], 0);
         load_x(xr[1], 1);
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const bf16_t* __rest
     // contiguous slab of N*256 bytes, which spreads evenly over the HBM channels (a row-major
     // W with its power-of-two row pitch makes concurrent workgroups hit the same channels).
     // (row tiles past N are clamped; their results are never stored)
-    const bf16_t* wtile[MT];
+    const f16_t* wtile[MT];
     const int n_tiles = N >> 4;
     const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;     // elements per K chunk slab
 #pragma unroll
@@ -142,27 +142,27 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const bf16_t* __rest
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    bf16x8 a[GEMM_DEPTH][MT][4];
+    f16x8 a[GEMM_DEPTH][MT][4];
     const int last = nchunks - 1;
-    auto load_w = [&](bf16x8 (*dst)[4], int c) {
+    auto load_w = [&](f16x8 (*dst)[4], int c) {
         c = c < last ? c : last;               // clamped, see the producer
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                dst[mt][s] = *reinterpret_cast<const bf16x8*>(wtile[mt] + c * chunk_stride + s * 512);
+                dst[mt][s] = *reinterpret_cast<const f16x8*>(wtile[mt] + c * chunk_stride + s * 512);
     };
-    auto compute = [&](bf16x8 (*src)[4], int buf) {
+    auto compute = [&](f16x8 (*src)[4], int buf) {
         const unsigned char* xb = xs[buf];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(
+                const f16x8 bfrag = *reinterpret_cast<const f16x8*>(
                     xb + (nt * 16 + lrow) * GEMM_LDS_ROW + s * 64 + g * 16);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(src[mt][s], bfrag, acc[mt][nt], 0, 0, 0);
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(src[mt][s], bfrag, acc[mt][nt], 0, 0, 0);
             }
         }
     };
@@ -211,20 +211,20 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const bf16_t* __rest
                 const int n = n_wave + mp * 32;
                 if (n >= N) continue;
                 const int f = n / 2 + 4 * g;
-                bf16x4 o;
+                f16x4 o;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
-                    o[j] = (bf16_t)(gt / (1.0f + __expf(-gt)) * up);
+                    o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
                 }
-                *reinterpret_cast<bf16x4*>(act + (int64_t)r * F + f) = o;
+                *reinterpret_cast<f16x4*>(act + (int64_t)r * F + f) = o;
             }
         }
     }
 }
 
 template <int MT, int NT>
-static int launch_mfma(const bf16_t* X, const bf16_t* W, float* Y, bf16_t* act, int R, int N, int K,
+static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K,
                        int mode, int ksplit, hipStream_t s) {
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     dim3 grid((unsigned)cs_ceil_div(N, 64 * MT), (unsigned)cs_ceil_div(K, Ks),
@@ -245,7 +245,7 @@ static bool mfma_shape_ok(int N, int K) { return K % GEMM_KC == 0 && N % 16 == 0
 // matrix (the fused q,k,v projection).  rowmap 0: source row = n.  rowmap 1: rows alternate
 // 16 gate rows (src) / 16 up rows (src2).
 __global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restrict__ src2, int N, int K,
-                         int rowmap, int N_total, int n_off, bf16_t* __restrict__ dst) {
+                         int rowmap, int N_total, int n_off, f16_t* __restrict__ dst) {
     const int64_t nvec = (int64_t)N * K / 8;
     const int n_tiles = N >> 4, nt_total = N_total >> 4;
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec;
@@ -263,7 +263,13 @@ __global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restric
             sp = (((n >> 4) & 1) ? src2 : src) + (int64_t)f * K;
         }
         const int64_t o = ((((int64_t)kc * nt_total + (n_off >> 4) + nt) * 4 + s) * 64 + lane) * 8;
-        *reinterpret_cast<bf16x8*>(dst + o) = *reinterpret_cast<const bf16x8*>(sp + k);
+        // bfloat16 -> float16: exact for 2^-17 <= |w| < 65504 (8 significant bits fit the
+        // 11-bit significand, subnormals included); smaller magnitudes round to 2^-24 steps
+        const bf16x8 wv = *reinterpret_cast<const bf16x8*>(sp + k);
+        f16x8 hv;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) hv[j] = (f16_t)(float)wv[j];
+        *reinterpret_cast<f16x8*>(dst + o) = hv;
     }
 }
 
@@ -274,7 +280,7 @@ int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int 
     const int64_t nvec = (int64_t)N * K / 8;
     const int blocks = (int)(cs_ceil_div(nvec, 256) < 8192 ? cs_ceil_div(nvec, 256) : 8192);
     k_tile_w<<<blocks, 256, 0, s>>>((const bf16_t*)src, (const bf16_t*)src2, N, K, rowmap, N_total, n_off,
-                                    (bf16_t*)dst);
+                                    (f16_t*)dst);
     return cs_launch_ok("k_tile_w");
 }
 
@@ -308,9 +314,9 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     const int nparts = (int)cs_ceil_div(K, Ks);
     if (nparts_out) *nparts_out = nparts;
     const int rt = (int)cs_ceil_div(R < 96 ? R : 96, 16);
-    const bf16_t* x = (const bf16_t*)X;
-    const bf16_t* w = (const bf16_t*)W;
-    bf16_t* act = (bf16_t*)m->act;
+    const f16_t* x = (const f16_t*)X;
+    const f16_t* w = (const f16_t*)W;
+    f16_t* act = (f16_t*)m->act;
     switch (rt) {
         case 1: return launch_mfma<2, 1>(x, w, Y, act, R, N, K, mode, nparts, s);
         case 2: return launch_mfma<2, 2>(x, w, Y, act, R, N, K, mode, nparts, s);
