@@ -198,6 +198,20 @@ def cpu_baseline(st, args):
                       f"scaled to {sh.n_layers} layers x {st['B']} streams"}
 
 
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE +
+    WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB device copy), or None.
+    bench.py cannot collect hardware counters itself; the summary says how they were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b_b8_k10.txt")
+    try:
+        for line in open(path):
+            if line.startswith(f"TRAFFIC {kernel} "):
+                return float(line.split()[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -214,6 +228,8 @@ def main():
     ap.add_argument("--cpu-streams", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-scan", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="only run a 1 GiB device copy (yardstick for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -225,6 +241,17 @@ def main():
     from paper_2502_08923_amd import binding as cs
     cs.load_library()
     torch.cuda.set_device(0)
+
+    if args.calib_copy:
+        # plain device copy of known size: the yardstick for the FETCH_SIZE / WRITE_SIZE counters
+        n = 1 << 28                                       # 1 GiB of float32 read, 1 GiB written
+        x = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
+        y = torch.empty_like(x)
+        for _ in range(5):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib_copy_bytes_read": n * 4, "calib_copy_bytes_written": n * 4}))
+        return
 
     st = build_workload(args)
     B, k = st["B"], st["k"]
@@ -298,7 +325,8 @@ def main():
                    "batch": B, "k": k, "gamma": st["gamma"], "kv_len": st["L"], "rows": B * (k + 1)},
         "roofline": {"bound": "hbm", "kernel": "k_attn_mfma (block attention, one layer, all streams)",
                      "achieved": ab["attn_launch"] / attn_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": ab["attn_launch"] / attn_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "frac": ab["attn_launch"] / attn_s / 1e9 / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("k_attn_mfma"),
                      "algorithmic_bytes_per_launch": ab["attn_launch"], "avg_launch_us": attn_s * 1e6},
         "kernels": kern,
         "step": {"algorithmic_GB": step_bytes / 1e9,
