@@ -3,12 +3,15 @@
 // With R = B*(k+1) block rows (88 at batch 8, k = 10) every weight is used R times, far
 // below the ~312 flop/byte ridge of MI355X, so these GEMMs are bound by streaming W from
 // HBM once.  The tuned kernel therefore treats W as the operand that must never be
-// re-read: each wave loads its W rows straight from global memory into MFMA A-operand
-// registers (16 B per lane, 64 contiguous bytes per lane per 128-wide K chunk), while the
-// small X block is staged through LDS and shared by the four waves of a workgroup.
-// v_mfma_f32_16x16x32_bf16 accumulates in float32.  Small-N projections are split along K
-// across workgroups; the float32 partial tiles are summed by the consumer kernel in a
-// fixed order (deterministic, no atomics).
+// re-read: each consumer wave loads its W tiles straight from global memory into MFMA
+// A-operand registers (W is pre-tiled so that a wave load is 1 KB contiguous), while the
+// small X block is staged through LDS by producer waves and shared by the consumers.
+// Operands are float16 (weights converted exactly from bfloat16 when the model is created,
+// activations rounded to float16 by their producers); v_mfma_f32_16x16x32_f16 accumulates
+// in float32.  Small-N projections are split along K across workgroups; the float32 partial
+// tiles are summed by the consumer kernel in a fixed order (deterministic, no atomics).
+#include <stdlib.h>
+
 #include "cs_common.h"
 
 // -------------------------------------------------------------------------------------
@@ -45,11 +48,11 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const XT* __restrict__ X,
 // -------------------------------------------------------------------------------------
 #define GEMM_KC 128                       // K elements per pipeline stage
 #define GEMM_LDS_ROW (GEMM_KC * 2 + 16)   // bytes per X row in LDS (padded)
-#define GEMM_DEPTH 4                      // W stages in flight per consumer wave
+#define GEMM_RING_TILES 8                 // W tile-chunks (4 KB each) in flight per consumer wave
 #define GEMM_THREADS 384                  // 4 consumer waves + 2 producer waves
 
 // The workgroup is specialised by wave.  Waves 0..3 (consumers) stream W: each owns MT
-// 16-row tiles, keeps GEMM_DEPTH K-chunks of them in flight in registers and multiplies.
+// 16-row tiles, keeps 8/MT K-chunks of them (32 KB) in flight in registers and multiplies.
 // Waves 4 and 5 (producers) stage the X block of every chunk (half of its rows each)
 // through registers into a double-buffered LDS tile.  The hardware counts outstanding loads per wave and retires
 // them in order, so a wave that waits for a near X load would also drain its far W loads;
@@ -142,6 +145,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+    constexpr int GEMM_DEPTH = GEMM_RING_TILES / MT;            // K chunks in flight
     f16x8 a[GEMM_DEPTH][MT][4];
     const int last = nchunks - 1;
     auto load_w = [&](f16x8 (*dst)[4], int c) {
@@ -230,10 +234,12 @@ static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int
     dim3 grid((unsigned)cs_ceil_div(N, 64 * MT), (unsigned)cs_ceil_div(K, Ks),
               (unsigned)cs_ceil_div(R, 16 * NT));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
-    if (mode == CS_GEMM_STORE)
+    if (mode == CS_GEMM_STORE) {
         k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks);
-    else
-        k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks);
+    } else {
+        if constexpr (MT % 2 == 0)
+            k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks);
+    }
     cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_mfma");
 }
@@ -299,17 +305,29 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     }
     CS_REQUIRE(mfma_shape_ok(N, K) && (mode != CS_GEMM_SWIGLU || N % 32 == 0), CS_E_UNSUPPORTED,
                "bf16 GEMM needs N %% 16 == 0 and K %% 128 == 0 (N=%d K=%d)", N, K);
-    // Split K until there are about two workgroups per compute unit, keeping at least four
-    // K chunks per split so the load pipeline has something to overlap.
-    const int MT = 2;
-    const int n_tiles = (int)cs_ceil_div(N, 64 * MT);
+    // Shape of the launch.  One workgroup (6 waves, ~250 registers) fills a compute unit.  Wide
+    // projections (gate/up, lm_head) have enough 128-row tiles.  Narrow ones (q/k/v, o, down)
+    // are split along K, but only until about 3/4 of the compute units have a workgroup:
+    // measured at the 8B shapes, more splits cost more in partial-tile traffic and fixed
+    // per-workgroup latency than they gain in parallelism (q/k/v 4, o 8, down 8 splits).
     const int r_blocks = (int)cs_ceil_div(R, 96);
-    int ksplit = 1;
+    int MT = 2, ksplit = 1;
     if (allow_split && mode == CS_GEMM_STORE) {
+        const int n_tiles = (int)cs_ceil_div(N, 128);
         const int max_split = K / (4 * GEMM_KC) > 0 ? K / (4 * GEMM_KC) : 1;
-        while (n_tiles * r_blocks * ksplit < 512 && ksplit * 2 <= max_split) ksplit *= 2;
-        while (ksplit > 1 && (size_t)ksplit * R * N > m->part_floats) ksplit /= 2;
+        while (n_tiles * r_blocks * ksplit < 192 && ksplit * 2 <= max_split) ksplit *= 2;
     }
+    static const char* dbg = getenv("CS_GEMM_DEBUG");      // "MT,ksplit" override for tuning runs
+    if (dbg && allow_split && mode == CS_GEMM_STORE) {
+        int mt = 0, ks = 0;
+        if (sscanf(dbg, "%d,%d", &mt, &ks) == 2 && (mt == 1 || mt == 2) && ks >= 1 && ks <= 64) {
+            MT = mt;
+            ksplit = ks;
+        }
+    }
+    // the partial tiles must fit the workspace whatever chose the split
+    while (ksplit > 1 && (size_t)ksplit * R * N > m->part_floats) ksplit /= 2;
+    if (ksplit > 1) CS_REQUIRE(allow_split, CS_E_STATE, "K split without a partial-tile buffer");
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     const int nparts = (int)cs_ceil_div(K, Ks);
     if (nparts_out) *nparts_out = nparts;
@@ -317,6 +335,16 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     const f16_t* x = (const f16_t*)X;
     const f16_t* w = (const f16_t*)W;
     f16_t* act = (f16_t*)m->act;
+    if (MT == 1) {
+        switch (rt) {
+            case 1: return launch_mfma<1, 1>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 2: return launch_mfma<1, 2>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 3: return launch_mfma<1, 3>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 4: return launch_mfma<1, 4>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 5: return launch_mfma<1, 5>(x, w, Y, act, R, N, K, mode, nparts, s);
+            default: return launch_mfma<1, 6>(x, w, Y, act, R, N, K, mode, nparts, s);
+        }
+    }
     switch (rt) {
         case 1: return launch_mfma<2, 1>(x, w, Y, act, R, N, K, mode, nparts, s);
         case 2: return launch_mfma<2, 2>(x, w, Y, act, R, N, K, mode, nparts, s);
