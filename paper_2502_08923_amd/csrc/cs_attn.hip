@@ -400,6 +400,254 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     }
 }
 
+// -------------------------------------------------------------------------------------
+// tuned kernel for wide blocks (more than 48 query rows per KV head, e.g. k = 32: 132 rows)
+//
+// Up to FA_QG consumer waves each own one 48-row query group and all walk the same token
+// range; one producer wave streams K and V from HBM once per workgroup and lays them into a
+// three-stage LDS ring in MFMA fragment order, so the KV bytes are read once however many
+// query groups share them.  One barrier per 32-token block hands the stages over.  Every
+// consumer writes its own partial (no in-workgroup merge); k_attn_merge combines the splits.
+// -------------------------------------------------------------------------------------
+#define FA_QG 3
+#define FA_STAGES 3
+#define FA_TEAMS 2          // (FA_QG consumers + 1 producer) per team; two waves per SIMD
+#define FA_LDS_THREADS (64 * (FA_QG + 1) * FA_TEAMS)
+
+template <int HD>
+__global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __restrict__ q,
+                                                              const bf16_t* __restrict__ kc,
+                                                              const bf16_t* __restrict__ vc,
+                                                              const int32_t* __restrict__ kv_len,
+                                                              int rows, int H, int KVH, int64_t cap,
+                                                              int Tw, int nqg, int nqgw, int nsplit,
+                                                              float* __restrict__ po,
+                                                              float* __restrict__ pml) {
+    constexpr int KS = HD / 32, MT = HD / 16;
+    constexpr int QROW = HD * 2 + 16;
+    constexpr int K_BYTES = 2 * KS * 1024, V_BYTES = MT * 1024;
+    constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char stage_all[FA_TEAMS][FA_STAGES][STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char qs[FA_QG][FA_QROWS * QROW];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int team = (tid >> 6) / (FA_QG + 1), wave = (tid >> 6) % (FA_QG + 1);
+    unsigned char (*stage)[STAGE_BYTES] = stage_all[team];
+    const int c = lane & 15, g = lane >> 4;
+    const int qgw = blockIdx.x % nqgw;                  // which group of FA_QG query groups
+    const int split = (blockIdx.x / nqgw) * FA_TEAMS + team;   // each team owns one token range
+    const int kvh = blockIdx.y, b = blockIdx.z;
+    const int G = H / KVH;
+    const int QR = G * rows;
+    const int L = kv_len[b];
+    const int n_tok = L + rows;
+    const int t_begin = min(split * Tw, n_tok);
+    const int t_end = min(n_tok, t_begin + Tw);
+    const int nblocks = (t_end - t_begin + 31) / 32;
+    // both teams pass the same number of barriers: the longer range of the two
+    const int t_begin0 = min((split - team) * Tw, n_tok);
+    const int nblocks_wg = (min(n_tok, t_begin0 + Tw) - t_begin0 + 31) / 32;
+    const bf16_t* __restrict__ K = kc + ((int64_t)b * KVH + kvh) * cap * HD;
+    const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
+
+    // stage the query tiles of all groups of this workgroup
+    for (int idx = tid; idx < FA_QG * FA_QROWS * (HD / 8); idx += FA_LDS_THREADS) {
+        const int grp = idx / (FA_QROWS * (HD / 8));
+        const int rem = idx % (FA_QROWS * (HD / 8));
+        const int row = rem / (HD / 8), seg = rem % (HD / 8);
+        const int n = (qgw * FA_QG + grp) * FA_QROWS + row;
+        bf16x8 v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        if (n < QR) {
+            const int i = n / G, gq = n % G;
+            v = *reinterpret_cast<const bf16x8*>(
+                q + (((int64_t)(b * rows + i)) * H + kvh * G + gq) * HD + seg * 8);
+        }
+        *reinterpret_cast<bf16x8*>(&qs[grp][row * QROW + seg * 16]) = v;
+    }
+
+    const int ktok0 = 8 * (c >> 2) + (c & 3);
+    if (wave == FA_QG) {
+        // ---------------- producer: K/V blocks -> LDS ring ----------------
+        bf16x8 kr[2][2][KS], vr[2][MT];       // two blocks in flight in registers
+        auto load = [&](int slot, int blk) {
+            const int bl = blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0);   // clamped
+            const int t0 = (nblocks > 0 ? t_begin : 0) + bl * 32;
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                const bf16_t* kp = K + (int64_t)(t0 + ktok0 + 4 * a) * HD + g * 8;
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    kr[slot][a][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                vr[slot][mt] = *reinterpret_cast<const bf16x8*>(V + (int64_t)(mt * 16 + c) * cap + t0 + 8 * g);
+        };
+        auto store = [&](int slot, int st, int blk) {
+            const int t0 = (nblocks > 0 ? t_begin : 0) + (blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0)) * 32;
+            unsigned char* sp = stage[st];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    *reinterpret_cast<bf16x8*>(sp + ((a * KS + s) * 64 + lane) * 16) = kr[slot][a][s];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                bf16x8 v = vr[slot][mt];
+                // dead cache rows may hold anything: zero their V so that 0 * garbage stays 0
+                if (t0 + 32 > n_tok) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (t0 + 8 * g + j >= n_tok) v[j] = (bf16_t)0.f;
+                }
+                *reinterpret_cast<bf16x8*>(sp + K_BYTES + (mt * 64 + lane) * 16) = v;
+            }
+        };
+        // an empty range still loads (clamped to block 0 of the cache, always allocated) and
+        // stores into stages nobody reads; the barrier count is the workgroup's, not the team's
+        load(0, 0);
+        load(1, 1);
+        store(0, 0, 0);
+        load(0, 2);
+        __syncthreads();                                   // stage 0 and the query tiles are ready
+        for (int i = 0; i < nblocks_wg; i += 2) {
+            // iteration i: block i+1 (registers slot 1) -> stage (i+1)%3; refill with block i+3
+            store(1, (i + 1) % FA_STAGES, i + 1);
+            load(1, i + 3);
+            __syncthreads();
+            if (i + 1 >= nblocks_wg) break;
+            store(0, (i + 2) % FA_STAGES, i + 2);
+            load(0, i + 4);
+            __syncthreads();
+        }
+        return;
+    }
+
+    // ---------------- consumers: one 48-row query group each ----------------
+    const int qg = qgw * FA_QG + wave;
+    const bool live = qg < nqg;
+    const unsigned char* myq = qs[wave];
+    int qi[FA_NT];
+#pragma unroll
+    for (int nt = 0; nt < FA_NT; ++nt) {
+        const int n = qg * FA_QROWS + nt * 16 + c;
+        qi[nt] = n < QR ? n / G : -1;
+    }
+    f32x4 oacc[MT][FA_NT], lacc[FA_NT];
+#pragma unroll
+    for (int nt = 0; nt < FA_NT; ++nt) {
+        lacc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    float m_run[FA_NT];
+#pragma unroll
+    for (int nt = 0; nt < FA_NT; ++nt) m_run[nt] = -INFINITY;
+    const float scale2 = 1.4426950408889634f / sqrtf((float)HD);
+    const bf16_t one = (bf16_t)1.0f;
+    const bf16x8 ones = (bf16x8){one, one, one, one, one, one, one, one};
+
+    auto compute = [&](const unsigned char* sp, int t0, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        f32x4 sacc[2][FA_NT];
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            f32x4 z0 = (f32x4){0.f, 0.f, 0.f, 0.f}, z1 = z0;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 qb = *reinterpret_cast<const bf16x8*>(myq + (nt * 16 + c) * QROW + s * 64 + g * 16);
+                const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(sp + ((0 * KS + s) * 64 + lane) * 16);
+                const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(sp + ((1 * KS + s) * 64 + lane) * 16);
+                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb, z0, 0, 0, 0);
+                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb, z1, 0, 0, 0);
+            }
+            sacc[0][nt] = z0;
+            sacc[1][nt] = z1;
+        }
+        bool moved = false;
+        float alpha[FA_NT];
+        bf16x8 pb[FA_NT];
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            float sv[8];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float sc = sacc[a][nt][j];
+                    if (TAIL && (t0 + 8 * g + 4 * a + j > L + qi[nt])) sc = -INFINITY;
+                    sv[4 * a + j] = sc;
+                }
+            float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
+            mx = fmaxf(fmaxf(mx, sv[3]), sv[4]);
+            mx = fmaxf(fmaxf(mx, sv[5]), fmaxf(sv[6], sv[7]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx *= scale2;
+            const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;      // see k_attn_mfma
+            const float m_new = up ? mx : m_run[nt];
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - m_safe) : 1.0f;
+            moved |= up;
+            m_run[nt] = m_new;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                pb[nt][j] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(sv[j], scale2, -m_safe));
+        }
+        if (__any(moved)) {
+#pragma unroll
+            for (int nt = 0; nt < FA_NT; ++nt) {
+                asm volatile("" : "+a"(lacc[nt]));
+                lacc[nt] *= alpha[nt];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    asm volatile("" : "+a"(oacc[mt][nt]));
+                    oacc[mt][nt] *= alpha[nt];
+                }
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sp + K_BYTES + (mt * 64 + lane) * 16);
+#pragma unroll
+            for (int nt = 0; nt < FA_NT; ++nt)
+                oacc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[nt], oacc[mt][nt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt) {
+            lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[nt], lacc[nt], 0, 0, 0);
+            asm volatile("" : "+a"(lacc[nt]));
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+a"(oacc[mt][nt]));
+        }
+    };
+    const std::integral_constant<bool, false> main_tag;
+    const std::integral_constant<bool, true> tail_tag;
+
+    __syncthreads();                                       // matches the producer's first barrier
+    for (int i = 0; i < nblocks_wg; ++i) {
+        const int t0 = t_begin + i * 32;
+        if (live && i < nblocks) {
+            if (t0 + 32 > L) compute(stage[i % FA_STAGES], t0, tail_tag);
+            else compute(stage[i % FA_STAGES], t0, main_tag);
+        }
+        __syncthreads();
+    }
+    if (!live) return;
+
+    const int64_t item = ((int64_t)b * KVH + kvh) * nqg + qg;
+    float* __restrict__ o_out = po + (item * nsplit + split) * FA_QROWS * HD;
+    float* __restrict__ ml_out = pml + (item * nsplit + split) * FA_QROWS * 2;
+#pragma unroll
+    for (int nt = 0; nt < FA_NT; ++nt) {
+        const int n = nt * 16 + c;
+        if (g == 0) { ml_out[n * 2] = m_run[nt]; ml_out[n * 2 + 1] = lacc[nt][0]; }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            *reinterpret_cast<f32x4*>(o_out + (int64_t)n * HD + mt * 16 + 4 * g) = oacc[mt][nt];
+    }
+}
+
 // out[r][h*HD + d] = sum_s 2^(m_s - M) O_s[d] / sum_s 2^(m_s - M) l_s  over the splits
 #define FA_MAX_SPLIT 64
 template <typename OT>
@@ -461,9 +709,44 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const int QR = G * rows;
     const int nqg = (int)cs_ceil_div(QR, FA_QROWS);
     const int64_t n_tok_ub = len_ub + rows;
+    const bf16_t* kc = (const bf16_t*)kv->k + layer * per_layer;
+    const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
+    int nsplit;
+    if (nqg > 1) {
+        // wide block: consumers share the K/V stream of one producer wave through LDS
+        const int nqgw = (int)cs_ceil_div(nqg, FA_QG);
+        nsplit = FA_TEAMS * (int)cs_ceil_div(256, (int64_t)B * KVH * nqgw);
+        const int max_split = (int)cs_ceil_div(n_tok_ub, 256);
+        if (nsplit > max_split) nsplit = max_split;
+        if (nsplit > FA_MAX_SPLIT) nsplit = FA_MAX_SPLIT;
+        if (nsplit < 1) nsplit = 1;
+        const int Tw = (int)cs_round_up(cs_ceil_div(n_tok_ub, nsplit), 32);
+        nsplit = (int)cs_round_up(cs_ceil_div(n_tok_ub, Tw), FA_TEAMS);
+        const size_t items = (size_t)B * KVH * nqg * nsplit;
+        CS_REQUIRE(items * FA_QROWS * (hd + 2) <= m->attn_part_floats, CS_E_CAPACITY,
+                   "attention workspace too small");
+        float* po = m->attn_part;
+        float* pml = m->attn_part + items * FA_QROWS * hd;
+        dim3 grid(nsplit / FA_TEAMS * nqgw, KVH, B);
+        const int pa = cs_prof_begin(CS_PROF_ATTN, s);
+        if (hd == 128)
+            k_attn_lds<128><<<grid, FA_LDS_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows,
+                                                             H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, po, pml);
+        else
+            k_attn_lds<64><<<grid, FA_LDS_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows,
+                                                            H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, po, pml);
+        cs_prof_end(pa, s);
+        CS_TRY(cs_launch_ok("k_attn_lds"));
+        dim3 mgrid(QR, KVH, B);
+        const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
+        k_attn_merge<f16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
+                                                              (f16_t*)m->xn);
+        cs_prof_end(pm, s);
+        return cs_launch_ok("k_attn_merge");
+    }
     // The kernel keeps one wave per SIMD (register budget), so one workgroup fills a compute
     // unit: aim at one workgroup per compute unit, at least 128 tokens per wave.
-    int nsplit = (int)cs_ceil_div(256, (int64_t)B * KVH * nqg);
+    nsplit = (int)cs_ceil_div(256, (int64_t)B * KVH * nqg);
     const int max_split = (int)cs_ceil_div(n_tok_ub, 4 * 128);
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit > FA_MAX_SPLIT) nsplit = FA_MAX_SPLIT;
@@ -476,8 +759,6 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
                "attention workspace too small (%zu > %zu floats)", need, m->attn_part_floats);
     float* po = m->attn_part;
     float* pml = m->attn_part + items * FA_QROWS * hd;
-    const bf16_t* kc = (const bf16_t*)kv->k + layer * per_layer;
-    const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
     dim3 grid(nsplit * nqg, KVH, B);
     const int pa = cs_prof_begin(CS_PROF_ATTN, s);
     if (hd == 128)
