@@ -233,176 +233,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
     }
 }
 
-// -------------------------------------------------------------------------------------
-// tuned kernel for many rows (R > 96, e.g. batch 16 x (k = 32) + 1 = 528 rows)
-//
-// Here the projections are compute-bound (528 flop per weight byte), so the tile is chosen
-// for operand reuse instead of weight streaming: a workgroup of eight waves (4 x 2) owns a
-// 256 (W rows) x 288 (X rows) output tile, each wave 64 x 144 (MT = 4, NT = 9: one LDS
-// fragment read per four MFMAs).  Two waves share a SIMD, so one wave's waits overlap the
-// other's MFMAs.  X goes through a double-buffered LDS tile (2 x 77 KB), loaded one chunk
-// ahead; W comes straight from global memory in fragment order, each K step refilled right
-// after it has been multiplied (one chunk ahead).  X loads are issued before the W loads of
-// the same age, so waiting for X never drains younger W loads (a wave's loads retire in order).
-// -------------------------------------------------------------------------------------
-#define BG_MT 4
-#define BG_NT 9
-#define BG_THREADS 512
-#define BG_XROWS (16 * BG_NT * 2)
-#define BG_WROWS (16 * BG_MT * 4)
-#define BG_XLOADS (BG_XROWS * 16 / BG_THREADS)     // 16-byte segments per thread per chunk
-
-template <int MODE>
-__global__ __launch_bounds__(BG_THREADS) void k_gemm_big(const f16_t* __restrict__ X,
-                                                         const f16_t* __restrict__ W,
-                                                         float* __restrict__ Y,
-                                                         f16_t* __restrict__ act, int R, int N, int K,
-                                                         int Ks, int RB) {
-    __shared__ __attribute__((aligned(16))) unsigned char xs[2][BG_XROWS * GEMM_LDS_ROW];
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int wn = wave & 3, wm = wave >> 2;
-    const int lrow = lane & 15, g = lane >> 4;
-    const int k_begin = blockIdx.y * Ks;
-    const int k_end = min(K, k_begin + Ks);
-    const int nchunks = (k_end - k_begin) / GEMM_KC;
-    const int last = nchunks - 1;
-    // same XCD-aware (W tile, X row block) mapping as k_gemm_mfma
-    const int grp = blockIdx.x / (8 * RB), rem = blockIdx.x % (8 * RB);
-    const int w_tile = grp * 8 + (rem & 7);
-    if (w_tile * BG_WROWS >= N) return;
-    const int r_base = (rem >> 3) * BG_XROWS;
-
-    // X staging: thread -> segment (tid & 15) of rows (tid >> 4) + 32*i.  Rows past R are
-    // clamped to the last row: they only feed output rows that are never stored.
-    const int seg = tid & 15, row0 = tid >> 4;
-    int xoff[BG_XLOADS];                              // 32-bit element offsets: R*K < 2^31 (host check)
-#pragma unroll
-    for (int i = 0; i < BG_XLOADS; ++i) {
-        int r = r_base + row0 + 32 * i;
-        r = r < R ? r : R - 1;
-        xoff[i] = r * K + k_begin + seg * 8;
-    }
-    const int dst0 = row0 * GEMM_LDS_ROW + seg * 16;
-    f16x8 xr[BG_XLOADS];
-    auto load_x = [&](int c) {
-        c = c < last ? c : last;
-#pragma unroll
-        for (int i = 0; i < BG_XLOADS; ++i)
-            xr[i] = *reinterpret_cast<const f16x8*>(X + (xoff[i] + c * GEMM_KC));
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < BG_XLOADS; ++i)
-            *reinterpret_cast<f16x8*>(&xs[buf][dst0 + i * 32 * GEMM_LDS_ROW]) = xr[i];
-    };
-
-    const int n_wave = w_tile * BG_WROWS + wn * 16 * BG_MT;
-    const int n_tiles = N >> 4;
-    const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;
-    const f16_t* wtile[BG_MT];
-#pragma unroll
-    for (int mt = 0; mt < BG_MT; ++mt) {
-        int t = (n_wave >> 4) + mt;
-        t = t < n_tiles ? t : n_tiles - 1;
-        wtile[mt] = W + (k_begin / GEMM_KC) * chunk_stride + (int64_t)t * 4 * 512 + lane * 8;
-    }
-    f16x8 a[BG_MT][4];
-    auto load_w_step = [&](int c, int st) {
-        c = c < last ? c : last;
-#pragma unroll
-        for (int mt = 0; mt < BG_MT; ++mt)
-            a[mt][st] = *reinterpret_cast<const f16x8*>(wtile[mt] + c * chunk_stride + st * 512);
-    };
-    f32x4 acc[BG_MT][BG_NT];
-#pragma unroll
-    for (int mt = 0; mt < BG_MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < BG_NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-    // multiply chunk `c` (W fragments in a[], X in LDS buffer u); each K step of a[] is refilled
-    // with the next chunk as soon as it has been used.  X fragments are read two ahead.
-    auto compute = [&](int u, int c) {
-        const unsigned char* xb = xs[u] + (wm * 16 * BG_NT + lrow) * GEMM_LDS_ROW + g * 16;
-        auto frag = [&](int f) {
-            return *reinterpret_cast<const f16x8*>(xb + (f % BG_NT) * 16 * GEMM_LDS_ROW + (f / BG_NT) * 64);
-        };
-        f16x8 bq[3];
-        bq[0] = frag(0);
-        bq[1] = frag(1);
-#pragma unroll
-        for (int f = 0; f < 4 * BG_NT; ++f) {
-            if (f + 2 < 4 * BG_NT) bq[(f + 2) % 3] = frag(f + 2);
-            const int st = f / BG_NT, nt = f % BG_NT;
-#pragma unroll
-            for (int mt = 0; mt < BG_MT; ++mt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt][st], bq[f % 3], acc[mt][nt], 0, 0, 0);
-            if (nt == BG_NT - 1) load_w_step(c + 1, st);
-        }
-    };
-
-    load_x(0);
-#pragma unroll
-    for (int st = 0; st < 4; ++st) load_w_step(0, st);
-    store_x(0);
-    load_x(1);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        store_x((c + 1) & 1);         // chunk c+1, loaded one iteration ago
-        load_x(c + 2);
-        compute(c & 1, c);
-        __syncthreads();
-    }
-
-    // epilogue: acc[mt][nt][j] = Y[r_base + (wm*NT + nt)*16 + lrow][n_wave + mt*16 + 4g + j]
-    if (MODE == CS_GEMM_STORE) {
-        float* __restrict__ y = Y + (int64_t)blockIdx.y * R * N;
-#pragma unroll
-        for (int nt = 0; nt < BG_NT; ++nt) {
-            const int r = r_base + (wm * BG_NT + nt) * 16 + lrow;
-            if (r >= R) continue;
-#pragma unroll
-            for (int mt = 0; mt < BG_MT; ++mt) {
-                const int n = n_wave + mt * 16 + 4 * g;
-                if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
-            }
-        }
-    } else {
-        const int F = N / 2;
-#pragma unroll
-        for (int nt = 0; nt < BG_NT; ++nt) {
-            const int r = r_base + (wm * BG_NT + nt) * 16 + lrow;
-            if (r >= R) continue;
-#pragma unroll
-            for (int mp = 0; mp < BG_MT / 2; ++mp) {
-                const int n = n_wave + mp * 32;
-                if (n >= N) continue;
-                const int f = n / 2 + 4 * g;
-                f16x4 o;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
-                    o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
-                }
-                *reinterpret_cast<f16x4*>(act + (int64_t)r * F + f) = o;
-            }
-        }
-    }
-}
-
-static int launch_big(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K, int mode,
-                      int ksplit, hipStream_t s) {
-    CS_REQUIRE((int64_t)R * K < ((int64_t)1 << 31), CS_E_UNSUPPORTED, "R*K too large for the many-row GEMM");
-    const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
-    const int RB = (int)cs_ceil_div(R, BG_XROWS);
-    dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, BG_WROWS), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
-    const int pg = cs_prof_begin(CS_PROF_GEMM, s);
-    if (mode == CS_GEMM_STORE) k_gemm_big<CS_GEMM_STORE><<<grid, BG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
-    else k_gemm_big<CS_GEMM_SWIGLU><<<grid, BG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
-    cs_prof_end(pg, s);
-    return cs_launch_ok("k_gemm_big");
-}
-
 template <int MT, int NT>
 static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K,
                        int mode, int ksplit, hipStream_t s) {
@@ -486,11 +316,13 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     // are split along K, but only until about 3/4 of the compute units have a workgroup:
     // measured at the 8B shapes, more splits cost more in partial-tile traffic and fixed
     // per-workgroup latency than they gain in parallelism (q/k/v 4, o 8, down 8 splits).
-    const bool big = R > 96;          // compute-bound regime: k_gemm_big
-    const int r_blocks = big ? (int)cs_ceil_div(R, BG_XROWS) : 1;
+    // A workgroup takes up to 96 block rows; more rows are split into equal row blocks whose
+    // workgroups share each W tile through one XCD's L2 (see the mapping in the kernel).
+    const int rt_total = (int)cs_ceil_div(R, 16);
+    const int r_blocks = (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;
     if (allow_split && mode == CS_GEMM_STORE) {
-        const int n_tiles = (int)cs_ceil_div(N, big ? BG_WROWS : 128);
+        const int n_tiles = (int)cs_ceil_div(N, 128);
         const int max_split = K / (4 * GEMM_KC) > 0 ? K / (4 * GEMM_KC) : 1;
         while (n_tiles * r_blocks * ksplit < 192 && ksplit * 2 <= max_split) ksplit *= 2;
     }
@@ -500,11 +332,10 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     const int nparts = (int)cs_ceil_div(K, Ks);
     if (nparts_out) *nparts_out = nparts;
-    const int rt = (int)cs_ceil_div(R < 96 ? R : 96, 16);
+    const int rt = (int)cs_ceil_div(rt_total, r_blocks);
     const f16_t* x = (const f16_t*)X;
     const f16_t* w = (const f16_t*)W;
     f16_t* act = (f16_t*)m->act;
-    if (big) return launch_big(x, w, Y, act, R, N, K, mode, nparts, s);
     switch (rt) {
         case 1: return launch_mfma<2, 1>(x, w, Y, act, R, N, K, mode, nparts, s);
         case 2: return launch_mfma<2, 2>(x, w, Y, act, R, N, K, mode, nparts, s);

@@ -1,0 +1,152 @@
+"""Block-size, gamma and match-policy sweeps on one MI355X (the paper's Sec. 5.2 / Table 4 and
+Sec. 5.1 questions, asked of this implementation on synthetic data).
+
+    python -m paper_2502_08923_amd.sweep [--layers N] [--json out.json]
+
+Two measurements are combined:
+
+1. Step cost: one whole cs_step (scan + verify forward + accept + rollback) of the 8B-shape
+   workload (batch 8, 18431 cached rows) timed for copy blocks k = 0 (plain decoding through
+   the same kernels) .. 100.
+2. Acceptance: a synthetic self-correction dialogue (three versions of a 1024-token answer,
+   each the previous one with 5 % token edits) is replayed through the library's match
+   search alone; the "target model" is the third version itself, so a draft token is accepted
+   iff it equals the next token of that version.  This gives tokens emitted per step for
+   every (gamma, k, policy) without any trained model.  The rightmost policy copies from the
+   second version (one round of edits away), the first-match policy from the original (two).
+
+emitted tokens/s = batch * (mean tokens per step) / (step time); the speed-up column is
+relative to k = 0.  The acceptance side is a projection for that edit law, not a property of
+a language model.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def replay_acceptance(cs, synth, gamma: int, k: int, policy: str, streams=(0, 1, 2, 3)):
+    """Mean tokens emitted per step and mean accepted drafts per attempt when the second turn
+    of the multi-turn workload is decoded with CopySpec and the target always emits the
+    edited answer."""
+    import numpy as np
+    tot_steps = tot_tokens = attempts = accepted = 0
+    for s in streams:
+        g = synth.multiturn_replay(s)
+        ctx, truth = g["context"].tolist(), g["truth"].tolist()
+        seq = ctx + truth[:gamma]                 # the first gamma tokens are generated plainly
+        pos = gamma
+        while pos < len(truth):
+            tot_steps += 1
+            if k > 0:
+                _, _, draft = cs.cs_find_match_ex(np.asarray(seq, dtype=np.int32), gamma, k, policy)
+            else:
+                draft = []
+            draft = draft[:len(truth) - pos - 1]
+            tau = 0
+            while tau < len(draft) and draft[tau] == truth[pos + tau]:
+                tau += 1
+            if draft:
+                attempts += 1
+                accepted += tau
+            emit = min(tau + 1, len(truth) - pos)
+            seq.extend(truth[pos:pos + emit])
+            pos += emit
+            tot_tokens += emit
+    return tot_tokens / tot_steps, (accepted / attempts if attempts else 0.0)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--layers", type=int, default=0, help="depth override (0 = full 32 layers)")
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--ks", default="0,5,10,20,32,50,100")
+    ap.add_argument("--json", default="")
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2502_08923_amd import binding as cs
+    import bench
+
+    cs.load_library()
+    ks = [int(x) for x in args.ks.split(",")]
+    kmax = max(ks)
+
+    class A:  # the benchmark's workload builder, with room for the largest block
+        shape, layers, batch, k, gamma, doc, hist = "8b", args.layers, 8, kmax, 3, 2048, 16384
+    st = bench.build_workload(A)
+    B = st["B"]
+
+    rows = []
+    for k in ks:
+        st["k"] = k
+        for _ in range(2):
+            bench.one_step(st, cs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            bench.one_step(st, cs)
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / args.steps
+        rows.append({"k": k, "ms_per_step": t * 1e3})
+        print(f"[sweep] k={k:3d}: {t * 1e3:7.2f} ms/step", file=sys.stderr, flush=True)
+    base = rows[0]["ms_per_step"] if ks[0] == 0 else None
+
+    table = []
+    for gamma in (2, 3, 5, 10):
+        for policy in ("rightmost", "first"):
+            for r in rows:
+                k = r["k"]
+                tps, tau = replay_acceptance(cs, synth, gamma, k, policy)
+                emitted = B * tps / (r["ms_per_step"] * 1e-3)
+                table.append({"gamma": gamma, "policy": policy, "k": k, "ms_per_step": r["ms_per_step"],
+                              "tokens_per_step": tps, "accepted_per_attempt": tau,
+                              "emitted_tokens_per_s": emitted,
+                              "speedup_vs_plain": (emitted / (B / (base * 1e-3))) if base else None})
+
+    # match-scan cost by gamma and policy on the 64 x 32768 scan configuration
+    hs = np.stack([synth.history_cfg2(s)["tokens"] for s in range(64)])
+    d_hist = torch.from_numpy(hs).to("cuda:0")
+    d_len = torch.full((64,), 32768, dtype=torch.int32, device="cuda:0")
+    scan = []
+    for gamma in (1, 2, 3, 5, 10, 16):
+        for policy in ("rightmost", "first"):
+            cs.cs_find_match_batch_dev(d_hist, d_len, gamma, 10, policy)
+            torch.cuda.synchronize()
+            cs.cs_profile_enable(["scan"])
+            cs.cs_profile_reset()
+            for _ in range(50):
+                cs.cs_find_match_batch_dev(d_hist, d_len, gamma, 10, policy)
+            ms, n = cs.cs_profile_read("scan")
+            cs.cs_profile_enable([])
+            scan.append({"gamma": gamma, "policy": policy, "kernel_us": ms / n * 1e3})
+
+    out = {"step_cost": rows, "projection": table, "scan": scan,
+           "workload": f"llama-8b shape x{st['shape'].n_layers} layers, batch {B}, KV {st['L']}"}
+    if args.json:
+        with open(args.json, "w") as f:
+            json.dump(out, f, indent=1)
+    print("| gamma | policy | k | ms/step | tokens/step | accepted/attempt | emitted tok/s | vs k=0 |")
+    print("|---|---|---|---|---|---|---|---|")
+    for r in table:
+        sp = f"{r['speedup_vs_plain']:.2f}x" if r["speedup_vs_plain"] else "-"
+        print(f"| {r['gamma']} | {r['policy']} | {r['k']} | {r['ms_per_step']:.2f} | {r['tokens_per_step']:.2f} | "
+              f"{r['accepted_per_attempt']:.2f} | {r['emitted_tokens_per_s']:.0f} | {sp} |")
+    print()
+    print("| gamma | policy | scan kernel us (64 x 32768 tokens) |")
+    print("|---|---|---|")
+    for r in scan:
+        print(f"| {r['gamma']} | {r['policy']} | {r['kernel_us']:.2f} |")
+
+
+if __name__ == "__main__":
+    main()

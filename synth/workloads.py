@@ -309,3 +309,23 @@ def history_cfg5(stream: int, n: int = 65536, vocab: int = 128256, answer: int =
     m = a + j - gamma
     return {"tokens": h, "first_match": m, "rightmost_match": m,
             "spans": [(n - j, a, j)], "gamma": gamma, "k": k, "edits": int(edit.sum())}
+
+
+def multiturn_replay(stream: int, answer: int = 1024, filler: int = 1024, vocab: int = 128256,
+                     edit_rate: float = 0.05, turns: int = 3) -> dict:
+    """Self-correction stand-in for acceptance replays: `turns` versions of one answer, each the
+    previous version with i.i.d. token substitutions at `edit_rate`, separated by random filler.
+    "context" holds everything up to the start of the last version, "truth" is the last
+    version (what a faithful target model would emit next)."""
+    rng = _rng(seed_for(5, 100 + stream))
+    draw = lambda m: rng.integers(0, vocab, m, dtype=np.int64).astype(np.int32)
+    ver = draw(answer)
+    parts = [draw(filler), ver]
+    for _ in range(turns - 1):
+        nxt = ver.copy()
+        edit = rng.random(answer) < edit_rate
+        nxt[edit] = draw(answer)[edit]
+        parts += [draw(filler), nxt]
+        ver = nxt
+    return {"context": np.concatenate(parts[:-1]), "truth": parts[-1]}
+

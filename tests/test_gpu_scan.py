@@ -113,3 +113,25 @@ def test_deterministic_repeat():
     b = cs.cs_find_match_batch_dev(d_hist, d_len, 3, 10)
     torch.cuda.synchronize()
     assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+@pytest.mark.parametrize("policy", ["rightmost", "first"])
+def test_acceptance_replay_matches_oracle(policy):
+    """The gamma/k/policy sweep replays a synthetic self-correction dialogue through the library's
+    match search; the same replay through the oracle's search must emit the same number of
+    tokens per step (Sec. 5.1, Sec. 5.2: the quantities those sweeps vary)."""
+    from paper_2502_08923_amd import sweep
+
+    class OracleSearch:
+        @staticmethod
+        def cs_find_match_ex(hist, gamma, k, pol):
+            return orc.find_match_np(np.asarray(hist), gamma, k, pol)
+
+    for gamma, k in [(2, 5), (3, 10), (5, 32)]:
+        got = sweep.replay_acceptance(cs, synth, gamma, k, policy, streams=(0,))
+        want = sweep.replay_acceptance(OracleSearch, synth, gamma, k, policy, streams=(0,))
+        assert got == want, (gamma, k, policy, got, want)
+    # the newest version of the answer is the better copy source
+    r = sweep.replay_acceptance(OracleSearch, synth, 3, 10, "rightmost", streams=(0,))
+    f = sweep.replay_acceptance(OracleSearch, synth, 3, 10, "first", streams=(0,))
+    assert r[0] > f[0]
