@@ -233,6 +233,174 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
     }
 }
 
+// -------------------------------------------------------------------------------------
+// tuned kernel for many rows (compute-bound blocks, e.g. batch 16 x (k = 32) + 1 = 528 rows)
+//
+// With hundreds of block rows the projections are bound by the matrix cores and by the
+// bandwidth between L2 and the compute units, so the tile is chosen for operand reuse: a
+// workgroup of eight waves (4 x 2) owns a 256 (W rows) x 32*NT (X rows) output tile, each
+// wave 64 x 16*NT.  Both operands go through LDS, every element fetched from L2 once per
+// workgroup.  LDS holds them in MFMA fragment order (1 KB blocks of 16 rows x 32 k, lane l's
+// 16 bytes at offset 16*l), so fragment reads and staging writes are conflict-free without
+// padding; the pre-tiled W is already stored that way in memory.  K advances 64 at a time
+// through two LDS stages: the loads of chunk c+2 are issued after chunk c+1 has been
+// written to LDS and stay in flight during the whole multiply of chunk c+1.
+// -------------------------------------------------------------------------------------
+#define TG_THREADS 512
+#define TG_KC 64
+#define TG_WROWS 256
+
+template <int NT, int MODE>
+__global__ __launch_bounds__(TG_THREADS) void k_gemm_tile(const f16_t* __restrict__ X,
+                                                          const f16_t* __restrict__ W,
+                                                          float* __restrict__ Y,
+                                                          f16_t* __restrict__ act, int R, int N, int K,
+                                                          int Ks, int RB) {
+    constexpr int XBLK = 2 * NT * 2;                 // X blocks per stage (2*NT row tiles x 2 K steps)
+    constexpr int NXLD = (XBLK + 7) / 8;             // X loads per thread per chunk
+    constexpr int STAGE = (32 + XBLK) * 1024;        // 32 W blocks (16 row tiles x 2 K steps) + X
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wn = wave & 3, wm = wave >> 2;
+    const int lrow = lane & 15, g = lane >> 4;
+    const int k_begin = blockIdx.y * Ks;             // multiple of 128
+    const int k_end = min(K, k_begin + Ks);
+    const int nchunks = (k_end - k_begin) / TG_KC;
+    const int last = nchunks - 1;
+    // same XCD-aware (W tile, X row block) mapping as k_gemm_mfma
+    const int grp = blockIdx.x / (8 * RB), rem = blockIdx.x % (8 * RB);
+    const int w_tile = grp * 8 + (rem & 7);
+    if (w_tile * TG_WROWS >= N) return;
+    const int r_base = (rem >> 3) * 32 * NT;
+    const int n_tiles = N >> 4;
+    const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;    // elements per 128-wide K slab of W
+
+    // Staging plan: wave w copies W blocks w, w+8, w+16, w+24 and X blocks w, w+8, ... of every
+    // chunk.  W block j = (row tile j/2, K step j%2) is 1 KB contiguous in memory.  X block j is
+    // gathered: lane l fetches 16 bytes of row (l % 16) at K group l / 16.  Indices past the end
+    // are clamped (the copy is repeated, or feeds output rows that are never stored).
+    int woff[4], xoff[NXLD], xdst[NXLD];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = wave + 8 * i;
+        int t = w_tile * 16 + (j >> 1);
+        t = t < n_tiles ? t : n_tiles - 1;
+        woff[i] = (t * 4 + (j & 1)) * 512 + lane * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < NXLD; ++i) {
+        int j = wave + 8 * i;
+        j = j < XBLK ? j : XBLK - 1;
+        int r = r_base + (j >> 1) * 16 + lrow;
+        r = r < R ? r : R - 1;
+        xoff[i] = r * K + k_begin + (j & 1) * 32 + g * 8;       // R*K < 2^31 (host check)
+        xdst[i] = (32 + j) * 1024 + lane * 16;
+    }
+    const f16_t* wbase = W + (int64_t)(k_begin / GEMM_KC) * chunk_stride;
+    f16x8 wr[4], xr[NXLD];
+    auto load = [&](int c) {
+        c = c < last ? c : last;
+        const f16_t* wc = wbase + (int64_t)(c >> 1) * chunk_stride + (c & 1) * 1024;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wr[i] = *reinterpret_cast<const f16x8*>(wc + woff[i]);
+#pragma unroll
+        for (int i = 0; i < NXLD; ++i) xr[i] = *reinterpret_cast<const f16x8*>(X + (xoff[i] + c * TG_KC));
+    };
+    auto store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<f16x8*>(&lds[buf][(wave + 8 * i) * 1024 + lane * 16]) = wr[i];
+#pragma unroll
+        for (int i = 0; i < NXLD; ++i) *reinterpret_cast<f16x8*>(&lds[buf][xdst[i]]) = xr[i];
+    };
+
+    f32x4 acc[4][NT];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int buf) {
+        const unsigned char* ab = lds[buf] + (wn * 4 * 2) * 1024 + lane * 16;
+        const unsigned char* bb = lds[buf] + (32 + wm * NT * 2) * 1024 + lane * 16;
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            f16x8 a[4];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) a[mt] = *reinterpret_cast<const f16x8*>(ab + (mt * 2 + st) * 1024);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const f16x8 b = *reinterpret_cast<const f16x8*>(bb + (nt * 2 + st) * 1024);
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, acc[mt][nt], 0, 0, 0);
+            }
+        }
+    };
+
+    load(0);
+    store(0);
+    load(1);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        compute(c & 1);
+        store((c + 1) & 1);          // chunk c+1; that buffer was last read while multiplying chunk c-1
+        load(c + 2);
+        __syncthreads();
+    }
+
+    // epilogue: acc[mt][nt][j] = Y[r_base + (wm*NT + nt)*16 + lrow][n_wave + mt*16 + 4g + j]
+    const int n_wave = w_tile * TG_WROWS + wn * 64;
+    if (MODE == CS_GEMM_STORE) {
+        float* __restrict__ y = Y + (int64_t)blockIdx.y * R * N;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int r = r_base + (wm * NT + nt) * 16 + lrow;
+            if (r >= R) continue;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const int n = n_wave + mt * 16 + 4 * g;
+                if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
+            }
+        }
+    } else {
+        const int F = N / 2;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int r = r_base + (wm * NT + nt) * 16 + lrow;
+            if (r >= R) continue;
+#pragma unroll
+            for (int mp = 0; mp < 2; ++mp) {
+                const int n = n_wave + mp * 32;
+                if (n >= N) continue;
+                const int f = n / 2 + 4 * g;
+                f16x4 o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
+                    o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
+                }
+                *reinterpret_cast<f16x4*>(act + (int64_t)r * F + f) = o;
+            }
+        }
+    }
+}
+
+template <int NT>
+static int launch_tile(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K, int mode,
+                       int ksplit, hipStream_t s) {
+    CS_REQUIRE((int64_t)R * K < ((int64_t)1 << 31), CS_E_UNSUPPORTED, "R*K too large for the many-row GEMM");
+    const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
+    const int RB = (int)cs_ceil_div(R, 32 * NT);
+    dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, TG_WROWS), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
+    const int pg = cs_prof_begin(CS_PROF_GEMM, s);
+    if (mode == CS_GEMM_STORE) k_gemm_tile<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+    else k_gemm_tile<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+    cs_prof_end(pg, s);
+    return cs_launch_ok("k_gemm_tile");
+}
+
 template <int MT, int NT>
 static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K,
                        int mode, int ksplit, hipStream_t s) {
@@ -316,13 +484,16 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     // are split along K, but only until about 3/4 of the compute units have a workgroup:
     // measured at the 8B shapes, more splits cost more in partial-tile traffic and fixed
     // per-workgroup latency than they gain in parallelism (q/k/v 4, o 8, down 8 splits).
-    // A workgroup takes up to 96 block rows; more rows are split into equal row blocks whose
-    // workgroups share each W tile through one XCD's L2 (see the mapping in the kernel).
+    // Weight-streaming kernel: a workgroup takes up to 96 block rows; more rows are split into
+    // equal row blocks whose workgroups share each W tile through one XCD's L2 (see the mapping
+    // in the kernel).  Many-row kernel: up to 288 rows per workgroup.
+    static const int tile_min_r = getenv("CS_TILE_MIN_R") ? atoi(getenv("CS_TILE_MIN_R")) : 200;
+    const bool tile = R > tile_min_r;
     const int rt_total = (int)cs_ceil_div(R, 16);
-    const int r_blocks = (int)cs_ceil_div(rt_total, 6);
+    const int r_blocks = tile ? (int)cs_ceil_div(rt_total, 18) : (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;
     if (allow_split && mode == CS_GEMM_STORE) {
-        const int n_tiles = (int)cs_ceil_div(N, 128);
+        const int n_tiles = (int)cs_ceil_div(N, tile ? TG_WROWS : 128);
         const int max_split = K / (4 * GEMM_KC) > 0 ? K / (4 * GEMM_KC) : 1;
         while (n_tiles * r_blocks * ksplit < 192 && ksplit * 2 <= max_split) ksplit *= 2;
     }
@@ -336,6 +507,15 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     const f16_t* x = (const f16_t*)X;
     const f16_t* w = (const f16_t*)W;
     f16_t* act = (f16_t*)m->act;
+    if (tile) {
+        switch ((int)cs_ceil_div(rt, 2)) {           // 16-row X tiles per wave
+            case 1: case 2: case 3: case 4: case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 6: return launch_tile<6>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 7: return launch_tile<7>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 8: return launch_tile<8>(x, w, Y, act, R, N, K, mode, nparts, s);
+            default: return launch_tile<9>(x, w, Y, act, R, N, K, mode, nparts, s);
+        }
+    }
     switch (rt) {
         case 1: return launch_mfma<2, 1>(x, w, Y, act, R, N, K, mode, nparts, s);
         case 2: return launch_mfma<2, 2>(x, w, Y, act, R, N, K, mode, nparts, s);
