@@ -11,6 +11,7 @@
 // in float32.  Small-N projections are split along K across workgroups; the float32 partial
 // tiles are summed by the consumer kernel in a fixed order (deterministic, no atomics).
 #include "cs_common.h"
+#include <type_traits>
 
 // -------------------------------------------------------------------------------------
 // plain reference kernel: one wave per W row, float32 accumulation
@@ -234,121 +235,149 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 }
 
 // -------------------------------------------------------------------------------------
-// tuned kernel for many rows (compute-bound blocks, e.g. batch 16 x (k = 32) + 1 = 528 rows)
+// tuned kernel for many rows (e.g. batch 16 x (k = 32) + 1 = 528 rows)
 //
 // With hundreds of block rows the projections are bound by the matrix cores and by the
 // bandwidth between L2 and the compute units, so the tile is chosen for operand reuse: a
-// workgroup of eight waves (4 x 2) owns a 256 (W rows) x 32*NT (X rows) output tile, each
-// wave 64 x 16*NT.  Both operands go through LDS, every element fetched from L2 once per
-// workgroup.  LDS holds them in MFMA fragment order (1 KB blocks of 16 rows x 32 k, lane l's
-// 16 bytes at offset 16*l), so fragment reads and staging writes are conflict-free without
-// padding; the pre-tiled W is already stored that way in memory.  K advances 64 at a time
-// through two LDS stages: the loads of chunk c+2 are issued after chunk c+1 has been
-// written to LDS and stay in flight during the whole multiply of chunk c+1.
+// workgroup of eight waves (4 x 2, two per SIMD so one wave's waits hide behind the other's
+// MFMAs) owns a 256 (W rows) x 32*NT (X rows) output tile, each wave 64 x 16*NT.  Both
+// operands go through LDS, every element fetched from L2 once per workgroup.  LDS holds them
+// in MFMA fragment order (1 KB blocks of 16 rows x 32 k, lane l's 16 bytes at offset 16*l), so
+// fragment reads are conflict-free without padding; the pre-tiled W is already stored that
+// way in memory.  The operands never pass through registers on their way in: every wave
+// issues 16-byte direct-to-LDS loads (lane l's 16 bytes land at the wave-uniform LDS address
+// in M0 plus 16*l, so one load fills one fragment block; an X block is gathered, lane l
+// fetching row l % 16 at K group l / 16).  K advances 32 at a time through a ring of four
+// LDS stages.  Chunk c+3 is requested
+// while chunk c is multiplied; one barrier per chunk publishes chunk c+1 and frees the stage
+// of chunk c-1, and the first fragments of chunk c+1 are read before that chunk's barrier so
+// the matrix cores do not drain at the hand-over.
+//
+// The loads and the waits on them are written as inline assembly: the compiler's own
+// bookkeeping would make every LDS read wait for all outstanding direct-to-LDS loads.  This
+// kernel issues no other vector memory loads, so the load counter counts exactly the
+// requests below and the s_waitcnt immediates are exact.
 // -------------------------------------------------------------------------------------
+#define TD_KC 32
 #define TG_THREADS 512
-#define TG_KC 64
 #define TG_WROWS 256
 
+// request 16 bytes per lane from (uniform base + per-lane byte offset) into LDS at lds_addr + 16*lane
+__device__ __forceinline__ void cs_load_to_lds(unsigned voff, const void* sbase, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "m0");
+}
+
 template <int NT, int MODE>
-__global__ __launch_bounds__(TG_THREADS) void k_gemm_tile(const f16_t* __restrict__ X,
-                                                          const f16_t* __restrict__ W,
-                                                          float* __restrict__ Y,
-                                                          f16_t* __restrict__ act, int R, int N, int K,
-                                                          int Ks, int RB) {
-    constexpr int XBLK = 2 * NT * 2;                 // X blocks per stage (2*NT row tiles x 2 K steps)
-    constexpr int NXLD = (XBLK + 7) / 8;             // X loads per thread per chunk
-    constexpr int STAGE = (32 + XBLK) * 1024;        // 32 W blocks (16 row tiles x 2 K steps) + X
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE];
+__global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict__ X,
+                                                         const f16_t* __restrict__ W,
+                                                         float* __restrict__ Y,
+                                                         f16_t* __restrict__ act, int R, int N, int K,
+                                                         int Ks, int RB) {
+    constexpr int XT = 2 * NT;                        // X row tiles per workgroup
+    constexpr int NBLK = 16 + XT;                     // 1 KB blocks per stage: 16 W tiles, then X tiles
+    constexpr int XLD = (XT + 7) / 8;                 // X loads per wave per stage (the last may be partial)
+    constexpr int LDMIN = 2 + XT / 8;                 // loads every wave issues per stage
+    constexpr int STAGE = NBLK * 1024;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[4 * STAGE];
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wn = wave & 3, wm = wave >> 2;
     const int lrow = lane & 15, g = lane >> 4;
-    const int k_begin = blockIdx.y * Ks;             // multiple of 128
+    const int k_begin = blockIdx.y * Ks;              // multiple of 128
     const int k_end = min(K, k_begin + Ks);
-    const int nchunks = (k_end - k_begin) / TG_KC;
-    const int last = nchunks - 1;
-    // same XCD-aware (W tile, X row block) mapping as k_gemm_mfma
+    const int nchunks = (k_end - k_begin) / TD_KC;    // multiple of 4
     const int grp = blockIdx.x / (8 * RB), rem = blockIdx.x % (8 * RB);
     const int w_tile = grp * 8 + (rem & 7);
     if (w_tile * TG_WROWS >= N) return;
     const int r_base = (rem >> 3) * 32 * NT;
     const int n_tiles = N >> 4;
-    const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;    // elements per 128-wide K slab of W
+    const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;
 
-    // Staging plan: wave w copies W blocks w, w+8, w+16, w+24 and X blocks w, w+8, ... of every
-    // chunk.  W block j = (row tile j/2, K step j%2) is 1 KB contiguous in memory.  X block j is
-    // gathered: lane l fetches 16 bytes of row (l % 16) at K group l / 16.  Indices past the end
-    // are clamped (the copy is repeated, or feeds output rows that are never stored).
-    int woff[4], xoff[NXLD], xdst[NXLD];
+    // wave w requests W tiles w, w+8 and X tiles w, w+8, ... of every chunk.  Per-lane byte
+    // offsets (32 bits) are fixed; the chunk moves the uniform base.
+    unsigned woff[2], xoff[XLD];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int j = wave + 8 * i;
-        int t = w_tile * 16 + (j >> 1);
+    for (int i = 0; i < 2; ++i) {
+        int t = w_tile * 16 + wave + 8 * i;
         t = t < n_tiles ? t : n_tiles - 1;
-        woff[i] = (t * 4 + (j & 1)) * 512 + lane * 8;
+        woff[i] = (unsigned)(t * 4 * 512 + lane * 8) * 2u;
     }
 #pragma unroll
-    for (int i = 0; i < NXLD; ++i) {
+    for (int i = 0; i < XLD; ++i) {
         int j = wave + 8 * i;
-        j = j < XBLK ? j : XBLK - 1;
-        int r = r_base + (j >> 1) * 16 + lrow;
+        j = j < XT ? j : XT - 1;
+        int r = r_base + j * 16 + lrow;
         r = r < R ? r : R - 1;
-        xoff[i] = r * K + k_begin + (j & 1) * 32 + g * 8;       // R*K < 2^31 (host check)
-        xdst[i] = (32 + j) * 1024 + lane * 16;
+        xoff[i] = (unsigned)(r * K + k_begin + g * 8) * 2u;   // R*K < 2^31 (host check)
     }
     const f16_t* wbase = W + (int64_t)(k_begin / GEMM_KC) * chunk_stride;
-    f16x8 wr[4], xr[NXLD];
-    auto load = [&](int c) {
-        c = c < last ? c : last;
-        const f16_t* wc = wbase + (int64_t)(c >> 1) * chunk_stride + (c & 1) * 1024;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+
+    // request chunk c into stage sb
+    auto issue = [&](int sb, int c) {
+        const unsigned dst = lds0 + sb * STAGE + wave * 1024;
+        const f16_t* wc = wbase + (int64_t)(c >> 2) * chunk_stride + (c & 3) * 512;
+        const f16_t* xc = X + c * TD_KC;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wr[i] = *reinterpret_cast<const f16x8*>(wc + woff[i]);
+        for (int i = 0; i < 2; ++i) cs_load_to_lds(woff[i], wc, dst + 8 * i * 1024);
 #pragma unroll
-        for (int i = 0; i < NXLD; ++i) xr[i] = *reinterpret_cast<const f16x8*>(X + (xoff[i] + c * TG_KC));
+        for (int i = 0; i < XLD; ++i) {
+            if (8 * i + 7 < XT || wave + 8 * i < XT) cs_load_to_lds(xoff[i], xc, dst + (16 + 8 * i) * 1024);
+        }
     };
-    auto store = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<f16x8*>(&lds[buf][(wave + 8 * i) * 1024 + lane * 16]) = wr[i];
-#pragma unroll
-        for (int i = 0; i < NXLD; ++i) *reinterpret_cast<f16x8*>(&lds[buf][xdst[i]]) = xr[i];
-    };
+    const unsigned char* a_base = lds + wn * 4 * 1024 + lane * 16;
+    const unsigned char* b_base = lds + (16 + wm * NT) * 1024 + lane * 16;
+    auto a_frag = [&](int sb, int mt) { return *reinterpret_cast<const f16x8*>(a_base + sb * STAGE + mt * 1024); };
+    auto b_frag = [&](int sb, int nt) { return *reinterpret_cast<const f16x8*>(b_base + sb * STAGE + nt * 1024); };
 
     f32x4 acc[4][NT];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    f16x8 a[4], bq[4];
 
-    auto compute = [&](int buf) {
-        const unsigned char* ab = lds[buf] + (wn * 4 * 2) * 1024 + lane * 16;
-        const unsigned char* bb = lds[buf] + (32 + wm * NT * 2) * 1024 + lane * 16;
+    // wait until at most `n` of this wave's loads are outstanding, then meet the other waves.
+    // (A plain s_barrier: the workgroup fence of __syncthreads would drain every load in flight.)
+#define TD_SYNC(n) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(n) : "memory")
+    issue(0, 0);
+    issue(1, 1);
+    issue(2, 2);
+    TD_SYNC(2 * LDMIN);                                        // chunk 0 has landed everywhere
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            f16x8 a[4];
+    for (int mt = 0; mt < 4; ++mt) a[mt] = a_frag(0, mt);
+    bq[0] = b_frag(0, 0);
+    bq[1] = b_frag(0, 1 % NT);
+
+    // four chunks, one per stage.  TAIL marks the last trip, where nothing more is requested.
+    auto trip = [&](int c0, auto tailc) {
+        constexpr bool TAIL = decltype(tailc)::value;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) a[mt] = *reinterpret_cast<const f16x8*>(ab + (mt * 2 + st) * 1024);
+        for (int u = 0; u < 4; ++u) {
+            // chunk c+1 (requested two iterations ago) must be in LDS before its first fragments
+            // are read at the end of this iteration; only chunk c+2 may still be in flight
+            if (TAIL && u >= 2) TD_SYNC(0);
+            else TD_SYNC(LDMIN);
+            if (!TAIL || u == 0) issue((u + 3) & 3, c0 + u + 3);  // stage of chunk c-1, free since the barrier
+            const bool more = !TAIL || u < 3;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const f16x8 b = *reinterpret_cast<const f16x8*>(bb + (nt * 2 + st) * 1024);
+                const int q = u * NT + nt;                        // position in the B fragment stream
+                if (nt + 2 < NT) bq[(q + 2) & 3] = b_frag(u, nt + 2);
+                else if (more) bq[(q + 2) & 3] = b_frag((u + 1) & 3, nt + 2 - NT);
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b, acc[mt][nt], 0, 0, 0);
+                for (int mt = 0; mt < 4; ++mt) {
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bq[q & 3], acc[mt][nt], 0, 0, 0);
+                    // an A fragment is replaced by the next chunk's right after its last use
+                    if (nt == NT - 1 && more) a[mt] = a_frag((u + 1) & 3, mt);
+                }
             }
         }
     };
-
-    load(0);
-    store(0);
-    load(1);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        compute(c & 1);
-        store((c + 1) & 1);          // chunk c+1; that buffer was last read while multiplying chunk c-1
-        load(c + 2);
-        __syncthreads();
-    }
+    int c0 = 0;
+    for (; c0 + 4 < nchunks; c0 += 4) trip(c0, std::false_type{});
+    trip(c0, std::true_type{});
+#undef TD_SYNC
 
     // epilogue: acc[mt][nt][j] = Y[r_base + (wm*NT + nt)*16 + lrow][n_wave + mt*16 + 4g + j]
     const int n_wave = w_tile * TG_WROWS + wn * 64;
@@ -395,10 +424,10 @@ static int launch_tile(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int
     const int RB = (int)cs_ceil_div(R, 32 * NT);
     dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, TG_WROWS), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
-    if (mode == CS_GEMM_STORE) k_gemm_tile<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
-    else k_gemm_tile<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+    if (mode == CS_GEMM_STORE) k_gemm_dma<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+    else k_gemm_dma<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
     cs_prof_end(pg, s);
-    return cs_launch_ok("k_gemm_tile");
+    return cs_launch_ok("k_gemm_dma");
 }
 
 template <int MT, int NT>
@@ -486,9 +515,11 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     // per-workgroup latency than they gain in parallelism (q/k/v 4, o 8, down 8 splits).
     // Weight-streaming kernel: a workgroup takes up to 96 block rows; more rows are split into
     // equal row blocks whose workgroups share each W tile through one XCD's L2 (see the mapping
-    // in the kernel).  Many-row kernel: up to 288 rows per workgroup.
-    static const int tile_min_r = getenv("CS_TILE_MIN_R") ? atoi(getenv("CS_TILE_MIN_R")) : 200;
-    const bool tile = R > tile_min_r;
+    // in the kernel).  Many-row kernel: up to 288 rows per workgroup.  Measured at the 8B
+    // shapes, the many-row kernel wins from 97 rows on for the wide projections (q/k/v, gate/up,
+    // lm_head) and from about 265 rows on for the narrow ones (o, down), which need deep K
+    // splits to fill the chip and pay for them in partial-tile traffic.
+    const bool tile = R > 96 && (N > 4096 || R > 264);
     const int rt_total = (int)cs_ceil_div(R, 16);
     const int r_blocks = tile ? (int)cs_ceil_div(rt_total, 18) : (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;
@@ -509,7 +540,9 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     f16_t* act = (f16_t*)m->act;
     if (tile) {
         switch ((int)cs_ceil_div(rt, 2)) {           // 16-row X tiles per wave
-            case 1: case 2: case 3: case 4: case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 1: case 2: case 3: return launch_tile<3>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 4: return launch_tile<4>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, s);
             case 6: return launch_tile<6>(x, w, Y, act, R, N, K, mode, nparts, s);
             case 7: return launch_tile<7>(x, w, Y, act, R, N, K, mode, nparts, s);
             case 8: return launch_tile<8>(x, w, Y, act, R, N, K, mode, nparts, s);

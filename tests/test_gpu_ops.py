@@ -69,15 +69,16 @@ def test_argmax_accept_full_size(host_model, B, k, V):
 
 
 # ----------------------------------------------------------------------------------------
-# projections at the 8B shapes, R = 88 (benchmark) and 528 (batch 16, k = 32)
+# projections at the 8B shapes, R = 88 (benchmark) and 528 (batch 16, k = 32); 104 .. 408
+# rows cover every row-tile count of the many-row kernel (one and two row blocks, ragged tails)
 # ----------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("N,K", [(6144, 4096), (4096, 4096), (28672, 4096), (4096, 14336),
                                  (128256, 4096)])
-@pytest.mark.parametrize("R", [88, 528, 1])
+@pytest.mark.parametrize("R", [88, 528, 1, 104, 168, 200, 250, 264, 408])
 def test_gemm_bf16_full_shapes(host_model, N, K, R):
-    if R == 528 and N == 128256:
-        pytest.skip("covered at R=88; the 528-row case repeats the same tiles six times")
+    if R not in (88, 528, 1) and (N, K) not in ((6144, 4096), (4096, 14336)):
+        pytest.skip("intermediate row counts are checked on one wide and one K-split projection")
     seed = N * 7 + K + R
     xb = synth.workloads._draw(seed, (R, K), "n", 1.0, "bf16")
     wb = synth.workloads._draw(seed + 1, (N, K), "u", (3.0 / K) ** 0.5, "bf16")
@@ -230,6 +231,14 @@ def _deep_verify(shape, B, L, k, check_streams, seed):
 def test_verify_llama1b_full_depth():
     """Configuration 3 shape at full depth: 16 layers, 4096 cached rows, k = 10."""
     worst = _deep_verify(synth.LLAMA_1B, 1, 4096, 10, [0], seed=synth.seed_for(3))
+    assert worst <= 2e-2, worst
+
+
+def test_verify_llama8b_width_many_rows():
+    """8B width, batch 8, k = 32: 264 block rows go through the many-row projection kernel
+    (SwiGLU epilogue, K splits) and the wide-block attention kernel; 2 layers, short cache."""
+    shape = synth.LLAMA_8B.with_layers(2)
+    worst = _deep_verify(shape, 8, 700, 32, [0, 7], seed=synth.seed_for(5))
     assert worst <= 2e-2, worst
 
 
