@@ -304,9 +304,14 @@ def main():
         "attn_merge": {"avg_us": prof["attn_merge"][0] / max(prof["attn_merge"][1], 1) * 1e3},
         "scan_in_step": {"avg_us": prof["scan"][0] / max(prof["scan"][1], 1) * 1e3},
     }
+    # more than 48 query rows per KV head go to the LDS-ring attention kernel
+    g_rows = (k + 1) * (st["shape"].n_heads // st["shape"].n_kv_heads)
+    attn_kernel = "k_attn_mfma" if g_rows <= 48 else "k_attn_lds"
+    # the committed counter summary covers the default workload only
+    default_workload = (args.shape, B, k, args.doc, args.hist, args.layers) == ("8b", 8, 10, 2048, 16384, 0)
     step_bytes = ab["gemm_step"] + ab["attn_step"] + ab["scan_launch"] + ab["argmax_launch"]
     out = {
-        "metric": "verified tokens/sec/GPU (8B shape, k=10)",
+        "metric": f"verified tokens/sec/GPU ({args.shape.upper()} shape, k={k})",
         "value": B * k / t_step,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -323,10 +328,10 @@ def main():
                                f"document spans (KV length {st['L']} + pending), gamma={st['gamma']}, k={k}, "
                                f"one whole cs_step per step",
                    "batch": B, "k": k, "gamma": st["gamma"], "kv_len": st["L"], "rows": B * (k + 1)},
-        "roofline": {"bound": "hbm", "kernel": "k_attn_mfma (block attention, one layer, all streams)",
+        "roofline": {"bound": "hbm", "kernel": f"{attn_kernel} (block attention, one layer, all streams)",
                      "achieved": ab["attn_launch"] / attn_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": ab["attn_launch"] / attn_s / 1e9 / HBM_PEAK_GBS,
-                     "traffic": measured_traffic("k_attn_mfma"),
+                     "traffic": measured_traffic("k_attn_mfma") if default_workload else None,
                      "algorithmic_bytes_per_launch": ab["attn_launch"], "avg_launch_us": attn_s * 1e6},
         "kernels": kern,
         "step": {"algorithmic_GB": step_bytes / 1e9,

@@ -44,14 +44,34 @@ import numpy as np
 # match search (Sec. 3.1, Sec. 3.2, App. B.1, App. B.3 step 1)
 # ----------------------------------------------------------------------------
 
+CONTEXT_CAP = 64    # longest backward agreement the "context" policy looks at
+
+
+def context_length(h, p: int, gamma: int) -> int:
+    """Number of tokens immediately before candidate p that equal the tokens immediately
+    before the query suffix h[n-gamma:], counted backwards until the first difference,
+    the start of the history or CONTEXT_CAP."""
+    n = len(h)
+    e = 0
+    while e < CONTEXT_CAP and p - e - 1 >= 0 and int(h[p - e - 1]) == int(h[n - gamma - e - 1]):
+        e += 1
+    return e
+
+
 def find_match(h, gamma: int, k: int, policy: str = "rightmost"):
     """Search history h[0..n) for an earlier, non-overlapping occurrence of its
     last gamma tokens and copy what follows.
 
     M = { p : 0 <= p <= n - 2*gamma, h[p+j] == h[n-gamma+j] for all j < gamma }.
-    Returns (match_pos, src_pos, draft) with match_pos = max M ("rightmost") or
-    min M ("first"), src_pos = match_pos + gamma, draft = h[src_pos : src_pos+k]
-    truncated at n.  No match (or n < 2*gamma): (-1, -1, []).
+    Returns (match_pos, src_pos, draft) with match_pos = max M ("rightmost"),
+    min M ("first"), or ("context") the candidate whose preceding tokens agree longest
+    with the tokens preceding the suffix (context_length; the rightmost among equals),
+    src_pos = match_pos + gamma, draft = h[src_pos : src_pos+k] truncated at n.
+    No match (or n < 2*gamma): (-1, -1, []).
+
+    "context" is one concrete form of the structural ranking of candidates that the
+    paper's Limitations section leaves to future work; like the other policies it only
+    changes which draft is proposed, never the emitted tokens.
     """
     h = [int(t) for t in h]
     n = len(h)
@@ -72,6 +92,8 @@ def find_match(h, gamma: int, k: int, policy: str = "rightmost"):
         p = max(matches)
     elif policy == "first":
         p = min(matches)
+    elif policy == "context":
+        p = max(matches, key=lambda c: (context_length(h, c, gamma), c))
     else:
         raise ValueError(policy)
     src = p + gamma
@@ -94,8 +116,13 @@ def find_match_np(h, gamma: int, k: int, policy: str = "rightmost"):
     pos = np.flatnonzero(same)
     if pos.size == 0:
         return -1, -1, []
-    p = int(pos.max() if policy == "rightmost" else pos.min())
-    if policy not in ("rightmost", "first"):
+    if policy == "rightmost":
+        p = int(pos.max())
+    elif policy == "first":
+        p = int(pos.min())
+    elif policy == "context":
+        p = max((int(c) for c in pos), key=lambda c: (context_length(h, c, gamma), c))
+    else:
         raise ValueError(policy)
     src = p + gamma
     return p, src, [int(t) for t in h[src:min(src + k, n)]]
@@ -129,7 +156,10 @@ class GammaGramDict:
         occ = [p for p in occ if p + g - 1 < t - g]
         if not occ:
             return -1, -1, []
-        p = occ[-1] if policy == "rightmost" else occ[0]
+        if policy == "context":
+            p = max(occ, key=lambda c: (context_length(self.tokens, c, g), c))
+        else:
+            p = occ[-1] if policy == "rightmost" else occ[0]
         return p, p + g, self.tokens[p + g:min(p + g + k, t)]
 
 

@@ -100,6 +100,63 @@ def test_find_match_invariants():
             assert len(d) == min(10, n - s) and len(d) >= min(10, gamma)
 
 
+def _bytes_search_context(h, gamma, cap):
+    """Independent formulation of the "context" policy with the standard library's substring
+    search: a candidate whose x preceding tokens agree with the x tokens before the suffix is
+    an occurrence of the last gamma + x tokens that ends before the suffix starts.  The longest
+    such x (at most cap) wins, and among its occurrences the rightmost."""
+    n = len(h)
+    if n < 2 * gamma:
+        return -1
+    b = bytes(h)
+    for x in range(min(cap, n - 2 * gamma), -1, -1):
+        q = b.rfind(b[n - gamma - x:], 0, n - gamma)
+        if q >= 0:
+            return q + x
+    return -1
+
+
+def test_context_policy_exhaustive_and_random(monkeypatch):
+    k = 4
+    for cap in (64, 2):                     # the cap itself is exercised with a small value
+        monkeypatch.setattr(orc, "CONTEXT_CAP", cap)
+        for n in range(0, 11):
+            for h in itertools.product(range(2), repeat=n):
+                h = list(h)
+                for gamma in (1, 2, 3):
+                    want = _bytes_search_context(h, gamma, cap)
+                    m, s, d = orc.find_match(h, gamma, k, "context")
+                    assert m == want, (h, gamma, cap)
+                    assert orc.find_match_dict(h, gamma, k, "context") == (m, s, d)
+                    if n > 0:
+                        assert orc.find_match_np(h, gamma, k, "context") == (m, s, d)
+                    if m >= 0:
+                        assert (s, d) == (m + gamma, h[m + gamma:min(m + gamma + k, n)])
+        rng = np.random.default_rng(23)
+        for _ in range(200):
+            n = int(rng.integers(1, 500))
+            h = rng.integers(0, int(rng.integers(2, 5)), n).tolist()
+            gamma = int(rng.integers(1, 6))
+            want = _bytes_search_context(h, gamma, cap)
+            for fn in (orc.find_match, orc.find_match_np, orc.find_match_dict):
+                assert fn(h, gamma, 10, "context")[0] == want
+
+
+def test_context_policy_hand_cases():
+    # suffix (7, 8): candidates at 1 (preceded by 5) and 5 (preceded by 6); the suffix is preceded by 5
+    h = [5, 7, 8, 1, 6, 7, 8, 2, 5, 7, 8]
+    assert orc.find_match(h, 2, 3, "rightmost")[0] == 5
+    assert orc.find_match(h, 2, 3, "first")[0] == 1
+    assert orc.find_match(h, 2, 3, "context") == (1, 3, [1, 6, 7])
+    # equal context lengths (both 0): the rightmost candidate
+    h = [3, 7, 8, 1, 4, 7, 8, 2, 5, 7, 8]
+    assert orc.find_match(h, 2, 3, "context")[0] == 5
+    # a candidate at position 0 has no context
+    h = [7, 8, 9, 7, 8]
+    assert orc.find_match(h, 2, 3, "context") == (0, 2, [9, 7, 8])
+    assert orc.context_length([1, 2, 3, 9, 1, 2, 3], 2, 1) == 2
+
+
 def test_find_match_bad_args():
     with pytest.raises(ValueError):
         orc.find_match([1, 2, 3], 0, 10)
