@@ -42,7 +42,7 @@ typedef enum cs_status {
     CS_E_UNSUPPORTED = -6 /* shape outside what the kernels are built for */
 } cs_status;
 
-enum { CS_POLICY_RIGHTMOST = 0, CS_POLICY_FIRST = 1 };
+enum { CS_POLICY_RIGHTMOST = 0, CS_POLICY_FIRST = 1, CS_POLICY_CONTEXT = 2 };
 enum { CS_F32 = 0, CS_BF16 = 1 };
 
 const char* cs_last_error(void);
@@ -56,8 +56,13 @@ const char* cs_version(void);
  *   M = { p : 0 <= p <= n - 2*gamma  and  h[p+j] == h[n-gamma+j] for all 0 <= j < gamma }
  *
  * The bound p <= n - 2*gamma is App. B.3 step 1c (the earlier occurrence must end before
- * the query suffix starts).  match_pos = max M (CS_POLICY_RIGHTMOST) or min M
- * (CS_POLICY_FIRST); src_pos = match_pos + gamma is the first token to copy;
+ * the query suffix starts).  match_pos = max M (CS_POLICY_RIGHTMOST), min M
+ * (CS_POLICY_FIRST), or (CS_POLICY_CONTEXT) the p in M whose preceding tokens agree longest
+ * with the tokens preceding the suffix -- the largest e <= min(64, p) with
+ * h[p-j] == h[n-gamma-j] for 1 <= j <= e, the rightmost p among equal e; this is one concrete
+ * form of the candidate ranking the paper's Limitations section leaves to future work.
+ * The policy never changes the emitted tokens, only which draft is proposed.
+ * src_pos = match_pos + gamma is the first token to copy;
  * draft[i] = h[src_pos + i] for i < draft_len = min(k, n - src_pos).  If M is empty or
  * n < 2*gamma: match_pos = src_pos = -1, draft_len = 0.  Unused draft slots are set to -1.
  * The paper finds p with a hash map of all gamma-grams; this library scans the history,

@@ -17,9 +17,9 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcopyspec.so")
 
-CS_POLICY_RIGHTMOST, CS_POLICY_FIRST = 0, 1
+CS_POLICY_RIGHTMOST, CS_POLICY_FIRST, CS_POLICY_CONTEXT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
-POLICIES = {"rightmost": CS_POLICY_RIGHTMOST, "first": CS_POLICY_FIRST}
+POLICIES = {"rightmost": CS_POLICY_RIGHTMOST, "first": CS_POLICY_FIRST, "context": CS_POLICY_CONTEXT}
 
 EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev",

@@ -404,8 +404,8 @@ extern "C" int cs_kv_read(cs_kv* kv, int32_t layer, int32_t b, int64_t pos0, int
 static int check_scan_args(int gamma, int k, int policy) {
     CS_REQUIRE(gamma >= 1 && gamma <= 16, CS_E_ARG, "gamma must be in 1..16 (got %d)", gamma);
     CS_REQUIRE(k >= 0 && k <= 256, CS_E_ARG, "k must be in 0..256 (got %d)", k);
-    CS_REQUIRE(policy == CS_POLICY_RIGHTMOST || policy == CS_POLICY_FIRST, CS_E_ARG,
-               "unknown match policy %d", policy);
+    CS_REQUIRE(policy == CS_POLICY_RIGHTMOST || policy == CS_POLICY_FIRST || policy == CS_POLICY_CONTEXT,
+               CS_E_ARG, "unknown match policy %d", policy);
     return CS_OK;
 }
 

@@ -521,11 +521,12 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     // per-workgroup latency than they gain in parallelism (q/k/v 4, o 8, down 8 splits).
     // Weight-streaming kernel: a workgroup takes up to 96 block rows; more rows are split into
     // equal row blocks whose workgroups share each W tile through one XCD's L2 (see the mapping
-    // in the kernel).  Many-row kernel: up to 288 rows per workgroup.  Measured at the 8B
-    // shapes, the many-row kernel wins from 97 rows on for the wide projections (q/k/v, gate/up,
-    // lm_head) and from about 265 rows on for the narrow ones (o, down), which need deep K
-    // splits to fill the chip and pay for them in partial-tile traffic.
-    const bool tile = R > 96 && (N > 4096 || R > 264);
+    // in the kernel).  Many-row kernel: 256 W rows x up to 288 block rows per workgroup.  It needs
+    // enough 256-row W tiles, or two row blocks of them, to fill the chip: measured inside whole
+    // steps at the 8B shapes it wins from 97 rows on for the lm_head (501 tiles) and from 289
+    // rows on for every projection (at 168 and 264 rows the q/k/v and gate/up projections,
+    // 24 and 112 tiles, are still faster through the weight-streaming kernel).
+    const bool tile = R > 96 && (cs_ceil_div(N, TG_WROWS) >= 192 || R > 288);
     const int rt_total = (int)cs_ceil_div(R, 16);
     const int r_blocks = tile ? (int)cs_ceil_div(rt_total, 18) : (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;
@@ -546,8 +547,7 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     f16_t* act = (f16_t*)m->act;
     if (tile) {
         switch ((int)cs_ceil_div(rt, 2)) {           // 16-row X tiles per wave
-            case 1: case 2: case 3: return launch_tile<3>(x, w, Y, act, R, N, K, mode, nparts, s);
-            case 4: return launch_tile<4>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 1: case 2: case 3: case 4: return launch_tile<4>(x, w, Y, act, R, N, K, mode, nparts, s);
             case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, s);
             case 6: return launch_tile<6>(x, w, Y, act, R, N, K, mode, nparts, s);
             case 7: return launch_tile<7>(x, w, Y, act, R, N, K, mode, nparts, s);

@@ -4,12 +4,32 @@
 // history returns the same position at 4 bytes per token, streamed once.  The scan is
 // HBM-bound: every thread loads 16 bytes (4 tokens) per step, compares them with the first
 // token of the query suffix, and only on a hit (rare for real vocabularies) checks the
-// other gamma-1 tokens.  Each workgroup reduces its chunk to one position; a second tiny
+// other gamma-1 tokens.  Each workgroup reduces its chunk to one key; a second tiny
 // kernel reduces the chunks of a stream, applies the policy and copies the draft.
+//
+// Keys (int64, -1 = no candidate): the position for the rightmost (max) and first (min)
+// policies; (context length << 32) | position, reduced by max, for the context policy, which
+// ranks candidates by how many tokens before them agree with the tokens before the suffix
+// (the match-selection refinement the paper's Limitations section leaves open) and takes the
+// rightmost among equals.
 #include "cs_common.h"
 
 #define SCAN_THREADS 256
 #define SCAN_CHUNK 4096   // candidate positions per workgroup
+#define SCAN_CONTEXT_CAP 64
+
+// tokens before candidate p that equal the tokens before the suffix, counted backwards
+__device__ __forceinline__ int context_length(const int32_t* __restrict__ h, int p, int n, int gamma) {
+    int e = 0;
+    while (e < SCAN_CONTEXT_CAP && p - e - 1 >= 0 && h[p - e - 1] == h[n - gamma - e - 1]) ++e;
+    return e;
+}
+
+template <int POLICY>
+__device__ __forceinline__ int64_t key_better(int64_t a, int64_t b) {
+    if (POLICY == CS_POLICY_FIRST) return (a < 0) ? b : (b < 0 ? a : (a < b ? a : b));
+    return a > b ? a : b;
+}
 
 __device__ __forceinline__ bool rest_matches(const int32_t* __restrict__ h, int p, int n, int gamma) {
     for (int j = 1; j < gamma; ++j)
@@ -17,12 +37,12 @@ __device__ __forceinline__ bool rest_matches(const int32_t* __restrict__ h, int 
     return true;
 }
 
-// chunk_best[b][c] = best candidate in chunk c (max for rightmost, min for first), -1 if none
+// chunk_best[b][c] = best key in chunk c, -1 if none
 template <int POLICY>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict__ hist,
                                                        int64_t stride,
                                                        const int32_t* __restrict__ len, int gamma,
-                                                       int vec_ok, int32_t* __restrict__ chunk_best,
+                                                       int vec_ok, int64_t* __restrict__ chunk_best,
                                                        int nchunks) {
     const int b = blockIdx.y;
     const int c = blockIdx.x;
@@ -30,8 +50,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
     const int32_t* __restrict__ h = hist + (int64_t)b * stride;
     const int cnt = n - 2 * gamma + 1;            // candidate starts are 0 .. cnt-1
     const int begin = c * SCAN_CHUNK;
-    const int NONE = POLICY == CS_POLICY_RIGHTMOST ? -1 : 0x7fffffff;
-    int best = NONE;
+    int64_t best = -1;
     if (begin < cnt) {
         const int end = min(cnt, begin + SCAN_CHUNK);
         const int s0 = h[n - gamma];
@@ -48,8 +67,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
             for (int i = 0; i < 4; ++i) {
                 const int pp = p + i;
                 if (pp < end && t[i] == s0 && rest_matches(h, pp, n, gamma)) {
-                    if (POLICY == CS_POLICY_RIGHTMOST) best = max(best, pp);
-                    else best = min(best, pp);
+                    int64_t key = pp;
+                    if (POLICY == CS_POLICY_CONTEXT) key |= (int64_t)context_length(h, pp, n, gamma) << 32;
+                    best = key_better<POLICY>(best, key);
                 }
             }
         }
@@ -57,18 +77,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
     // workgroup reduction: wave shuffle, then LDS across the 4 waves
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-        const int other = __shfl_xor(best, o, 64);
-        best = POLICY == CS_POLICY_RIGHTMOST ? max(best, other) : min(best, other);
+        const int64_t other = __shfl_xor(best, o, 64);
+        best = key_better<POLICY>(best, other);
     }
-    __shared__ int wave_best[SCAN_THREADS / CS_WAVE];
+    __shared__ int64_t wave_best[SCAN_THREADS / CS_WAVE];
     if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
     __syncthreads();
     if (threadIdx.x == 0) {
-        int r = wave_best[0];
+        int64_t r = wave_best[0];
 #pragma unroll
-        for (int w = 1; w < SCAN_THREADS / CS_WAVE; ++w)
-            r = POLICY == CS_POLICY_RIGHTMOST ? max(r, wave_best[w]) : min(r, wave_best[w]);
-        if (r == NONE) r = -1;
+        for (int w = 1; w < SCAN_THREADS / CS_WAVE; ++w) r = key_better<POLICY>(r, wave_best[w]);
         chunk_best[(int64_t)b * nchunks + c] = r;
     }
 }
@@ -76,7 +94,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
 // One wave per stream: reduce the chunk results, then copy the draft (App. B.1 "Chunk").
 __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist, int64_t stride,
                                                const int32_t* __restrict__ len, int gamma, int k,
-                                               int policy, const int32_t* __restrict__ chunk_best,
+                                               int policy, const int64_t* __restrict__ chunk_best,
                                                int nchunks, const int32_t* __restrict__ room,
                                                int32_t* __restrict__ match_pos,
                                                int32_t* __restrict__ src_pos,
@@ -85,20 +103,17 @@ __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist,
     const int b = blockIdx.x;
     const int n = len[b];
     const int32_t* __restrict__ h = hist + (int64_t)b * stride;
-    int best = -1;
+    int64_t key = -1;
     for (int c = threadIdx.x; c < nchunks; c += 64) {
-        const int v = chunk_best[(int64_t)b * nchunks + c];
-        if (v >= 0) {
-            if (policy == CS_POLICY_RIGHTMOST) best = max(best, v);
-            else best = best < 0 ? v : min(best, v);
-        }
+        const int64_t v = chunk_best[(int64_t)b * nchunks + c];
+        key = policy == CS_POLICY_FIRST ? key_better<CS_POLICY_FIRST>(key, v) : key_better<CS_POLICY_RIGHTMOST>(key, v);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-        const int other = __shfl_xor(best, o, 64);
-        if (policy == CS_POLICY_RIGHTMOST) best = max(best, other);
-        else best = best < 0 ? other : (other < 0 ? best : min(best, other));
+        const int64_t other = __shfl_xor(key, o, 64);
+        key = policy == CS_POLICY_FIRST ? key_better<CS_POLICY_FIRST>(key, other) : key_better<CS_POLICY_RIGHTMOST>(key, other);
     }
+    const int best = key < 0 ? -1 : (int)(key & 0x7fffffff);      // low word: the position
     const int src = best < 0 ? -1 : best + gamma;
     int dl = best < 0 ? 0 : min(k, n - src);
     if (room) dl = min(dl, max(room[b] - 1, 0));   // never draft past the emission budget
@@ -111,7 +126,7 @@ __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist,
 }
 
 // library-owned scratch for the per-chunk results; grown on demand (synchronises then)
-static int32_t* g_chunk_best = nullptr;
+static int64_t* g_chunk_best = nullptr;
 static size_t g_chunk_best_n = 0;
 
 int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B, int gamma,
@@ -125,7 +140,7 @@ int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, 
         if (g_chunk_best) CS_HIP(hipFree(g_chunk_best));
         g_chunk_best = nullptr;
         g_chunk_best_n = 0;
-        CS_HIP(hipMalloc(&g_chunk_best, need * sizeof(int32_t)));
+        CS_HIP(hipMalloc(&g_chunk_best, need * sizeof(int64_t)));
         g_chunk_best_n = need;
     }
     const int vec_ok = ((reinterpret_cast<uintptr_t>(d_hist) & 15) == 0) && (stride % 4 == 0);
@@ -134,9 +149,12 @@ int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, 
     if (policy == CS_POLICY_RIGHTMOST)
         k_scan<CS_POLICY_RIGHTMOST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
                                                                  g_chunk_best, nchunks);
-    else
+    else if (policy == CS_POLICY_FIRST)
         k_scan<CS_POLICY_FIRST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
                                                              g_chunk_best, nchunks);
+    else
+        k_scan<CS_POLICY_CONTEXT><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
+                                                               g_chunk_best, nchunks);
     cs_prof_end(ps, s);
     CS_TRY(cs_launch_ok("k_scan"));
     k_gather<<<B, 64, 0, s>>>(d_hist, stride, d_len, gamma, k, policy, g_chunk_best, nchunks, d_room,

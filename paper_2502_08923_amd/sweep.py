@@ -13,7 +13,8 @@ Two measurements are combined:
    search alone; the "target model" is the third version itself, so a draft token is accepted
    iff it equals the next token of that version.  This gives tokens emitted per step for
    every (gamma, k, policy) without any trained model.  The rightmost policy copies from the
-   second version (one round of edits away), the first-match policy from the original (two).
+   second version (one round of edits away), the first-match policy from the original (two);
+   the context policy ranks the candidates by the length of their agreeing backward context.
 
 emitted tokens/s = batch * (mean tokens per step) / (step time); the speed-up column is
 relative to k = 0.  The acceptance side is a projection for that edit law, not a property of
@@ -103,7 +104,7 @@ def main():
 
     table = []
     for gamma in (2, 3, 5, 10):
-        for policy in ("rightmost", "first"):
+        for policy in ("rightmost", "first", "context"):
             for r in rows:
                 k = r["k"]
                 tps, tau = replay_acceptance(cs, synth, gamma, k, policy)
@@ -119,7 +120,7 @@ def main():
     d_len = torch.full((64,), 32768, dtype=torch.int32, device="cuda:0")
     scan = []
     for gamma in (1, 2, 3, 5, 10, 16):
-        for policy in ("rightmost", "first"):
+        for policy in ("rightmost", "first", "context"):
             cs.cs_find_match_batch_dev(d_hist, d_len, gamma, 10, policy)
             torch.cuda.synchronize()
             cs.cs_profile_enable(["scan"])

@@ -69,16 +69,10 @@ def test_argmax_accept_full_size(host_model, B, k, V):
 
 
 # ----------------------------------------------------------------------------------------
-# projections at the 8B shapes, R = 88 (benchmark) and 528 (batch 16, k = 32); 104 .. 408
-# rows cover every row-tile count of the many-row kernel (one and two row blocks, ragged tails)
+# projections at the 8B shapes, R = 88 (benchmark) and 528 (batch 16, k = 32)
 # ----------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("N,K", [(6144, 4096), (4096, 4096), (28672, 4096), (4096, 14336),
-                                 (128256, 4096)])
-@pytest.mark.parametrize("R", [88, 528, 1, 104, 168, 200, 250, 264, 408])
-def test_gemm_bf16_full_shapes(host_model, N, K, R):
-    if R not in (88, 528, 1) and (N, K) not in ((6144, 4096), (4096, 14336)):
-        pytest.skip("intermediate row counts are checked on one wide and one K-split projection")
+def _gemm_case(host_model, N, K, R):
     seed = N * 7 + K + R
     xb = synth.workloads._draw(seed, (R, K), "n", 1.0, "bf16")
     wb = synth.workloads._draw(seed + 1, (N, K), "u", (3.0 / K) ** 0.5, "bf16")
@@ -90,6 +84,25 @@ def test_gemm_bf16_full_shapes(host_model, N, K, R):
     ref = x64 @ w64.T
     err = np.abs(Y[:, cols] - ref).max()
     assert err < 2e-4 * max(1.0, np.abs(ref).max()), err      # fp32 accumulation of exact products
+
+
+@pytest.mark.parametrize("N,K", [(6144, 4096), (4096, 4096), (28672, 4096), (4096, 14336),
+                                 (128256, 4096)])
+@pytest.mark.parametrize("R", [88, 528, 1])
+def test_gemm_bf16_full_shapes(host_model, N, K, R):
+    if R == 528 and N == 128256:
+        pytest.skip("covered at R=88 and, for the many-row kernel, by the row sweep below")
+    _gemm_case(host_model, N, K, R)
+
+
+@pytest.mark.parametrize("R", [97, 120, 168, 200, 250, 264, 300, 408, 528])
+@pytest.mark.parametrize("N,K", [(49168, 512), (49168, 128), (6144, 4096)])
+def test_gemm_row_sweep(host_model, N, K, R):
+    """Row counts between the two regimes.  The 193 W tiles of the 49168-row matrix send every
+    row count above 96 to the many-row kernel (each of its row-tile counts, one and two row
+    blocks, ragged last tiles in both dimensions, K of one and of four pipeline trips); the
+    q/k/v shape switches kernels at 289 rows and is split along K."""
+    _gemm_case(host_model, N, K, R)
 
 
 def test_gemm_tiny_weights_are_not_flushed(host_model):

@@ -45,7 +45,7 @@ def test_hand_cases():
             assert cs.cs_find_match(case["h"], case["gamma"]) == case["src"]
 
 
-@pytest.mark.parametrize("policy", ["rightmost", "first"])
+@pytest.mark.parametrize("policy", ["rightmost", "first", "context"])
 def test_cfg2_all_histories(policy):
     """Configuration 2 in full: 64 histories x 32768 tokens, gamma=3, k=10."""
     gens = [synth.history_cfg2(s) for s in range(64)]
@@ -53,8 +53,9 @@ def test_cfg2_all_histories(policy):
     _check_batch(hs, 3, 10, policy, stride=32768)
     d_hist, d_len = _batch(hs, 32768)
     mp = cs.cs_find_match_batch_dev(d_hist, d_len, 3, 10, policy)[0].cpu().numpy()
-    key = "rightmost_match" if policy == "rightmost" else "first_match"
-    assert mp.tolist() == [g[key] for g in gens]          # the generator's planted truth
+    if policy != "context":      # the generator records where the extreme candidates were planted
+        key = "rightmost_match" if policy == "rightmost" else "first_match"
+        assert mp.tolist() == [g[key] for g in gens]
 
 
 @pytest.mark.parametrize("gamma", [1, 2, 3, 5, 16])
@@ -65,7 +66,7 @@ def test_ragged_lengths_small_vocab(gamma, k):
     rng = np.random.default_rng(100 * gamma + k)
     lens = [0, 1, 2, 5, 6, 7, 63, 64, 65, 4095, 4096, 4097, 8191, 12289, 20000, 33]
     hs = [rng.integers(0, 2 + (i % 3), n).astype(np.int32) for i, n in enumerate(lens)]
-    for policy in ("rightmost", "first"):
+    for policy in ("rightmost", "first", "context"):
         _check_batch(hs, gamma, k, policy, stride=20000)
 
 
@@ -74,7 +75,7 @@ def test_degenerate_histories():
     period = np.tile(np.array([1, 2, 3], dtype=np.int32), 3000)
     nomatch = np.arange(10000, dtype=np.int32)
     late = np.concatenate([np.arange(5000), [7, 8, 9, 1, 2, 3], np.arange(100, 300), [7, 8, 9]]).astype(np.int32)
-    for policy in ("rightmost", "first"):
+    for policy in ("rightmost", "first", "context"):
         _check_batch([same, period, nomatch, late], 3, 10, policy)
     # unaligned stride takes the scalar load path
     _check_batch([same[:777], period[:1001], late], 3, 10, "rightmost", stride=5211)
@@ -115,7 +116,7 @@ def test_deterministic_repeat():
     assert all(torch.equal(x, y) for x, y in zip(a, b))
 
 
-@pytest.mark.parametrize("policy", ["rightmost", "first"])
+@pytest.mark.parametrize("policy", ["rightmost", "first", "context"])
 def test_acceptance_replay_matches_oracle(policy):
     """The gamma/k/policy sweep replays a synthetic self-correction dialogue through the library's
     match search; the same replay through the oracle's search must emit the same number of
