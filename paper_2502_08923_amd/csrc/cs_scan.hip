@@ -18,11 +18,15 @@
 #define SCAN_CHUNK 4096   // candidate positions per workgroup
 #define SCAN_CONTEXT_CAP 64
 
-// tokens before candidate p that equal the tokens before the suffix, counted backwards
-__device__ __forceinline__ int context_length(const int32_t* __restrict__ h, int p, int n, int gamma) {
-    int e = 0;
-    while (e < SCAN_CONTEXT_CAP && p - e - 1 >= 0 && h[p - e - 1] == h[n - gamma - e - 1]) ++e;
-    return e;
+// Tokens before candidate p that equal the tokens before the suffix, counted backwards up to
+// SCAN_CONTEXT_CAP = 64: the whole wave compares one position per lane, so the length is the
+// number of trailing ones of one ballot.  Must be called by all 64 lanes with the same p.
+__device__ __forceinline__ int context_length_wave(const int32_t* __restrict__ h, int p, int n, int gamma,
+                                                   int lane) {
+    const int i = p - lane - 1;
+    const bool same = i >= 0 && h[i] == h[n - gamma - lane - 1];
+    const unsigned long long agree = __ballot(same);
+    return agree == ~0ull ? SCAN_CONTEXT_CAP : __builtin_ctzll(~agree);
 }
 
 template <int POLICY>
@@ -54,7 +58,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
     if (begin < cnt) {
         const int end = min(cnt, begin + SCAN_CHUNK);
         const int s0 = h[n - gamma];
-        for (int p = begin + (int)threadIdx.x * 4; p < end; p += SCAN_THREADS * 4) {
+        // every lane runs every iteration (positions past the end just never hit), so the wave
+        // stays converged for the cooperative context measurement
+        for (int it = 0; it < SCAN_CHUNK / (SCAN_THREADS * 4); ++it) {
+            const int p = begin + (it * SCAN_THREADS + (int)threadIdx.x) * 4;
             int t[4];
             if (vec_ok && p + 3 < n) {
                 const int4 v = *reinterpret_cast<const int4*>(h + p);
@@ -63,13 +70,29 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
 #pragma unroll
                 for (int i = 0; i < 4; ++i) t[i] = (p + i < n) ? h[p + i] : ~s0;
             }
+            int hits = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int pp = p + i;
                 if (pp < end && t[i] == s0 && rest_matches(h, pp, n, gamma)) {
-                    int64_t key = pp;
-                    if (POLICY == CS_POLICY_CONTEXT) key |= (int64_t)context_length(h, pp, n, gamma) << 32;
-                    best = key_better<POLICY>(best, key);
+                    hits |= 1 << i;
+                    if (POLICY != CS_POLICY_CONTEXT) best = key_better<POLICY>(best, (int64_t)pp);
+                }
+            }
+            if (POLICY == CS_POLICY_CONTEXT) {
+                const int lane = threadIdx.x & 63;
+                unsigned long long pending = __ballot(hits != 0);
+                while (pending) {                                   // wave-uniform
+                    const int src = __builtin_ctzll(pending);
+                    pending &= pending - 1;
+                    const int p_src = __shfl(p, src, 64);
+                    const int h_src = __shfl(hits, src, 64);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (!((h_src >> i) & 1)) continue;          // wave-uniform
+                        const int e = context_length_wave(h, p_src + i, n, gamma, lane);
+                        if (lane == src) best = key_better<POLICY>(best, ((int64_t)e << 32) | (p_src + i));
+                    }
                 }
             }
         }
