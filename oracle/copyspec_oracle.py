@@ -393,3 +393,79 @@ def copyspec_decode(w: dict, prompt, max_new: int, gamma: int, k: int,
             stats["accepted"] += tau
             stats["taus"].append(tau)
     return out, stats
+
+
+def _top2_margin(row) -> float:
+    top = np.partition(np.asarray(row), -2)[-2:]
+    return float(top[1] - top[0])
+
+
+def merged_decode(w_target: dict, w_draft: dict, prompt, max_new: int, gamma: int, k: int,
+                  delta: int, policy: str = "rightmost"):
+    """CopySpec merged with vanilla speculative decoding (Sec. 3.3, App. B.3 steps 1-4).
+
+    Every step first looks for a copy opportunity (step 1).  With a match the copied block
+    is verified by the target model exactly as in copyspec_decode (step 2).  Without one the
+    draft model proposes delta tokens greedily, one at a time, continuing the accepted
+    sequence (step 3a); the target verifies them in one block with the same acceptance rule
+    (step 3b); both caches are truncated to the accepted prefix (step 3c).  The draft model
+    is only run when it is needed, so before drafting it first reads the tokens accepted
+    since it last ran.
+
+    Returns (tokens, stats); stats counts steps and, per branch, attempts / drafted /
+    accepted tokens, records the smallest top-2 logit margin of every target and of every
+    draft-model decision (how close the run came to a tie), and lists (history length,
+    proposed tokens) of every draft-model attempt in "spec_trace".
+    """
+    assert w_target["shape"].vocab == w_draft["shape"].vocab
+    cap = len(prompt) + max_new + max(k, delta) + 2
+    kv_t = KVCache(w_target["shape"], cap)
+    kv_d = KVCache(w_draft["shape"], cap)
+    seq = [int(t) for t in prompt]
+    pending = prefill(w_target, kv_t, seq)
+    out = []
+    st = {"steps": 0, "copy_attempts": 0, "copy_drafted": 0, "copy_accepted": 0,
+          "spec_attempts": 0, "spec_drafted": 0, "spec_accepted": 0,
+          "target_margin": np.inf, "draft_margin": np.inf, "spec_trace": []}
+    while len(out) < max_new:
+        room = max_new - len(out) - 1                      # drafts that can still be emitted
+        n = len(seq)
+        _, _, draft = find_match_np(seq, gamma, k, policy) if n > 64 else find_match(seq, gamma, k, policy)
+        draft = draft[:room]
+        copied = len(draft) > 0
+        if not copied and delta > 0 and room > 0:
+            # draft model: catch up on seq[kv_d.length : n-1], then generate from the pending token
+            while kv_d.length < n - 1:
+                part = seq[kv_d.length:min(n - 1, kv_d.length + 64)]
+                forward_block(w_draft, kv_d, part, return_hidden=True)
+                kv_d.truncate(kv_d.length + len(part))
+            tok = pending
+            for _ in range(min(delta, room)):
+                lg = forward_block(w_draft, kv_d, [tok])
+                kv_d.truncate(kv_d.length + 1)
+                st["draft_margin"] = min(st["draft_margin"], _top2_margin(lg[0]))
+                tok = argmax_first(lg[0])
+                draft.append(tok)
+            st["spec_trace"].append((n, list(draft)))
+        L = kv_t.length
+        logits = forward_block(w_target, kv_t, [pending] + draft)
+        am = [argmax_first(r) for r in logits]
+        tau, nxt = accept_prefix(am, draft)
+        kv_t.truncate(L + tau + 1)
+        for i in range(tau + 1):
+            st["target_margin"] = min(st["target_margin"], _top2_margin(logits[i]))
+        if draft and not copied:
+            # the draft cache holds seq[0:n] and the drafts it was fed (all but the last one)
+            kv_d.truncate(n + min(tau, len(draft) - 1))
+        new = draft[:tau] + [nxt]
+        seq.extend(new)
+        out.extend(new)
+        pending = nxt
+        st["steps"] += 1
+        if draft:
+            key = "copy" if copied else "spec"
+            st[key + "_attempts"] += 1
+            st[key + "_drafted"] += len(draft)
+            st[key + "_accepted"] += tau
+    return out, st
+

@@ -266,3 +266,76 @@ def test_one_guaranteed_token_per_step(small_w):
     assert kv.length == L + tau + 1 and 0 <= nxt < SMALL.vocab
     with pytest.raises(ValueError):
         orc.forward_block(small_w, kv, list(range(64)))
+
+
+# ----------------------------------------------------------------------------------------
+# CopySpec merged with speculative decoding (Sec. 3.3, App. B.3 step 3)
+# ----------------------------------------------------------------------------------------
+
+def _looping_prompt(rng, n=36):
+    """A prompt that already contains a repeated span, so the copy branch fires early."""
+    p = rng.integers(0, SMALL.vocab, n).tolist()
+    p[n - 9:n - 3] = p[4:10]
+    return p
+
+
+def test_merged_output_is_greedy_for_any_draft_model(small_w):
+    """Whatever the draft model proposes, the emitted sequence is the target's greedy sequence
+    (Sec. 3.3: the merge changes speed only).  Three draft models: unrelated weights, the
+    target itself, and a model that always repeats its input token."""
+    rng = np.random.default_rng(77)
+    other = synth.model_weights(SMALL, 4321, threads=1)
+    rep = synth.model_weights(SMALL, 99, threads=1)
+    for lw in rep["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["wd"] = np.zeros_like(lw["wd"])
+    rep["lm_head"] = rep["embed"].copy()
+    rep["final_norm"] = np.ones_like(rep["final_norm"])
+    for trial in range(3):
+        prompt = _looping_prompt(rng)
+        ref = orc.greedy_decode(small_w, prompt, 48)
+        for wd in (other, small_w, rep):
+            for gamma, k, delta in ((3, 10, 4), (2, 5, 3), (3, 0, 5)):
+                out, st = orc.merged_decode(small_w, wd, prompt, 48, gamma, k, delta)
+                assert out == ref, (trial, gamma, k, delta)
+                assert st["copy_accepted"] <= st["copy_drafted"] and st["spec_accepted"] <= st["spec_drafted"]
+                assert st["copy_attempts"] + st["spec_attempts"] <= st["steps"]
+                if k == 0:
+                    assert st["copy_attempts"] == 0
+                if wd is small_w:              # a perfect draft model is never rejected
+                    assert st["spec_accepted"] == st["spec_drafted"]
+
+
+def test_merged_pure_speculative_closed_form(small_w):
+    """No copying (k = 0) and draft == target: every step emits delta + 1 tokens until the
+    budget clamps the last block."""
+    rng = np.random.default_rng(78)
+    prompt = rng.integers(0, SMALL.vocab, 17).tolist()
+    out, st = orc.merged_decode(small_w, small_w, prompt, 23, 3, 0, 4)
+    assert out == orc.greedy_decode(small_w, prompt, 23)
+    # 5 + 5 + 5 + 5 + 3 tokens: drafts of 4, 4, 4, 4 and min(4, 23 - 20 - 1) = 2
+    assert (st["steps"], st["spec_attempts"], st["spec_drafted"], st["spec_accepted"]) == (5, 5, 18, 18)
+
+
+def test_merged_draft_cache_is_never_stale(small_w):
+    """Catch-up and rollback of the draft model's cache: what it proposes at every attempt
+    equals a fresh greedy continuation, by the draft model, of the sequence accepted so far."""
+    rng = np.random.default_rng(79)
+    other = synth.model_weights(SMALL, 555, threads=1)
+    prompt = _looping_prompt(rng)
+    out, st = orc.merged_decode(small_w, other, prompt, 40, 3, 6, 4)
+    assert st["spec_attempts"] >= 3 and st["copy_attempts"] >= 1     # both branches ran
+    seq = prompt + out
+    for n, proposed in st["spec_trace"]:
+        assert proposed == orc.greedy_decode(other, seq[:n], len(proposed)), n
+
+
+def test_merged_without_draft_model_is_copyspec(small_w):
+    rng = np.random.default_rng(80)
+    prompt = _looping_prompt(rng)
+    a, sa = orc.merged_decode(small_w, small_w, prompt, 40, 3, 8, 0)
+    b, sb = orc.copyspec_decode(small_w, prompt, 40, 3, 8)
+    assert a == b
+    assert (sa["steps"], sa["copy_attempts"], sa["copy_accepted"], sa["spec_attempts"]) == \
+           (sb["steps"], sb["attempts"], sb["accepted"], 0)
+
