@@ -209,6 +209,38 @@ int cs_decode_greedy(cs_model* m, cs_kv* kv, const int32_t* prompt /*host*/, int
                      int64_t max_new, int32_t eos_id, int32_t* out_tokens /*host*/,
                      int64_t* n_out);
 
+/* ------------------------------------------------------------------------------------
+ * CopySpec merged with draft-model speculative decoding  (Sec. 3.3; App. B.3 steps 1-4)
+ *
+ * Every step first looks for a copy opportunity (App. B.3 step 1).  With a match the copied
+ * block is verified as in cs_decode (step 2).  Without one, a second, smaller model (its own
+ * handle and its own single-stream cache, same vocabulary) proposes up to `delta` tokens
+ * greedily, one per forward pass, continuing the accepted sequence (step 3a); the target
+ * verifies them in one block with the same acceptance rule (step 3b) and both caches are cut
+ * back to the accepted prefix (step 3c).  The draft model runs only when it is needed and
+ * first reads the tokens accepted since it last ran.  The emitted tokens are the target's
+ * greedy tokens whatever the draft model proposes.  delta = 0 is cs_decode.
+ * Requires 0 <= delta <= the target's max_k, target capacity >= prompt_len + max_new +
+ * max(k, delta) + 1, draft capacity >= prompt_len + max_new + delta + 1.  prompt and
+ * out_tokens are host pointers.  Synchronous.
+ * ---------------------------------------------------------------------------------- */
+typedef struct cs_merged_stats {
+    int64_t steps;            /* target verify calls */
+    int64_t copy_attempts;    /* steps whose draft was copied from the history */
+    int64_t copy_drafted;
+    int64_t copy_accepted;
+    int64_t spec_attempts;    /* steps whose draft came from the draft model */
+    int64_t spec_drafted;
+    int64_t spec_accepted;
+    int64_t draft_forwards;   /* forward passes of the draft model (catch-up blocks + proposals) */
+} cs_merged_stats;
+
+int cs_decode_merged(cs_model* target, cs_kv* target_kv, cs_model* draft, cs_kv* draft_kv,
+                     const int32_t* prompt /*host*/, int64_t prompt_len, int64_t max_new,
+                     int32_t gamma, int32_t k, int32_t policy, int32_t delta, int32_t eos_id,
+                     int32_t* out_tokens /*host*/, int64_t* n_out,
+                     cs_merged_stats* stats /*may be NULL*/);
+
 /* Run prompt[0 .. n-1) of one stream through the model in blocks so that its cache holds
  * them and its length is n-1 (the last prompt token stays pending).  Resets the stream's
  * length first.  prompt: host.  Synchronous. */

@@ -25,7 +25,7 @@ EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev",
     "cs_model_create", "cs_model_destroy", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
-    "cs_decode_greedy", "cs_prefill", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
+    "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
     "cs_set_plain_kernels", "cs_kv_set_len_dev", "cs_profile_enable", "cs_profile_reset",
     "cs_profile_read",
 ]
@@ -57,6 +57,12 @@ class cs_weights(C.Structure):
 
 class cs_stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("steps", "attempts", "drafted", "accepted")]
+
+
+class cs_merged_stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("steps", "copy_attempts", "copy_drafted", "copy_accepted",
+                                         "spec_attempts", "spec_drafted", "spec_accepted",
+                                         "draft_forwards")]
 
 
 _lib = None
@@ -96,6 +102,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_decode.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, C.POINTER(i64),
                               C.POINTER(cs_stats)]
     lib.cs_decode_greedy.argtypes = [vp, vp, vp, i64, i64, i32, vp, C.POINTER(i64)]
+    lib.cs_decode_merged.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp,
+                                     C.POINTER(i64), C.POINTER(cs_merged_stats)]
     lib.cs_prefill.argtypes = [vp, vp, i32, vp, i64]
     lib.cs_op_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp]
     lib.cs_op_attention.argtypes = [vp, vp, i32, vp, i32, vp, vp]
@@ -364,6 +372,18 @@ def cs_decode_greedy(model: Model, kv: KV, prompt: Sequence[int], max_new: int, 
     _check(load_library().cs_decode_greedy(model.handle, kv.handle, p.ctypes.data, p.shape[0],
                                            max_new, eos_id, out.ctypes.data, C.byref(n_out)))
     return out[:n_out.value].tolist()
+
+
+def cs_decode_merged(model: Model, kv: KV, draft_model: Model, draft_kv: KV, prompt: Sequence[int],
+                     max_new: int, gamma: int, k: int, delta: int, policy="rightmost", eos_id: int = -1):
+    """Returns (tokens list, stats dict)."""
+    p = np.ascontiguousarray(prompt, dtype=np.int32)
+    out = np.zeros(max(max_new, 1), dtype=np.int32)
+    n_out, st = C.c_int64(), cs_merged_stats()
+    _check(load_library().cs_decode_merged(model.handle, kv.handle, draft_model.handle, draft_kv.handle,
+                                           p.ctypes.data, p.shape[0], max_new, gamma, k, _policy(policy),
+                                           delta, eos_id, out.ctypes.data, C.byref(n_out), C.byref(st)))
+    return out[:n_out.value].tolist(), {n: getattr(st, n) for n, _ in cs_merged_stats._fields_}
 
 
 def cs_prefill(model: Model, kv: KV, stream_idx: int, prompt: Sequence[int]):

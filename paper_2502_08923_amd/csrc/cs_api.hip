@@ -691,6 +691,130 @@ extern "C" int cs_decode_greedy(cs_model* m, cs_kv* kv, const int32_t* prompt, i
 }
 
 // -------------------------------------------------------------------------------------
+// CopySpec merged with draft-model speculative decoding (Sec. 3.3, App. B.3 steps 1-4)
+// -------------------------------------------------------------------------------------
+extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv, const int32_t* prompt,
+                                int64_t prompt_len, int64_t max_new, int32_t gamma, int32_t k,
+                                int32_t policy, int32_t delta, int32_t eos_id, int32_t* out_tokens,
+                                int64_t* n_out, cs_merged_stats* stats) {
+    CS_REQUIRE(out_tokens && n_out, CS_E_ARG, "cs_decode_merged: NULL output");
+    CS_REQUIRE(max_new >= 0, CS_E_ARG, "max_new must be >= 0");
+    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(check_verify_args(m, kv, k));
+    CS_REQUIRE(dm && dkv && dkv->m == dm, CS_E_ARG, "cs_decode_merged: draft model and its cache do not match");
+    CS_REQUIRE(dm != m && dkv != kv, CS_E_ARG, "the draft model needs a model handle and a cache of its own");
+    CS_REQUIRE(dm->cfg.vocab == m->cfg.vocab, CS_E_ARG, "draft and target vocabularies differ (%d vs %d)",
+               dm->cfg.vocab, m->cfg.vocab);
+    CS_REQUIRE(delta >= 0 && delta <= m->cfg.max_k, CS_E_ARG, "delta=%d outside 0..max_k=%d", delta,
+               m->cfg.max_k);
+    CS_REQUIRE(kv->B == 1 && dkv->B == 1, CS_E_UNSUPPORTED, "cs_decode_merged needs single-stream caches");
+    CS_REQUIRE(prompt && prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
+    const int kmax = k > delta ? k : delta;
+    CS_REQUIRE(prompt_len + max_new + kmax + 1 <= kv->cap, CS_E_CAPACITY,
+               "target cache capacity %lld < prompt_len + max_new + max(k, delta) + 1", (long long)kv->cap);
+    CS_REQUIRE(prompt_len + max_new + delta + 1 <= dkv->cap, CS_E_CAPACITY,
+               "draft cache capacity %lld < prompt_len + max_new + delta + 1", (long long)dkv->cap);
+    cs_merged_stats st = {0, 0, 0, 0, 0, 0, 0, 0};
+    *n_out = 0;
+    CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));
+    CS_TRY(cs_kv_set_len(dkv, 0, 0));
+    int64_t draft_rows = 0;                       // rows of the accepted sequence in the draft cache
+
+    const int64_t stride = cs_round_up(prompt_len + max_new + kmax + 2, 4);
+    int32_t* d = nullptr;
+    CS_HIP(hipMalloc(&d, (size_t)(stride + 16 + (delta > 0 ? delta : 1)) * 4));
+    // d_len: [0] hist_len, [1] room, [2] accepted, [3] next, [4] draft_len, [5] scratch, [6] zero
+    int32_t* d_len = d + stride;
+    int32_t* d_proposed = d_len + 16;             // the draft model's tokens
+    int32_t init[7] = {(int32_t)prompt_len, (int32_t)max_new, 0, 0, 0, 0, 0};
+    int rc = CS_OK;
+    if (hipMemcpy(d, prompt, (size_t)prompt_len * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(d_len, init, sizeof(init), hipMemcpyHostToDevice) != hipSuccess) {
+        cs_set_error("cs_decode_merged: copy to device failed");
+        rc = CS_E_DEVICE;
+    }
+    hipStream_t s = nullptr;
+    int64_t emitted = 0, n = prompt_len;
+    bool stop = false;
+    // one step; returns through rc.  A lambda so that every exit path frees the buffer below.
+    auto step = [&]() -> int {
+        const int64_t room = max_new - emitted;
+        int dl = 0;
+        CS_REQUIRE(kv_max_ub(kv) + 1 + kmax + 1 <= stride, CS_E_CAPACITY, "history buffer may overflow");
+        // step 1: copy opportunity
+        if (k > 0) {
+            CS_TRY(cs_scan_launch(d, stride, d_len, 1, gamma, k, policy, n, m->match_pos, nullptr, m->draft,
+                                  m->draft_len, d_len + 1, s));
+            CS_HIP(hipMemcpy(&dl, m->draft_len, 4, hipMemcpyDeviceToHost));
+        }
+        k_pending<<<1, 64, 0, s>>>(d, stride, d_len, 1, m->pending);
+        CS_TRY(cs_launch_ok("k_pending"));
+        int block = 0, proposed = 0;
+        const int32_t* draft_ptr = m->draft;
+        const int32_t* len_ptr = d_len + 6;       // zero: a plain decode step
+        if (dl > 0) {                             // step 2: verify the copied block
+            block = k;
+            len_ptr = m->draft_len;
+        } else if (delta > 0 && room > 1) {       // step 3: the draft model proposes
+            proposed = (int)(delta < room - 1 ? delta : room - 1);
+            while (draft_rows < n - 1) {          // read what was accepted since it last ran
+                const int64_t left = n - 1 - draft_rows;
+                const int rows = (int)(left < dm->rows_max ? left : dm->rows_max);
+                CS_HIP(hipMemcpyAsync(dm->tok, d + draft_rows, (size_t)rows * 4, hipMemcpyDeviceToDevice, s));
+                CS_TRY(forward_layers(dm, dkv, rows, s));
+                k_add_i32<<<1, 64, 0, s>>>(dkv->d_len, rows, 1);
+                CS_TRY(cs_launch_ok("k_add_i32"));
+                dkv->h_len_ub[0] += rows;
+                draft_rows += rows;
+                st.draft_forwards += 1;
+            }
+            for (int i = 0; i < proposed; ++i) {  // one greedy token per forward pass
+                const int32_t* tok = i == 0 ? m->pending : d_proposed + i - 1;
+                CS_TRY(verify_impl(dm, dkv, tok, nullptr, d_len + 6, 0, d_len + 5, d_proposed + i, nullptr,
+                                   nullptr, 0, nullptr, nullptr, s));
+                draft_rows += 1;
+                st.draft_forwards += 1;
+            }
+            CS_TRY(cs_fill_i32_launch(d_len + 4, proposed, 1, s));
+            block = proposed;
+            draft_ptr = d_proposed;
+            len_ptr = d_len + 4;
+        }
+        CS_TRY(verify_impl(m, kv, m->pending, draft_ptr, len_ptr, block, d_len + 2, d_len + 3, nullptr, d,
+                           stride, d_len, d_len + 1, s));
+        int32_t h[4];
+        CS_HIP(hipMemcpy(h, d_len, sizeof(h), hipMemcpyDeviceToHost));
+        const int tau = h[2], got = tau + 1;
+        kv->h_len_ub[0] = h[0] - 1;               // true length: everything but the pending token
+        if (proposed > 0) {
+            // the draft cache holds the old sequence and every proposal it was fed (all but the last)
+            draft_rows = n + (tau < proposed - 1 ? tau : proposed - 1);
+            CS_TRY(cs_kv_set_len(dkv, 0, draft_rows));
+        }
+        CS_HIP(hipMemcpy(out_tokens + emitted, d + (h[0] - got), (size_t)got * 4, hipMemcpyDeviceToHost));
+        n = h[0];
+        st.steps += 1;
+        if (dl > 0) { st.copy_attempts += 1; st.copy_drafted += dl; st.copy_accepted += tau; }
+        if (proposed > 0) { st.spec_attempts += 1; st.spec_drafted += proposed; st.spec_accepted += tau; }
+        for (int i = 0; i < got; ++i) {
+            if (eos_id >= 0 && out_tokens[emitted + i] == eos_id) {
+                emitted += i + 1;
+                stop = true;
+                return CS_OK;
+            }
+        }
+        emitted += got;
+        return CS_OK;
+    };
+    while (rc == CS_OK && emitted < max_new && !stop) rc = step();
+    (void)hipFree(d);
+    if (rc != CS_OK) return rc;
+    *n_out = emitted;
+    if (stats) *stats = st;
+    return CS_OK;
+}
+
+// -------------------------------------------------------------------------------------
 // single operations
 // -------------------------------------------------------------------------------------
 extern "C" int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void* W, float* Y, int32_t R,

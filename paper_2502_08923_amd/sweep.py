@@ -19,6 +19,13 @@ Two measurements are combined:
 emitted tokens/s = batch * (mean tokens per step) / (step time); the speed-up column is
 relative to k = 0.  The acceptance side is a projection for that edit law, not a property of
 a language model.
+
+3. (--merged) Cost of the merge with draft-model speculative decoding (Sec. 3.3): one stream,
+   8B-shape target, 1B-shape draft model (same vocabulary), 4096-token prompt with planted
+   repeats, 64 new tokens through plain greedy decoding, CopySpec alone and the merged loop with
+   delta = 3 and 5.  With random-init weights nothing is accepted, so the figures are the cost
+   side only: time per target step, per draft-model forward pass, and the acceptance a merged
+   step needs to break even with plain decoding.
 """
 from __future__ import annotations
 
@@ -64,12 +71,55 @@ def replay_acceptance(cs, synth, gamma: int, k: int, policy: str, streams=(0, 1,
     return tot_tokens / tot_steps, (accepted / attempts if attempts else 0.0)
 
 
+def merged_costs(cs, synth, model, torch):
+    """Wall-clock cost of greedy / CopySpec / merged decoding of one stream (see the module text)."""
+    draft_shape = synth.LLAMA_1B.with_vocab(model.shape.vocab)
+    wd = synth.model_weights(draft_shape, synth.seed_for(3), threads=16)
+    dmodel = cs.Model(wd, max_batch=1, max_k=31)
+    prompt = synth.history_cfg4(0)["tokens"][:4096].tolist()
+    new, cap = 64, 4096 + 64 + 128
+    kv, dkv = cs.KV(model, 1, cap), cs.KV(dmodel, 1, cap)
+    rows = []
+
+    def timed(label, fn):
+        fn()                                              # warm-up (includes the prompt pass)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = fn()
+        torch.cuda.synchronize()
+        return label, time.perf_counter() - t0, out
+
+    t_prefill = timed("prefill", lambda: cs.cs_prefill(model, kv, 0, prompt))[1]
+    label, t, out = timed("greedy", lambda: cs.cs_decode_greedy(model, kv, prompt, new))
+    greedy = out
+    t_plain_step = (t - t_prefill) / new
+    rows.append({"mode": label, "total_ms": t * 1e3, "steps": new, "ms_per_target_step": t_plain_step * 1e3})
+    label, t, (out, st) = timed("copyspec k=10", lambda: cs.cs_decode(model, kv, prompt, new, 3, 10))
+    assert out == greedy
+    rows.append({"mode": label, "total_ms": t * 1e3, "steps": st["steps"], "copy_attempts": st["attempts"],
+                 "ms_per_target_step": (t - t_prefill) / st["steps"] * 1e3})
+    for delta in (3, 5):
+        label, t, (out, st) = timed(f"merged k=10 delta={delta}",
+                                    lambda: cs.cs_decode_merged(model, kv, dmodel, dkv, prompt, new, 3, 10, delta))
+        assert out == greedy
+        # every step here is a rejected proposal: target block of delta+1 rows + delta draft forwards
+        t_step = (t - t_prefill) / st["steps"]
+        rows.append({"mode": label, "total_ms": t * 1e3, "steps": st["steps"], "copy_attempts": st["copy_attempts"],
+                     "spec_attempts": st["spec_attempts"], "draft_forwards": st["draft_forwards"],
+                     "ms_per_merged_step": t_step * 1e3,
+                     "break_even_tokens_per_step": t_step / t_plain_step})
+    for h in (dkv, kv, dmodel):
+        h.destroy()
+    return {"prefill_ms": t_prefill * 1e3, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=0, help="depth override (0 = full 32 layers)")
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--ks", default="0,5,10,20,32,50,100")
     ap.add_argument("--json", default="")
+    ap.add_argument("--merged", action="store_true", help="also time the merge with a draft model")
     args = ap.parse_args()
 
     import numpy as np
@@ -131,7 +181,8 @@ def main():
             cs.cs_profile_enable([])
             scan.append({"gamma": gamma, "policy": policy, "kernel_us": ms / n * 1e3})
 
-    out = {"step_cost": rows, "projection": table, "scan": scan,
+    merged = merged_costs(cs, synth, st["model"], torch) if args.merged else None
+    out = {"step_cost": rows, "projection": table, "scan": scan, "merged": merged,
            "workload": f"llama-8b shape x{st['shape'].n_layers} layers, batch {B}, KV {st['L']}"}
     if args.json:
         with open(args.json, "w") as f:
@@ -147,6 +198,15 @@ def main():
     print("|---|---|---|")
     for r in scan:
         print(f"| {r['gamma']} | {r['policy']} | {r['kernel_us']:.2f} |")
+    if merged:
+        print()
+        print(f"One stream, 4096-token prompt (prompt pass {merged['prefill_ms']:.1f} ms, subtracted below), 64 new tokens:")
+        print("| mode | steps | ms per step | break-even tokens per step |")
+        print("|---|---|---|---|")
+        for r in merged["rows"]:
+            ms = r.get("ms_per_merged_step", r.get("ms_per_target_step"))
+            be = f"{r['break_even_tokens_per_step']:.2f}" if "break_even_tokens_per_step" in r else "-"
+            print(f"| {r['mode']} | {r['steps']} | {ms:.2f} | {be} |")
 
 
 if __name__ == "__main__":

@@ -48,6 +48,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(binding.cs_layer_weights) == 9 * 8
     assert ctypes.sizeof(binding.cs_weights) == 4 * 8
     assert ctypes.sizeof(binding.cs_stats) == 4 * 8
+    assert ctypes.sizeof(binding.cs_merged_stats) == 8 * 8
 
 
 def test_version_and_error_strings_without_gpu(lib):

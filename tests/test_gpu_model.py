@@ -229,6 +229,125 @@ def test_decode_invariance_bf16_models():
         model.destroy()
 
 
+# ----------------------------------------------------------------------------------------
+# CopySpec merged with draft-model speculative decoding (Sec. 3.3, App. B.3 step 3)
+# ----------------------------------------------------------------------------------------
+
+DRAFT_TINY = ModelShape("tiny-draft", 1, 128, 2, 2, 64, 256, 1024, 10000.0, 1e-5, "f32")
+
+
+def _noisy_head(w, scale, seed):
+    """A stand-in for a distilled draft model: the target with a perturbed lm_head, so that it
+    agrees with the target on most tokens but not all."""
+    rng = np.random.default_rng(seed)
+    d = w["shape"].d_model
+    noise = rng.standard_normal(w["lm_head"].shape).astype(np.float32) * np.float32(scale / np.sqrt(d))
+    return {"shape": w["shape"], "embed": w["embed"], "final_norm": w["final_norm"],
+            "lm_head": (w["lm_head"] + noise).astype(np.float32), "layers": w["layers"]}
+
+
+def _repeat_model(shape, seed):
+    """Attention and FFN outputs zeroed, lm_head = embedding: the greedy token repeats the input."""
+    w = synth.model_weights(shape, seed, threads=4)
+    for lw in w["layers"]:
+        lw["wo"] = np.zeros_like(lw["wo"])
+        lw["wd"] = np.zeros_like(lw["wd"])
+    w["lm_head"] = w["embed"].copy()
+    w["final_norm"] = np.ones_like(w["final_norm"])
+    return w
+
+
+FP32_MARGIN = 1e-3      # float32 models agree with the oracle to 1e-4, so decisions are the
+                        # oracle's wherever its top-2 margin exceeds this (stricter than 1e-2)
+STAT_KEYS = ("steps", "copy_attempts", "copy_drafted", "copy_accepted", "spec_attempts", "spec_drafted",
+             "spec_accepted")
+
+
+def test_merged_decode_tiny_matches_greedy_and_oracle(tiny):
+    """Configuration 1 prompt with draft models that agree with the target on part of the
+    tokens: the merged loop emits the plain greedy sequence, and its step counts and per-branch
+    statistics equal the oracle's whenever no target or draft decision of the oracle run came
+    within FP32_MARGIN of a tie."""
+    w, model = tiny
+    prompt = synth.history_cfg1()["tokens"].tolist()
+    kv = cs.KV(model, 1, 512 + 64 + 16)
+    greedy = cs.cs_decode_greedy(model, kv, prompt, 64)
+    compared = accepted = 0
+    for scale, seed, (gamma, k, delta) in ((0.1, 1, (3, 10, 4)), (0.4, 1, (3, 10, 4)), (0.2, 1, (2, 6, 3)),
+                                           (0.4, 1, (3, 0, 5)), (0.1, 1, (3, 10, 0))):
+        wd = _noisy_head(w, scale, seed)
+        dmodel = cs.Model(wd, max_batch=1, max_k=7)     # 8-row catch-up blocks
+        dkv = cs.KV(dmodel, 1, 512 + 64 + 16)
+        out, st = cs.cs_decode_merged(model, kv, dmodel, dkv, prompt, 64, gamma, k, delta)
+        assert out == greedy, (scale, gamma, k, delta)
+        oout, ost = orc.merged_decode(w, wd, prompt, 64, gamma, k, delta)
+        if min(ost["target_margin"], ost["draft_margin"]) > FP32_MARGIN:
+            assert out == oout
+            assert {key: st[key] for key in STAT_KEYS} == {key: ost[key] for key in STAT_KEYS}
+            compared += 1
+            accepted += st["spec_accepted"]
+        if k == 0:
+            assert st["copy_attempts"] == 0
+        if delta == 0:
+            assert st["spec_attempts"] == 0 and st["draft_forwards"] == 0
+        dkv.destroy()
+        dmodel.destroy()
+    assert compared >= 3 and accepted >= 60            # the comparison is not vacuous
+    # the target as its own draft model (a second handle): nothing is ever rejected
+    twin = cs.Model(w, max_batch=1, max_k=10)
+    tkv = cs.KV(twin, 1, 512 + 64 + 16)
+    out, st = cs.cs_decode_merged(model, kv, twin, tkv, prompt, 64, 3, 0, 4)
+    assert out == greedy and st["spec_accepted"] == st["spec_drafted"] and st["steps"] == 13   # ceil(64 / 5)
+    for h in (tkv, twin, kv):
+        h.destroy()
+
+
+def test_merged_decode_copy_branch_accepts_and_draft_catches_up():
+    """A target that repeats its input makes the history x, x, x, ...: the first steps find no
+    match and go to the draft model (unrelated weights, everything rejected), then copied
+    blocks are accepted in full under every match policy.  Statistics equal the oracle's."""
+    w = _repeat_model(SMALLF32, 99)
+    wd = synth.model_weights(SMALLF32.with_layers(1), 5, threads=4)
+    model, dmodel = cs.Model(w, max_batch=1, max_k=10), cs.Model(wd, max_batch=1, max_k=3)
+    kv, dkv = cs.KV(model, 1, 256), cs.KV(dmodel, 1, 256)
+    prompt = [3, 1, 4, 1, 5, 9, 2, 6]
+    for gamma, k, delta, policy in ((3, 10, 2, "first"), (3, 10, 3, "rightmost"), (2, 5, 1, "context")):
+        out, st = cs.cs_decode_merged(model, kv, dmodel, dkv, prompt, 60, gamma, k, delta, policy)
+        assert out == [6] * 60
+        oout, ost = orc.merged_decode(w, wd, prompt, 60, gamma, k, delta, policy)
+        assert oout == out and ost["target_margin"] > FP32_MARGIN
+        if ost["draft_margin"] > FP32_MARGIN:
+            assert {key: st[key] for key in STAT_KEYS} == {key: ost[key] for key in STAT_KEYS}
+        assert st["copy_accepted"] == st["copy_drafted"] > 0
+    for h in (dkv, kv, dmodel, model):
+        h.destroy()
+
+
+def test_merged_decode_bf16_models_and_errors():
+    shape = MINI64
+    w = synth.model_weights(shape, 31337, threads=4)
+    wd = synth.model_weights(shape.with_layers(1), 777, threads=4)
+    model, dmodel = cs.Model(w, max_batch=1, max_k=10), cs.Model(wd, max_batch=1, max_k=10)
+    g = synth.planted_history(17, 400, shape.vocab, (16, 32), density=0.3, end="span")
+    prompt = g["tokens"].tolist()
+    kv, dkv = cs.KV(model, 1, 400 + 96 + 16), cs.KV(dmodel, 1, 400 + 96 + 16)
+    greedy = cs.cs_decode_greedy(model, kv, prompt, 96)
+    out, st = cs.cs_decode_merged(model, kv, dmodel, dkv, prompt, 96, 3, 10, 4)
+    n_same = next((i for i in range(96) if out[i] != greedy[i]), 96)     # see test_decode_invariance_bf16_models
+    assert len(out) == 96 and n_same >= 48, n_same
+    assert st["copy_attempts"] >= 1 and st["spec_attempts"] >= 1 and st["draft_forwards"] > st["spec_drafted"]
+    with pytest.raises(cs.CopySpecError):        # the draft model needs handles of its own
+        cs.cs_decode_merged(model, kv, model, kv, prompt, 8, 3, 10, 4)
+    with pytest.raises(cs.CopySpecError):        # delta beyond the target's block size
+        cs.cs_decode_merged(model, kv, dmodel, dkv, prompt, 8, 3, 10, 11)
+    small = cs.KV(dmodel, 1, 64)
+    with pytest.raises(cs.CopySpecError) as e:   # draft cache too small
+        cs.cs_decode_merged(model, kv, dmodel, small, prompt, 8, 3, 10, 4)
+    assert e.value.code == -3
+    for h in (small, dkv, kv, dmodel, model):
+        h.destroy()
+
+
 def test_capacity_and_argument_errors(tiny):
     w, model = tiny
     kv = cs.KV(model, 1, 64)
