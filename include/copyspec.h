@@ -88,6 +88,33 @@ int cs_find_match_batch_dev(const int32_t* d_hist /*device*/, int64_t stride,
                             int32_t* d_draft, int32_t* d_draft_len, void* stream);
 
 /* ------------------------------------------------------------------------------------
+ * Gamma-gram index  (Sec. 3.1: "a dictionary of all gamma-token subsequences and their
+ * locations, updated as tokens are appended"; App. B.1 "Dictionary D"; App. B.3 steps 1b, 2d)
+ *
+ * The paper's own data structure as an alternative to the scan, for very long histories:
+ * one hash table per stream on the device, keyed by the gamma tokens themselves (entries
+ * are verified against the history, so results never depend on hash collisions).  At history
+ * length n it holds the grams starting at p <= n - 2*gamma, the candidates App. B.3 step 1c
+ * admits; each call first inserts the grams that became admissible since the previous call,
+ * then looks up the last gamma tokens.  Results equal cs_find_match_batch_dev for
+ * CS_POLICY_RIGHTMOST and CS_POLICY_FIRST (other policies: CS_E_UNSUPPORTED).
+ * Histories may only grow between calls, and tokens already indexed must not change; call
+ * cs_index_reset otherwise.  gamma is fixed at creation; max_len bounds stride.
+ * max_new_positions: upper bound on how many tokens any stream gained since the previous
+ * call (max_len for the first call); it only sizes the launch.  Asynchronous on `stream`;
+ * calls on one index must be ordered on one stream.
+ * ---------------------------------------------------------------------------------- */
+typedef struct cs_index cs_index;
+int cs_index_create(int32_t B, int64_t max_len, int32_t gamma, cs_index** out);
+void cs_index_destroy(cs_index*);
+int cs_index_reset(cs_index*, void* stream);
+int cs_index_find_match_batch_dev(cs_index*, const int32_t* d_hist /*device*/, int64_t stride,
+                                  const int32_t* d_len /*device [B]*/, int64_t max_new_positions,
+                                  int32_t k, int32_t policy, int32_t* d_match_pos,
+                                  int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
+                                  void* stream);
+
+/* ------------------------------------------------------------------------------------
  * Target model  (Sec. 4.1 names the families: Llama-3.1 / Qwen2.5 style decoders; the
  * paper does not restate the architecture).  Pre-norm decoder: RMSNorm, rotary position
  * embedding (rotate-half pairing of (j, j + head_dim/2), angle pos * theta^(-2j/head_dim)),

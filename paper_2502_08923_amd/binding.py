@@ -25,7 +25,8 @@ EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev",
     "cs_model_create", "cs_model_destroy", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
-    "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
+    "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_index_create", "cs_index_destroy",
+    "cs_index_reset", "cs_index_find_match_batch_dev", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
     "cs_set_plain_kernels", "cs_kv_set_len_dev", "cs_profile_enable", "cs_profile_reset",
     "cs_profile_read",
 ]
@@ -86,6 +87,11 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_find_match_ex.argtypes = [vp, i64, i32, i32, i32, C.POINTER(i64), C.POINTER(i64), vp,
                                      C.POINTER(i32)]
     lib.cs_find_match_batch_dev.argtypes = [vp, i64, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.cs_index_create.argtypes = [i32, i64, i32, C.POINTER(vp)]
+    lib.cs_index_destroy.argtypes = [vp]
+    lib.cs_index_destroy.restype = None
+    lib.cs_index_reset.argtypes = [vp, vp]
+    lib.cs_index_find_match_batch_dev.argtypes = [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.cs_model_create.argtypes = [C.POINTER(cs_model_cfg), C.POINTER(cs_weights), C.POINTER(vp)]
     lib.cs_model_destroy.argtypes = [vp]
     lib.cs_model_destroy.restype = None
@@ -184,6 +190,44 @@ def cs_find_match_batch_dev(d_hist: torch.Tensor, d_len: torch.Tensor, gamma: in
                                                   gamma, k, _policy(policy), mp.data_ptr(),
                                                   sp.data_ptr(), dr.data_ptr(), dl.data_ptr(),
                                                   _stream(stream)))
+    return mp, sp, dr, dl
+
+
+class Index:
+    """cs_index handle: the gamma-gram hash index of B device-resident histories."""
+
+    def __init__(self, B: int, max_len: int, gamma: int):
+        self.B, self.max_len, self.gamma = B, max_len, gamma
+        h = C.c_void_p()
+        _check(load_library().cs_index_create(B, max_len, gamma, C.byref(h)))
+        self.handle = h
+
+    def reset(self, stream=None):
+        _check(load_library().cs_index_reset(self.handle, _stream(stream)))
+
+    def destroy(self):
+        if self.handle:
+            load_library().cs_index_destroy(self.handle)
+            self.handle = None
+
+
+def cs_index_find_match_batch_dev(index: Index, d_hist: torch.Tensor, d_len: torch.Tensor,
+                                  max_new_positions: int, k: int, policy="rightmost", stream=None):
+    """Same outputs as cs_find_match_batch_dev, answered from the index (which is first brought
+    up to date with the histories)."""
+    _dev_i32(d_hist, "d_hist"), _dev_i32(d_len, "d_len")
+    B, stride = d_hist.shape
+    if B != index.B:
+        raise ValueError(f"index was created for {index.B} streams, got {B}")
+    dev = d_hist.device
+    mp = torch.empty(B, dtype=torch.int32, device=dev)
+    sp = torch.empty(B, dtype=torch.int32, device=dev)
+    dr = torch.empty((B, k), dtype=torch.int32, device=dev)
+    dl = torch.empty(B, dtype=torch.int32, device=dev)
+    _check(load_library().cs_index_find_match_batch_dev(index.handle, d_hist.data_ptr(), stride,
+                                                        d_len.data_ptr(), max_new_positions, k,
+                                                        _policy(policy), mp.data_ptr(), sp.data_ptr(),
+                                                        dr.data_ptr(), dl.data_ptr(), _stream(stream)))
     return mp, sp, dr, dl
 
 

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcopyspec.so")
-SOURCES = ["cs_api.hip", "cs_scan.hip", "cs_elem.hip", "cs_gemm.hip", "cs_attn.hip"]
+SOURCES = ["cs_api.hip", "cs_scan.hip", "cs_index.hip", "cs_elem.hip", "cs_gemm.hip", "cs_attn.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -29,7 +29,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_lib(jobs: int = 5) -> str:
+def build_lib(jobs: int = 6) -> str:
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))

@@ -118,6 +118,10 @@ struct cs_kv {
 
 // ---- kernels' host launchers (defined in the .hip files) ------------------------------
 // scan
+int cs_gather_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B, int gamma, int k,
+                     int policy, const int64_t* d_keys, int nchunks, const int32_t* d_room,
+                     int32_t* d_match_pos, int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
+                     hipStream_t s);
 int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B,
                    int gamma, int k, int policy, int64_t max_len, int32_t* d_match_pos,
                    int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,

@@ -184,3 +184,15 @@ int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, 
                               d_match_pos, d_src_pos, d_draft, d_draft_len);
     return cs_launch_ok("k_gather");
 }
+
+// draft gather alone, for callers that bring their own per-chunk keys (the gamma-gram index)
+int cs_gather_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B, int gamma, int k,
+                     int policy, const int64_t* d_keys, int nchunks, const int32_t* d_room,
+                     int32_t* d_match_pos, int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
+                     hipStream_t s) {
+    if (B == 0) return CS_OK;
+    k_gather<<<B, 64, 0, s>>>(d_hist, stride, d_len, gamma, k, policy, d_keys, nchunks, d_room, d_match_pos,
+                              d_src_pos, d_draft, d_draft_len);
+    return cs_launch_ok("k_gather");
+}
+

@@ -26,6 +26,8 @@ a language model.
    delta = 3 and 5.  With random-init weights nothing is accepted, so the figures are the cost
    side only: time per target step, per draft-model forward pass, and the acceptance a merged
    step needs to break even with plain decoding.
+
+4. (--index) The gamma-gram hash index of Sec. 3.1 against the linear scan on one long history.
 """
 from __future__ import annotations
 
@@ -113,6 +115,48 @@ def merged_costs(cs, synth, model, torch):
     return {"prefill_ms": t_prefill * 1e3, "rows": rows}
 
 
+def index_vs_scan(cs, torch):
+    """Match search through the gamma-gram index (the paper's data structure, Sec. 3.1) against
+    the linear scan, one stream, uniform tokens over a 128256-token vocabulary with the last
+    gamma tokens planted once: time to build the index over n tokens, time of a call after the
+    history grew by 11 tokens (insert + lookup + draft gather), time of a scan call."""
+    import numpy as np
+    rows = []
+    for n in (32768, 1 << 20, 1 << 24, 1 << 26):
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(n)
+        cap = n + 1024
+        hist = torch.randint(0, 128256, (1, cap), generator=g, device="cuda:0", dtype=torch.int32)
+        hist[0, n - 3:n] = hist[0, n // 3:n // 3 + 3]
+        d_len = torch.tensor([n], dtype=torch.int32, device="cuda:0")
+        ix = cs.Index(1, cap, 3)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a = cs.cs_index_find_match_batch_dev(ix, hist, d_len, n, 10)
+        torch.cuda.synchronize()
+        t_build = time.perf_counter() - t0
+        b = cs.cs_find_match_batch_dev(hist, d_len, 3, 10)
+        torch.cuda.synchronize()
+        assert all(torch.equal(x, y) for x, y in zip(a, b)) and int(a[0][0]) >= n // 3
+        lens = [torch.tensor([n + 11 * (i + 1)], dtype=torch.int32, device="cuda:0") for i in range(50)]
+        t0 = time.perf_counter()
+        for dl in lens:
+            a = cs.cs_index_find_match_batch_dev(ix, hist, dl, 11, 10)
+        torch.cuda.synchronize()
+        t_inc = (time.perf_counter() - t0) / len(lens)
+        t0 = time.perf_counter()
+        for dl in lens:
+            b = cs.cs_find_match_batch_dev(hist, dl, 3, 10)
+        torch.cuda.synchronize()
+        t_scan = (time.perf_counter() - t0) / len(lens)
+        assert all(torch.equal(x, y) for x, y in zip(a, b))
+        rows.append({"tokens": n, "index_build_ms": t_build * 1e3, "index_call_us": t_inc * 1e6,
+                     "scan_call_us": t_scan * 1e6})
+        ix.destroy()
+        del hist
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--layers", type=int, default=0, help="depth override (0 = full 32 layers)")
@@ -120,6 +164,7 @@ def main():
     ap.add_argument("--ks", default="0,5,10,20,32,50,100")
     ap.add_argument("--json", default="")
     ap.add_argument("--merged", action="store_true", help="also time the merge with a draft model")
+    ap.add_argument("--index", action="store_true", help="also time the gamma-gram index against the scan")
     args = ap.parse_args()
 
     import numpy as np
@@ -182,7 +227,8 @@ def main():
             scan.append({"gamma": gamma, "policy": policy, "kernel_us": ms / n * 1e3})
 
     merged = merged_costs(cs, synth, st["model"], torch) if args.merged else None
-    out = {"step_cost": rows, "projection": table, "scan": scan, "merged": merged,
+    index = index_vs_scan(cs, torch) if args.index else None
+    out = {"step_cost": rows, "projection": table, "scan": scan, "merged": merged, "index": index,
            "workload": f"llama-8b shape x{st['shape'].n_layers} layers, batch {B}, KV {st['L']}"}
     if args.json:
         with open(args.json, "w") as f:
@@ -207,6 +253,13 @@ def main():
             ms = r.get("ms_per_merged_step", r.get("ms_per_target_step"))
             be = f"{r['break_even_tokens_per_step']:.2f}" if "break_even_tokens_per_step" in r else "-"
             print(f"| {r['mode']} | {r['steps']} | {ms:.2f} | {be} |")
+    if index:
+        print()
+        print("Match search, one stream, gamma=3, k=10 (whole calls, wall clock):")
+        print("| history tokens | index build ms | index call us (11 new tokens) | scan call us |")
+        print("|---|---|---|---|")
+        for r in index:
+            print(f"| {r['tokens']} | {r['index_build_ms']:.2f} | {r['index_call_us']:.1f} | {r['scan_call_us']:.1f} |")
 
 
 if __name__ == "__main__":
