@@ -203,7 +203,8 @@ static int model_build(cs_model* m, const cs_weights* w) {
                                             (float*)L.wgu);
         CS_TRY(cs_launch_ok("k_pack_gu"));
     }
-    const size_t R = (size_t)m->R_max;
+    // verify blocks have up to R_max rows; prompt blocks of a single stream up to prefill_rows
+    const size_t R = (size_t)(m->R_max > m->prefill_rows ? m->R_max : m->prefill_rows);
     const size_t a = m->asz;
     const int wide = d > nq ? d : nq;
     DEV_ALLOC(m->x, R * d * 4);
@@ -211,19 +212,20 @@ static int model_build(cs_model* m, const cs_weights* w) {
     DEV_ALLOC(m->q, R * nq * 4);
     if (!m->fast) DEV_ALLOC(m->gu, R * 2 * F * 4);
     DEV_ALLOC(m->act, R * F * (a > 0 ? a : 4));
-    DEV_ALLOC(m->logits, R * V * 4);
+    DEV_ALLOC(m->logits, (size_t)m->R_max * V * 4);
     const int widest = nqkv > d ? nqkv : d;
     m->part_floats = (size_t)16 * R * widest;
     DEV_ALLOC(m->part, m->part_floats * 4);
-    const int nqg_max = (int)cs_ceil_div((H / KVH) * m->rows_max, 48);
-    m->attn_part_floats =
-        (size_t)(4 * (512 + (size_t)c.max_batch * KVH * nqg_max) + 64) * 48 * (hd + 2);
+    const size_t groups_verify = (size_t)c.max_batch * KVH * cs_ceil_div((H / KVH) * m->rows_max, 48);
+    const size_t groups_prompt = (size_t)KVH * cs_ceil_div((H / KVH) * m->prefill_rows, 48);
+    const size_t groups_max = groups_verify > groups_prompt ? groups_verify : groups_prompt;
+    m->attn_part_floats = (size_t)(4 * (512 + groups_max) + 64) * 48 * (hd + 2);
     if (m->fast) DEV_ALLOC(m->attn_part, m->attn_part_floats * 4);
     DEV_ALLOC(m->rope, R * (hd / 2) * sizeof(float2));
     DEV_ALLOC(m->tok, R * 4);
     m->am_chunks = 64;
-    DEV_ALLOC(m->am_val_idx, R * m->am_chunks * 2 * 4);
-    DEV_ALLOC(m->row_argmax, R * 4);
+    DEV_ALLOC(m->am_val_idx, (size_t)m->R_max * m->am_chunks * 2 * 4);
+    DEV_ALLOC(m->row_argmax, (size_t)m->R_max * 4);
     DEV_ALLOC(m->draft, (size_t)c.max_batch * (c.max_k > 0 ? c.max_k : 1) * 4);
     DEV_ALLOC(m->draft_len, (size_t)c.max_batch * 4);
     DEV_ALLOC(m->match_pos, (size_t)c.max_batch * 4);
@@ -255,6 +257,7 @@ extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_
     m->plain = g_plain;
     m->rows_max = c.max_k + 1;
     m->R_max = c.max_batch * m->rows_max;
+    m->prefill_rows = m->rows_max > 512 ? m->rows_max : 512;
     m->esz = c.dtype == CS_BF16 ? 2 : 4;
     const int nq = c.n_heads * c.head_dim;
     m->fast = !m->plain && c.dtype == CS_BF16 && (c.head_dim == 64 || c.head_dim == 128) &&
@@ -601,7 +604,7 @@ extern "C" int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int3
                    "prompt token %lld out of vocabulary", (long long)i);
     CS_TRY(cs_kv_set_len(kv, 0, 0));
     const int64_t body = prompt_len - 1;
-    const int chunk = m->rows_max;
+    const int chunk = m->prefill_rows;
     for (int64_t c0 = 0; c0 < body; c0 += chunk) {
         const int rows = (int)(body - c0 < chunk ? body - c0 : chunk);
         CS_HIP(hipMemcpyAsync(m->tok, prompt + c0, (size_t)rows * 4, hipMemcpyHostToDevice, nullptr));
@@ -759,7 +762,7 @@ extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv
             proposed = (int)(delta < room - 1 ? delta : room - 1);
             while (draft_rows < n - 1) {          // read what was accepted since it last ran
                 const int64_t left = n - 1 - draft_rows;
-                const int rows = (int)(left < dm->rows_max ? left : dm->rows_max);
+                const int rows = (int)(left < dm->prefill_rows ? left : dm->prefill_rows);
                 CS_HIP(hipMemcpyAsync(dm->tok, d + draft_rows, (size_t)rows * 4, hipMemcpyDeviceToDevice, s));
                 CS_TRY(forward_layers(dm, dkv, rows, s));
                 k_add_i32<<<1, 64, 0, s>>>(dkv->d_len, rows, 1);

@@ -112,7 +112,7 @@ def merged_costs(cs, synth, model, torch):
                      "break_even_tokens_per_step": t_step / t_plain_step})
     for h in (dkv, kv, dmodel):
         h.destroy()
-    return {"prefill_ms": t_prefill * 1e3, "rows": rows}
+    return {"prefill_ms": t_prefill * 1e3, "prefill_tokens_per_s": (len(prompt) - 1) / t_prefill, "rows": rows}
 
 
 def index_vs_scan(cs, torch):
@@ -246,7 +246,8 @@ def main():
         print(f"| {r['gamma']} | {r['policy']} | {r['kernel_us']:.2f} |")
     if merged:
         print()
-        print(f"One stream, 4096-token prompt (prompt pass {merged['prefill_ms']:.1f} ms, subtracted below), 64 new tokens:")
+        print(f"One stream, 4096-token prompt (prompt pass {merged['prefill_ms']:.1f} ms = "
+              f"{merged['prefill_tokens_per_s']:.0f} tokens/s, subtracted below), 64 new tokens:")
         print("| mode | steps | ms per step | break-even tokens per step |")
         print("|---|---|---|---|")
         for r in merged["rows"]:

@@ -136,6 +136,26 @@ def test_verify_matches_oracle(shape, plain):
     model.destroy()
 
 
+@pytest.mark.parametrize("shape", [MINI64, MINI128, SMALLF32])
+def test_long_prompt_goes_through_512_row_blocks(shape):
+    """A 700-token prompt is ingested in blocks of 512 rows (a full block and a ragged one that
+    attends to the rows before it): the cache rows and the logits of the following
+    verify step match the oracle, which ingests the same prompt 32 rows at a time."""
+    w = synth.model_weights(shape, 2024, threads=4)
+    model = cs.Model(w, max_batch=1, max_k=10)
+    g = synth.planted_history(23, 700, shape.vocab, (16, 32), density=0.2, end="span")
+    prompt = g["tokens"].tolist()
+    _, _, draft = orc.find_match_np(prompt, 3, 10)
+    kv, okv, err = _verify_case(w, model, prompt, draft, 10, cap=768)
+    tol = 2e-2 if shape.dtype == "bf16" else 1e-4
+    for layer in range(shape.n_layers):
+        k_rows, v_rows = kv.read(layer, 0, 0, 699)
+        assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :699]).max() < tol * 4
+        assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :699]).max() < tol * 4
+    kv.destroy()
+    model.destroy()
+
+
 def test_rollback_leaves_no_trace_on_gpu():
     """After a rejection the next step must see only the accepted prefix (App. B.2)."""
     shape = MINI64
