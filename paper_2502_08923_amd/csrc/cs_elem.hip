@@ -184,7 +184,24 @@ __global__ __launch_bounds__(AM_THREADS) void k_argmax_partial(const float* __re
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     if (vec_ok) {
-        for (int i = lo + (int)threadIdx.x * 4; i < hi; i += AM_THREADS * 4) {
+        // four independent 16-byte loads per thread are issued before any of them is compared,
+        // so a workgroup keeps 16 KB in flight; candidates are visited in increasing index order
+        // per thread, which keeps "first index on ties" a plain strict comparison
+        int i = lo + (int)threadIdx.x * 4;
+        for (; i + 3 * AM_THREADS * 4 + 3 < hi; i += 4 * AM_THREADS * 4) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(row + i + u * AM_THREADS * 4);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int iu = i + u * AM_THREADS * 4;
+                if (v[u].x > bv) { bv = v[u].x; bi = iu; }
+                if (v[u].y > bv) { bv = v[u].y; bi = iu + 1; }
+                if (v[u].z > bv) { bv = v[u].z; bi = iu + 2; }
+                if (v[u].w > bv) { bv = v[u].w; bi = iu + 3; }
+            }
+        }
+        for (; i < hi; i += AM_THREADS * 4) {
             if (i + 3 < hi) {
                 const float4 v = *reinterpret_cast<const float4*>(row + i);
                 if (v.x > bv) { bv = v.x; bi = i; }
@@ -365,7 +382,7 @@ int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k
                             int32_t* hist, int64_t hist_stride, int32_t* hist_len,
                             int32_t* room, hipStream_t s) {
     const int R = B * (k + 1);
-    int nch = (int)cs_ceil_div(V, 16384);
+    int nch = (int)cs_ceil_div(V, 8192);
     if (nch < 1) nch = 1;
     if (nch > m->am_chunks) nch = m->am_chunks;
     const int Vc = (int)cs_round_up(cs_ceil_div(V, nch), 4);
