@@ -662,20 +662,27 @@ __global__ void k_attn_merge(const float* __restrict__ po, const float* __restri
     const float* __restrict__ ml = pml + (item * nsplit * FA_QROWS + nl) * 2;
     const float* __restrict__ o = po + (item * nsplit * FA_QROWS + nl) * HD;
     __shared__ float wgt[FA_MAX_SPLIT];
-    __shared__ float den_s;
-    if (threadIdx.x == 0) {
-        float M = -INFINITY;
-        for (int w = 0; w < nsplit; ++w) M = fmaxf(M, ml[(int64_t)w * FA_QROWS * 2]);
-        float den = 0.f;
-        for (int w = 0; w < nsplit; ++w) {
-            const float mw = ml[(int64_t)w * FA_QROWS * 2];
-            const float sc = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-            wgt[w] = sc;
-            den += sc * ml[(int64_t)w * FA_QROWS * 2 + 1];
-        }
-        den_s = den;
+    __shared__ float lsum[FA_MAX_SPLIT];
+    // one split per thread: the (max, sum) pairs are fetched side by side, not one after another
+    if ((int)threadIdx.x < nsplit) {
+        wgt[threadIdx.x] = ml[(int64_t)threadIdx.x * FA_QROWS * 2];
+        lsum[threadIdx.x] = ml[(int64_t)threadIdx.x * FA_QROWS * 2 + 1];
     }
     __syncthreads();
+    float M = -INFINITY;
+    for (int w = 0; w < nsplit; ++w) M = fmaxf(M, wgt[w]);
+    float den = 0.f;
+    for (int w = 0; w < nsplit; ++w) {                      // same order in every thread
+        const float mw = wgt[w];
+        den += ((mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M)) * lsum[w];
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < nsplit) {
+        const float mw = wgt[threadIdx.x];
+        wgt[threadIdx.x] = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+    }
+    __syncthreads();
+    const float den_s = den;
     const float inv = 1.0f / den_s;
     const int r = b * rows + i;
     for (int d = threadIdx.x; d < HD; d += blockDim.x) {
