@@ -42,14 +42,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def replay_acceptance(cs, synth, gamma: int, k: int, policy: str, streams=(0, 1, 2, 3)):
-    """Mean tokens emitted per step and mean accepted drafts per attempt when the second turn
-    of the multi-turn workload is decoded with CopySpec and the target always emits the
-    edited answer."""
+def replay_acceptance(cs, synth, gamma: int, k: int, policy: str, streams=(0, 1, 2, 3),
+                      workload: str = "multiturn"):
+    """Mean tokens emitted per step and mean accepted drafts per attempt when the "truth" of a
+    replay workload (synth.multiturn_replay or synth.zipf_replay) is decoded with CopySpec and
+    the target always emits that truth."""
     import numpy as np
     tot_steps = tot_tokens = attempts = accepted = 0
     for s in streams:
-        g = synth.multiturn_replay(s)
+        g = synth.multiturn_replay(s) if workload == "multiturn" else synth.zipf_replay(s)
         ctx, truth = g["context"].tolist(), g["truth"].tolist()
         seq = ctx + truth[:gamma]                 # the first gamma tokens are generated plainly
         pos = gamma
@@ -209,6 +210,16 @@ def main():
                               "emitted_tokens_per_s": emitted,
                               "speedup_vs_plain": (emitted / (B / (base * 1e-3))) if base else None})
 
+    # second replay workload: Zipf-distributed tokens with 30 % copied spans, k = 10 only
+    k10 = next((r for r in rows if r["k"] == 10), rows[-1])
+    ztable = []
+    for gamma in (2, 3, 5):
+        for policy in ("rightmost", "first", "context"):
+            tps, tau = replay_acceptance(cs, synth, gamma, k10["k"], policy, workload="zipf")
+            ztable.append({"gamma": gamma, "policy": policy, "k": k10["k"], "tokens_per_step": tps,
+                           "accepted_per_attempt": tau,
+                           "speedup_vs_plain": (tps * base / k10["ms_per_step"]) if base else None})
+
     # match-scan cost by gamma and policy on the 64 x 32768 scan configuration
     hs = np.stack([synth.history_cfg2(s)["tokens"] for s in range(64)])
     d_hist = torch.from_numpy(hs).to("cuda:0")
@@ -228,7 +239,7 @@ def main():
 
     merged = merged_costs(cs, synth, st["model"], torch) if args.merged else None
     index = index_vs_scan(cs, torch) if args.index else None
-    out = {"step_cost": rows, "projection": table, "scan": scan, "merged": merged, "index": index,
+    out = {"step_cost": rows, "projection": table, "projection_zipf": ztable, "scan": scan, "merged": merged, "index": index,
            "workload": f"llama-8b shape x{st['shape'].n_layers} layers, batch {B}, KV {st['L']}"}
     if args.json:
         with open(args.json, "w") as f:
@@ -239,6 +250,13 @@ def main():
         sp = f"{r['speedup_vs_plain']:.2f}x" if r["speedup_vs_plain"] else "-"
         print(f"| {r['gamma']} | {r['policy']} | {r['k']} | {r['ms_per_step']:.2f} | {r['tokens_per_step']:.2f} | "
               f"{r['accepted_per_attempt']:.2f} | {r['emitted_tokens_per_s']:.0f} | {sp} |")
+    print()
+    print("Zipf-law tokens (exponent 1.1) with 30 % of the answer copied from the context in spans of 8-64:")
+    print("| gamma | policy | k | tokens/step | accepted/attempt | vs k=0 |")
+    print("|---|---|---|---|---|---|")
+    for r in ztable:
+        sp = f"{r['speedup_vs_plain']:.2f}x" if r["speedup_vs_plain"] else "-"
+        print(f"| {r['gamma']} | {r['policy']} | {r['k']} | {r['tokens_per_step']:.2f} | {r['accepted_per_attempt']:.2f} | {sp} |")
     print()
     print("| gamma | policy | scan kernel us (64 x 32768 tokens) |")
     print("|---|---|---|")

@@ -10,5 +10,5 @@ from .workloads import (  # noqa: F401
     bf16_bits_to_f32, f32_to_bf16_bits,
     model_weights, random_kv,
     history_cfg1, history_cfg2, history_cfg3, history_cfg4, history_cfg5,
-    planted_history, multiturn_replay,
+    planted_history, multiturn_replay, zipf_replay,
 )

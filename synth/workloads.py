@@ -329,3 +329,29 @@ def multiturn_replay(stream: int, answer: int = 1024, filler: int = 1024, vocab:
         ver = nxt
     return {"context": np.concatenate(parts[:-1]), "truth": parts[-1]}
 
+
+def zipf_replay(stream: int, context: int = 6144, answer: int = 2048, vocab: int = 128256,
+                exponent: float = 1.1, copy_density: float = 0.3, span=(8, 64)) -> dict:
+    """Natural-text-like stand-in for acceptance replays: token ranks follow a Zipf law
+    (p(rank r) ~ r^-exponent, truncated at `vocab`), so short gamma-grams of frequent tokens
+    recur by chance and produce matches whose continuation is wrong; on top of that,
+    `copy_density` of the answer consists of spans copied verbatim from the context (lengths
+    uniform in `span`).  "context" is what the model has seen, "truth" what a faithful target
+    model would emit next."""
+    rng = _rng(seed_for(5, 200 + stream))
+    ranks = np.arange(1, vocab + 1, dtype=np.float64)
+    p = ranks ** -exponent
+    p /= p.sum()
+    perm = rng.permutation(vocab).astype(np.int32)          # which token id has which rank
+    draw = lambda m: perm[rng.choice(vocab, size=m, p=p)]
+    ctx = draw(context)
+    truth = draw(answer)
+    covered, lo, hi = 0, span[0], span[1]
+    while covered < copy_density * answer:
+        ln = int(rng.integers(lo, hi + 1))
+        src = int(rng.integers(0, context - ln))
+        dst = int(rng.integers(0, answer - ln))
+        truth[dst:dst + ln] = ctx[src:src + ln]
+        covered += ln
+    return {"context": ctx, "truth": truth}
+

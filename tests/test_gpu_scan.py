@@ -132,6 +132,10 @@ def test_acceptance_replay_matches_oracle(policy):
         got = sweep.replay_acceptance(cs, synth, gamma, k, policy, streams=(0,))
         want = sweep.replay_acceptance(OracleSearch, synth, gamma, k, policy, streams=(0,))
         assert got == want, (gamma, k, policy, got, want)
+    # Zipf-law tokens: many chance matches of frequent gamma-grams
+    got = sweep.replay_acceptance(cs, synth, 2, 10, policy, streams=(1,), workload="zipf")
+    want = sweep.replay_acceptance(OracleSearch, synth, 2, 10, policy, streams=(1,), workload="zipf")
+    assert got == want
     # the newest version of the answer is the better copy source
     r = sweep.replay_acceptance(OracleSearch, synth, 3, 10, "rightmost", streams=(0,))
     f = sweep.replay_acceptance(OracleSearch, synth, 3, 10, "first", streams=(0,))
