@@ -135,7 +135,7 @@ static int dev_alloc(void** p, size_t bytes) {
 
 static void model_free(cs_model* m) {
     if (!m) return;
-    void* ptrs[] = {m->embed, m->lm_head, m->final_norm, m->x, m->xn, m->qkv, m->q, m->gu, m->act,
+    void* ptrs[] = {m->embed, m->lm_head, m->final_norm, m->x, m->xn, m->q, m->gu, m->act,
                     m->logits, m->part, m->attn_part, m->rope, m->tok, m->am_val_idx,
                     m->row_argmax, m->draft, m->draft_len, m->match_pos, m->pending};
     for (void* p : ptrs)

@@ -87,7 +87,6 @@ struct cs_model {
     // workspace (device)
     float* x;           // [R][d] residual stream
     void* xn;           // [R][max(d, H*hd)] GEMM input (normed rows / attention output)
-    float* qkv;         // [R][(H+2KVH)*hd]
     void* q;            // [R][H][hd] rotated queries
     float* gu;          // [R][2F]  (plain path only)
     void* act;          // [R][F]

@@ -10,6 +10,9 @@
 // activations rounded to float16 by their producers); v_mfma_f32_16x16x32_f16 accumulates
 // in float32.  Small-N projections are split along K across workgroups; the float32 partial
 // tiles are summed by the consumer kernel in a fixed order (deterministic, no atomics).
+// With hundreds of block rows (large k, large batches, prompt blocks) the same projections
+// become compute-bound and go to a second kernel, k_gemm_dma below, that tiles for operand
+// reuse and feeds both operands through LDS with direct-to-LDS loads.
 #include "cs_common.h"
 #include <type_traits>
 
