@@ -112,6 +112,19 @@ __global__ __launch_bounds__(PA_THREADS) void k_attn_plain(const QT* __restrict_
 // tuned bf16 kernel
 // -------------------------------------------------------------------------------------
 #define FA_NT 3            // 16-row query tiles per wave  (48 query rows)
+// max over the four lanes {c, c+16, c+32, c+48} that share a query row, with the row-swap
+// instructions of gfx950 (two register swaps and two max) instead of two round trips through
+// the LDS crossbar: swapping x with itself leaves (low half, low half) and (high half, high
+// half) in the two results, whose max is the reduction over lanes 32 apart; then 16 apart.
+__device__ __forceinline__ float fa_row4_max(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const float m = fmaxf(__uint_as_float(r32[0]), __uint_as_float(r32[1]));
+    const unsigned v = __float_as_uint(m);
+    const auto r16 = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return fmaxf(__uint_as_float(r16[0]), __uint_as_float(r16[1]));
+}
+
 #define FA_QROWS (16 * FA_NT)
 #define FA_RESCALE_LOG2 8.0f
 #define FA_OPAD 4          // LDS row padding (floats) of the in-workgroup merge buffers
@@ -258,8 +271,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
             float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
             mx = fmaxf(fmaxf(mx, sv[3]), sv[4]);
             mx = fmaxf(fmaxf(mx, sv[5]), fmaxf(sv[6], sv[7]));
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = fa_row4_max(mx);                                  // over the lanes c, c+16, c+32, c+48
             mx *= scale2;                       // scale2 > 0: scaling commutes with the max
             // The reference maximum only follows the true one when it is left behind by more
             // than 2^8: probabilities stay below 256, O and the row sum stay consistent, and
@@ -509,15 +521,18 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
         load(1, 1);
         store(0, 0, 0);
         load(0, 2);
-        __syncthreads();                                   // stage 0 and the query tiles are ready
+        store(1, 1, 1);
+        load(1, 3);
+        __syncthreads();                                   // stages 0, 1 and the query tiles are ready
         for (int i = 0; i < nblocks_wg; i += 2) {
-            // iteration i: block i+1 (registers slot 1) -> stage (i+1)%3; refill with block i+3
-            store(1, (i + 1) % FA_STAGES, i + 1);
-            load(1, i + 3);
-            __syncthreads();
-            if (i + 1 >= nblocks_wg) break;
+            // consumer iteration i reads stages i and i+1: block i+2 (registers slot 0) goes to
+            // stage (i+2)%3, which held block i-1; refill the slot with block i+4
             store(0, (i + 2) % FA_STAGES, i + 2);
             load(0, i + 4);
+            __syncthreads();
+            if (i + 1 >= nblocks_wg) break;
+            store(1, (i + 3) % FA_STAGES, i + 3);
+            load(1, i + 5);
             __syncthreads();
         }
         return;
@@ -547,23 +562,38 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     const bf16_t one = (bf16_t)1.0f;
     const bf16x8 ones = (bf16x8){one, one, one, one, one, one, one, one};
 
-    auto compute = [&](const unsigned char* sp, int t0, auto tail_tag) {
-        constexpr bool TAIL = decltype(tail_tag)::value;
-        f32x4 sacc[2][FA_NT];
+    // scores of one block: S^T = K Q^T from the K fragments of stage `sp`
+    auto scores = [&](const unsigned char* sp, f32x4 (&sacc)[2][FA_NT]) {
+        // all K fragments of the block and the first query tile are requested at once; the query
+        // fragments of tile nt+1 are fetched while tile nt is multiplied (LDS latency is ~100
+        // cycles and only two waves share a SIMD, so fragments are read well ahead of their use)
+        bf16x8 kf[2][KS], qf[2][KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            kf[0][s] = *reinterpret_cast<const bf16x8*>(sp + ((0 * KS + s) * 64 + lane) * 16);
+            kf[1][s] = *reinterpret_cast<const bf16x8*>(sp + ((1 * KS + s) * 64 + lane) * 16);
+            qf[0][s] = *reinterpret_cast<const bf16x8*>(myq + c * QROW + s * 64 + g * 16);
+        }
 #pragma unroll
         for (int nt = 0; nt < FA_NT; ++nt) {
+            if (nt + 1 < FA_NT) {
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    qf[(nt + 1) & 1][s] = *reinterpret_cast<const bf16x8*>(myq + ((nt + 1) * 16 + c) * QROW + s * 64 + g * 16);
+            }
             f32x4 z0 = (f32x4){0.f, 0.f, 0.f, 0.f}, z1 = z0;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const bf16x8 qb = *reinterpret_cast<const bf16x8*>(myq + (nt * 16 + c) * QROW + s * 64 + g * 16);
-                const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(sp + ((0 * KS + s) * 64 + lane) * 16);
-                const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(sp + ((1 * KS + s) * 64 + lane) * 16);
-                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb, z0, 0, 0, 0);
-                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb, z1, 0, 0, 0);
+                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt & 1][s], z0, 0, 0, 0);
+                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt & 1][s], z1, 0, 0, 0);
             }
             sacc[0][nt] = z0;
             sacc[1][nt] = z1;
         }
+    };
+    // softmax update and O^T += V^T P^T for the block whose scores are in `sacc`
+    auto finish = [&](const f32x4 (&sacc)[2][FA_NT], const unsigned char* sp, int t0, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         bool moved = false;
         float alpha[FA_NT];
         bf16x8 pb[FA_NT];
@@ -581,8 +611,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
             float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
             mx = fmaxf(fmaxf(mx, sv[3]), sv[4]);
             mx = fmaxf(fmaxf(mx, sv[5]), fmaxf(sv[6], sv[7]));
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = fa_row4_max(mx);                                  // over the lanes c, c+16, c+32, c+48
             mx *= scale2;
             const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;      // see k_attn_mfma
             const float m_new = up ? mx : m_run[nt];
@@ -597,40 +626,55 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
         if (__any(moved)) {
 #pragma unroll
             for (int nt = 0; nt < FA_NT; ++nt) {
-                asm volatile("" : "+a"(lacc[nt]));
                 lacc[nt] *= alpha[nt];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    asm volatile("" : "+a"(oacc[mt][nt]));
                     oacc[mt][nt] *= alpha[nt];
                 }
             }
         }
+        // V fragments are read three tiles ahead of the MFMAs that use them
+        bf16x8 vf[4];
+#pragma unroll
+        for (int mt = 0; mt < 3; ++mt) vf[mt] = *reinterpret_cast<const bf16x8*>(sp + K_BYTES + (mt * 64 + lane) * 16);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(sp + K_BYTES + (mt * 64 + lane) * 16);
+            if (mt + 3 < MT) vf[(mt + 3) & 3] = *reinterpret_cast<const bf16x8*>(sp + K_BYTES + ((mt + 3) * 64 + lane) * 16);
 #pragma unroll
             for (int nt = 0; nt < FA_NT; ++nt)
-                oacc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[nt], oacc[mt][nt], 0, 0, 0);
+                oacc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[mt & 3], pb[nt], oacc[mt][nt], 0, 0, 0);
         }
 #pragma unroll
         for (int nt = 0; nt < FA_NT; ++nt) {
             lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[nt], lacc[nt], 0, 0, 0);
-            asm volatile("" : "+a"(lacc[nt]));
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) asm volatile("" : "+a"(oacc[mt][nt]));
         }
     };
     const std::integral_constant<bool, false> main_tag;
     const std::integral_constant<bool, true> tail_tag;
 
     __syncthreads();                                       // matches the producer's first barrier
-    for (int i = 0; i < nblocks_wg; ++i) {
+    // Software pipeline: the score MFMAs of block i+1 are issued in the same iteration as the
+    // softmax arithmetic of block i (they do not depend on each other), which lets the matrix
+    // cores work while the vector ALU does the exponentials.
+    f32x4 sa[2][FA_NT], sb[2][FA_NT];
+    if (live && nblocks > 0) scores(stage[0], sa);
+    // one block: softmax + PV of block i (scores in `cur`) and the scores of block i+1 (into
+    // `nxt`).  The two teams do them in opposite order, so that the two waves sharing a SIMD
+    // want different units after every barrier.
+    auto block = [&](f32x4 (&cur)[2][FA_NT], f32x4 (&nxt)[2][FA_NT], int i) {
+        if (!(live && i < nblocks)) return;
         const int t0 = t_begin + i * 32;
-        if (live && i < nblocks) {
-            if (t0 + 32 > L) compute(stage[i % FA_STAGES], t0, tail_tag);
-            else compute(stage[i % FA_STAGES], t0, main_tag);
-        }
+        const bool has_next = i + 1 < nblocks;
+        if (team == 0 && has_next) scores(stage[(i + 1) % FA_STAGES], nxt);
+        if (t0 + 32 > L) finish(cur, stage[i % FA_STAGES], t0, tail_tag);
+        else finish(cur, stage[i % FA_STAGES], t0, main_tag);
+        if (team != 0 && has_next) scores(stage[(i + 1) % FA_STAGES], nxt);
+    };
+    for (int i = 0; i < nblocks_wg; i += 2) {
+        block(sa, sb, i);
+        __syncthreads();
+        if (i + 1 >= nblocks_wg) break;
+        block(sb, sa, i + 1);
         __syncthreads();
     }
     if (!live) return;
