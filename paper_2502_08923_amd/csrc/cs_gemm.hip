@@ -356,7 +356,8 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) a[mt] = a_frag(0, mt);
     bq[0] = b_frag(0, 0);
-    bq[1] = b_frag(0, 1 % NT);
+    bq[1] = b_frag(0, 1);
+    bq[2] = b_frag(0, 2);
 
     // four chunks, one per stage.  TAIL marks the last trip, where nothing more is requested.
     auto trip = [&](int c0, auto tailc) {
@@ -372,8 +373,8 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const int q = u * NT + nt;                        // position in the B fragment stream
-                if (nt + 2 < NT) bq[(q + 2) & 3] = b_frag(u, nt + 2);
-                else if (more) bq[(q + 2) & 3] = b_frag((u + 1) & 3, nt + 2 - NT);
+                if (nt + 3 < NT) bq[(q + 3) & 3] = b_frag(u, nt + 3);              // three tiles ahead
+                else if (more) bq[(q + 3) & 3] = b_frag((u + 1) & 3, nt + 3 - NT);
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt) {
                     acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bq[q & 3], acc[mt][nt], 0, 0, 0);
