@@ -433,7 +433,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
                                                               const int32_t* __restrict__ kv_len,
                                                               int rows, int H, int KVH, int64_t cap,
                                                               int Tw, int nqg, int nqgw, int nsplit,
-                                                              float* __restrict__ po,
+                                                              int ranges, float* __restrict__ po,
                                                               float* __restrict__ pml) {
     constexpr int KS = HD / 32, MT = HD / 16;
     constexpr int QROW = HD * 2 + 16;
@@ -446,9 +446,17 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     const int team = (tid >> 6) / (FA_QG + 1), wave = (tid >> 6) % (FA_QG + 1);
     unsigned char (*stage)[STAGE_BYTES] = stage_all[team];
     const int c = lane & 15, g = lane >> 4;
-    const int qgw = blockIdx.x % nqgw;                  // which group of FA_QG query groups
-    const int split = (blockIdx.x / nqgw) * FA_TEAMS + team;   // each team owns one token range
-    const int kvh = blockIdx.y, b = blockIdx.z;
+    // Workgroup -> (stream, KV head, token range pair, group of query groups).  The nqgw
+    // workgroups that walk the same K/V range (long blocks, e.g. prompt ingestion) get ids 8
+    // apart: consecutive ids go to different XCDs, each with its own L2, so this puts them on
+    // one XCD at about the same time and the range is fetched from HBM once, not nqgw times.
+    const int nsp = nsplit / FA_TEAMS;                  // ranges = B * KVH * nsp
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int range = (slot / nqgw) * 8 + xcd;
+    if (range >= ranges) return;                        // whole workgroup, before any barrier
+    const int qgw = slot % nqgw;                        // which group of FA_QG query groups
+    const int split = (range % nsp) * FA_TEAMS + team;  // each team owns one token range
+    const int kvh = (range / nsp) % KVH, b = range / (nsp * KVH);
     const int G = H / KVH;
     const int QR = G * rows;
     const int L = kv_len[b];
@@ -778,14 +786,16 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
                    "attention workspace too small");
         float* po = m->attn_part;
         float* pml = m->attn_part + items * FA_QROWS * hd;
-        dim3 grid(nsplit / FA_TEAMS * nqgw, KVH, B);
+        // one-dimensional grid, decoded in the kernel (XCD-aware order)
+        const int ranges = B * KVH * (nsplit / FA_TEAMS);
+        dim3 grid((unsigned)(cs_round_up(ranges, 8) * nqgw));
         const int pa = cs_prof_begin(CS_PROF_ATTN, s);
         if (hd == 128)
             k_attn_lds<128><<<grid, FA_LDS_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows,
-                                                             H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, po, pml);
+                                                             H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, ranges, po, pml);
         else
             k_attn_lds<64><<<grid, FA_LDS_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows,
-                                                            H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, po, pml);
+                                                            H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, ranges, po, pml);
         cs_prof_end(pa, s);
         CS_TRY(cs_launch_ok("k_attn_lds"));
         dim3 mgrid(QR, KVH, B);
