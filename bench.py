@@ -137,10 +137,23 @@ def bench_scan(cs, torch, synth, log):
 
     wall, kern = timed(d_hist, d_len, 200)
     tokens = 64 * 32768
+    # cold: a 1 GiB fill between calls evicts the 8 MB of histories from L2 and the 256 MB cache
+    evict = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    cs.cs_profile_enable(["scan"])
+    cs.cs_profile_reset()
+    for i in range(10):
+        evict.fill_(float(i))
+        cs.cs_find_match_batch_dev(d_hist, d_len, 3, 10)
+    torch.cuda.synchronize()
+    ms, nl = cs.cs_profile_read("scan")
+    cs.cs_profile_enable([])
+    cold = ms / nl * 1e-3
+    del evict
     res["cfg2"] = {"tokens": tokens, "call_us": wall * 1e6, "kernel_us": kern * 1e6,
+                   "kernel_us_cold": cold * 1e6,
                    "gtokens_per_s_call": tokens / wall / 1e9,
                    "gtokens_per_s_kernel": tokens / kern / 1e9,
-                   "kernel_GBps": tokens * 4 / kern / 1e9}
+                   "kernel_GBps": tokens * 4 / kern / 1e9, "kernel_GBps_cold": tokens * 4 / cold / 1e9}
     nb = 8192
     big = d_hist.repeat(nb // 64, 1).contiguous()
     big_len = torch.full((nb,), 32768, dtype=torch.int32, device=dev)
