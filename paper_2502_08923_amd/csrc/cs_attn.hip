@@ -571,29 +571,32 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     const bf16x8 ones = (bf16x8){one, one, one, one, one, one, one, one};
 
     // scores of one block: S^T = K Q^T from the K fragments of stage `sp`
+    // the wave's query fragments stay in registers for the whole token range (read once from
+    // the staged tile, after the first barrier below)
+    bf16x8 qreg[FA_NT][KS];
+    auto load_q = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt)
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                qreg[nt][s] = *reinterpret_cast<const bf16x8*>(myq + (nt * 16 + c) * QROW + s * 64 + g * 16);
+    };
     auto scores = [&](const unsigned char* sp, f32x4 (&sacc)[2][FA_NT]) {
-        // all K fragments of the block and the first query tile are requested at once; the query
-        // fragments of tile nt+1 are fetched while tile nt is multiplied (LDS latency is ~100
-        // cycles and only two waves share a SIMD, so fragments are read well ahead of their use)
-        bf16x8 kf[2][KS], qf[2][KS];
+        // all K fragments of the block are requested at once (LDS latency is ~100 cycles and
+        // only two waves share a SIMD, so fragments are read well ahead of their use)
+        bf16x8 kf[2][KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             kf[0][s] = *reinterpret_cast<const bf16x8*>(sp + ((0 * KS + s) * 64 + lane) * 16);
             kf[1][s] = *reinterpret_cast<const bf16x8*>(sp + ((1 * KS + s) * 64 + lane) * 16);
-            qf[0][s] = *reinterpret_cast<const bf16x8*>(myq + c * QROW + s * 64 + g * 16);
         }
 #pragma unroll
         for (int nt = 0; nt < FA_NT; ++nt) {
-            if (nt + 1 < FA_NT) {
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    qf[(nt + 1) & 1][s] = *reinterpret_cast<const bf16x8*>(myq + ((nt + 1) * 16 + c) * QROW + s * 64 + g * 16);
-            }
             f32x4 z0 = (f32x4){0.f, 0.f, 0.f, 0.f}, z1 = z0;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt & 1][s], z0, 0, 0, 0);
-                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt & 1][s], z1, 0, 0, 0);
+                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qreg[nt][s], z0, 0, 0, 0);
+                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qreg[nt][s], z1, 0, 0, 0);
             }
             sacc[0][nt] = z0;
             sacc[1][nt] = z1;
@@ -665,6 +668,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     // softmax arithmetic of block i (they do not depend on each other), which lets the matrix
     // cores work while the vector ALU does the exponentials.
     f32x4 sa[2][FA_NT], sb[2][FA_NT];
+    load_q();
     if (live && nblocks > 0) scores(stage[0], sa);
     // one block: softmax + PV of block i (scores in `cur`) and the scores of block i+1 (into
     // `nxt`).  The two teams do them in opposite order, so that the two waves sharing a SIMD
