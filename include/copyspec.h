@@ -203,7 +203,9 @@ int cs_verify(cs_model* m, cs_kv* kv, const int32_t* d_pending /*[B]*/,
  * kv length must be d_hist_len[b] - 1.  The call searches each history (gamma, policy),
  * drafts up to k tokens, clamps the draft to d_room[b] - 1 if d_room != NULL (room =
  * tokens the stream may still emit), verifies, then appends draft[0..tau) and next to the
- * history and advances d_hist_len[b] by tau+1 and d_room[b] by -(tau+1).
+ * history and advances d_hist_len[b] by tau+1 and d_room[b] by -(tau+1).  A stream with
+ * d_room[b] <= 0 takes no part: nothing is drafted, accepted, emitted or appended, its cache
+ * length stays, and its outputs are accepted_len 0 and next_token -1.
  * Outputs d_accepted_len[B], d_next_token[B], d_draft_len_out[B] (may be NULL).
  * No host synchronisation: the step can be enqueued back to back.
  * ---------------------------------------------------------------------------------- */
@@ -235,6 +237,30 @@ int cs_decode(cs_model* m, cs_kv* kv, const int32_t* prompt /*host*/, int64_t pr
 int cs_decode_greedy(cs_model* m, cs_kv* kv, const int32_t* prompt /*host*/, int64_t prompt_len,
                      int64_t max_new, int32_t eos_id, int32_t* out_tokens /*host*/,
                      int64_t* n_out);
+
+/* ------------------------------------------------------------------------------------
+ * The same loop for all streams of a cache at once  (Sec. 3.2; App. B.3 step 4; the streams
+ * are independent sequences, each with its own history, match and acceptance)
+ *
+ * cs_prefill_batch: prompts is a host array [B][prompt_stride], B = the batch of `kv`,
+ * stream b's prompt being its first prompt_len[b] >= 1 tokens.  All lengths are reset; the
+ * prompts are run through the model in lock step (every pass takes the same number of rows
+ * from every stream, the workspace rows divided by B; a stream whose prompt is used up rides
+ * along on padding rows that stay dead), leaving stream b with length prompt_len[b] - 1.
+ * cs_decode_batch: cs_prefill_batch, then cs_step on all streams until every stream has
+ * emitted max_new tokens or eos_id (>= 0; its output is cut after it).  A stream that is done
+ * takes no further part (its emission budget is 0, see cs_step).  out_tokens: host
+ * [B][max_new]; n_out: host [B]; stats: host [B] or NULL.  Every stream's output is what
+ * cs_decode gives for that prompt alone.  Requires capacity >= longest prompt + max_new + k
+ * + 1.  Synchronous.
+ * ---------------------------------------------------------------------------------- */
+int cs_prefill_batch(cs_model* m, cs_kv* kv, const int32_t* prompts /*host [B][prompt_stride]*/,
+                     int64_t prompt_stride, const int64_t* prompt_len /*host [B]*/);
+int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts /*host [B][prompt_stride]*/,
+                    int64_t prompt_stride, const int64_t* prompt_len /*host [B]*/, int64_t max_new,
+                    int32_t gamma, int32_t k, int32_t policy, int32_t eos_id,
+                    int32_t* out_tokens /*host [B][max_new]*/, int64_t* n_out /*host [B]*/,
+                    cs_stats* stats /*host [B], may be NULL*/);
 
 /* ------------------------------------------------------------------------------------
  * CopySpec merged with draft-model speculative decoding  (Sec. 3.3; App. B.3 steps 1-4)

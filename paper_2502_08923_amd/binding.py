@@ -25,7 +25,7 @@ EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev",
     "cs_model_create", "cs_model_destroy", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
-    "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_index_create", "cs_index_destroy",
+    "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_prefill_batch", "cs_decode_batch", "cs_index_create", "cs_index_destroy",
     "cs_index_reset", "cs_index_find_match_batch_dev", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
     "cs_set_plain_kernels", "cs_kv_set_len_dev", "cs_profile_enable", "cs_profile_reset",
     "cs_profile_read",
@@ -111,6 +111,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_decode_merged.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp,
                                      C.POINTER(i64), C.POINTER(cs_merged_stats)]
     lib.cs_prefill.argtypes = [vp, vp, i32, vp, i64]
+    lib.cs_prefill_batch.argtypes = [vp, vp, vp, i64, vp]
+    lib.cs_decode_batch.argtypes = [vp, vp, vp, i64, vp, i64, i32, i32, i32, i32, vp, vp, vp]
     lib.cs_op_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, vp]
     lib.cs_op_attention.argtypes = [vp, vp, i32, vp, i32, vp, vp]
     lib.cs_op_argmax_accept.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -433,6 +435,37 @@ def cs_decode_merged(model: Model, kv: KV, draft_model: Model, draft_kv: KV, pro
 def cs_prefill(model: Model, kv: KV, stream_idx: int, prompt: Sequence[int]):
     p = np.ascontiguousarray(prompt, dtype=np.int32)
     _check(load_library().cs_prefill(model.handle, kv.handle, stream_idx, p.ctypes.data, p.shape[0]))
+
+
+def _pack_prompts(kv: KV, prompts: Sequence[Sequence[int]]):
+    assert len(prompts) == kv.batch, "one prompt per stream of the cache"
+    lens = np.array([len(p) for p in prompts], dtype=np.int64)
+    flat = np.zeros((kv.batch, max(int(lens.max()), 1)), dtype=np.int32)
+    for b, p in enumerate(prompts):
+        flat[b, :len(p)] = np.asarray(p, dtype=np.int32)
+    return flat, lens
+
+
+def cs_prefill_batch(model: Model, kv: KV, prompts: Sequence[Sequence[int]]):
+    flat, lens = _pack_prompts(kv, prompts)
+    _check(load_library().cs_prefill_batch(model.handle, kv.handle, flat.ctypes.data, flat.shape[1],
+                                           lens.ctypes.data))
+
+
+def cs_decode_batch(model: Model, kv: KV, prompts: Sequence[Sequence[int]], max_new: int, gamma: int,
+                    k: int, policy="rightmost", eos_id: int = -1):
+    """Returns (one token list per stream, one stats dict per stream)."""
+    flat, lens = _pack_prompts(kv, prompts)
+    B = kv.batch
+    out = np.zeros((B, max(max_new, 1)), dtype=np.int32)
+    n_out = np.zeros(B, dtype=np.int64)
+    st = (cs_stats * B)()
+    _check(load_library().cs_decode_batch(model.handle, kv.handle, flat.ctypes.data, flat.shape[1],
+                                          lens.ctypes.data, max_new, gamma, k, _policy(policy), eos_id,
+                                          out.ctypes.data, n_out.ctypes.data, C.cast(st, C.c_void_p)))
+    toks = [out[b, :int(n_out[b])].tolist() for b in range(B)]
+    stats = [{n: getattr(st[b], n) for n, _ in cs_stats._fields_} for b in range(B)]
+    return toks, stats
 
 
 # ----------------------------------------------------------------------------------------

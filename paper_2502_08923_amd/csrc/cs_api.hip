@@ -113,6 +113,21 @@ __global__ void k_add_i32(int32_t* p, int32_t v, int n) {
     if (i < n) p[i] += v;
 }
 
+__global__ void k_add_i32_vec(int32_t* p, const int32_t* __restrict__ v, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] += v[i];
+}
+
+// the tokens a step appended to each history: out[b][0 .. accepted[b]] (k+1 slots per stream)
+__global__ void k_emitted(const int32_t* __restrict__ hist, int64_t stride,
+                          const int32_t* __restrict__ hist_len, const int32_t* __restrict__ accepted,
+                          int k, int32_t* __restrict__ out) {
+    const int b = blockIdx.x;
+    const int got = accepted[b] + 1;
+    const int32_t* __restrict__ h = hist + (int64_t)b * stride + hist_len[b] - got;
+    for (int i = threadIdx.x; i < got; i += blockDim.x) out[b * (k + 1) + i] = h[i];
+}
+
 __global__ void k_sum_parts(const float* __restrict__ part, int nparts, int64_t n,
                             float* __restrict__ y) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
@@ -217,7 +232,10 @@ static int model_build(cs_model* m, const cs_weights* w) {
     m->part_floats = (size_t)16 * R * widest;
     DEV_ALLOC(m->part, m->part_floats * 4);
     const size_t groups_verify = (size_t)c.max_batch * KVH * cs_ceil_div((H / KVH) * m->rows_max, 48);
-    const size_t groups_prompt = (size_t)KVH * cs_ceil_div((H / KVH) * m->prefill_rows, 48);
+    // prompt blocks: one stream with prefill_rows rows, or all streams in lock step with
+    // their share of the workspace rows each (one more query group per stream from rounding)
+    const size_t ws_rows = (size_t)(m->R_max > m->prefill_rows ? m->R_max : m->prefill_rows);
+    const size_t groups_prompt = (size_t)KVH * (cs_ceil_div((H / KVH) * ws_rows, 48) + c.max_batch);
     const size_t groups_max = groups_verify > groups_prompt ? groups_verify : groups_prompt;
     m->attn_part_floats = (size_t)(4 * (512 + groups_max) + 64) * 48 * (hd + 2);
     if (m->fast) DEV_ALLOC(m->attn_part, m->attn_part_floats * 4);
@@ -691,6 +709,164 @@ extern "C" int cs_decode_greedy(cs_model* m, cs_kv* kv, const int32_t* prompt, i
                                 int64_t max_new, int32_t eos_id, int32_t* out_tokens, int64_t* n_out) {
     return decode_impl(m, kv, prompt, prompt_len, max_new, 1, 0, CS_POLICY_RIGHTMOST, eos_id,
                        out_tokens, n_out, nullptr);
+}
+
+// -------------------------------------------------------------------------------------
+// all streams of a cache at once
+// -------------------------------------------------------------------------------------
+static int check_prompts(const cs_model* m, const cs_kv* kv, const int32_t* prompts, int64_t stride,
+                         const int64_t* prompt_len, int64_t* max_len_out) {
+    CS_REQUIRE(prompts && prompt_len, CS_E_ARG, "NULL prompt argument");
+    int64_t max_len = 0;
+    for (int b = 0; b < kv->B; ++b) {
+        CS_REQUIRE(prompt_len[b] >= 1, CS_E_ARG, "prompt %d must hold at least one token", b);
+        CS_REQUIRE(prompt_len[b] <= stride, CS_E_ARG, "prompt %d is longer than prompt_stride", b);
+        CS_REQUIRE(prompt_len[b] - 1 <= kv->cap, CS_E_CAPACITY, "prompt %d longer than the cache", b);
+        max_len = prompt_len[b] > max_len ? prompt_len[b] : max_len;
+        for (int64_t i = 0; i < prompt_len[b]; ++i) {
+            const int32_t t = prompts[(int64_t)b * stride + i];
+            CS_REQUIRE(t >= 0 && t < m->cfg.vocab, CS_E_ARG, "prompt %d token %lld out of vocabulary", b,
+                       (long long)i);
+        }
+    }
+    *max_len_out = max_len;
+    return CS_OK;
+}
+
+extern "C" int cs_prefill_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, int64_t prompt_stride,
+                                const int64_t* prompt_len) {
+    CS_REQUIRE(m && kv, CS_E_ARG, "cs_prefill_batch: NULL handle");
+    CS_REQUIRE(kv->m == m, CS_E_STATE, "kv cache belongs to a different model");
+    int64_t max_len = 0;
+    CS_TRY(check_prompts(m, kv, prompts, prompt_stride, prompt_len, &max_len));
+    const int B = kv->B;
+    CS_HIP(hipDeviceSynchronize());
+    CS_HIP(hipMemset(kv->d_len, 0, (size_t)B * 4));
+    for (int b = 0; b < B; ++b) kv->h_len_ub[b] = 0;
+    // Lock step: every pass runs the same number of rows for every stream.  A stream whose
+    // prompt is used up rides along on padding rows; their cache entries land beyond its
+    // length (dead rows) and, the block being causal, no live row ever sees them.
+    const int64_t ws_rows = m->R_max > m->prefill_rows ? m->R_max : m->prefill_rows;
+    const int64_t chunk = ws_rows / B > 0 ? ws_rows / B : 1;
+    const int64_t max_body = max_len - 1;
+    std::vector<int32_t> tok, inc((size_t)B);
+    int32_t* d_inc = nullptr;
+    CS_HIP(hipMalloc(&d_inc, (size_t)B * 4));
+    int rc = CS_OK;
+    for (int64_t c0 = 0; c0 < max_body && rc == CS_OK; c0 += chunk) {
+        const int rows = (int)(max_body - c0 < chunk ? max_body - c0 : chunk);
+        tok.assign((size_t)B * rows, 0);
+        for (int b = 0; b < B; ++b) {
+            const int64_t left = prompt_len[b] - 1 - c0;
+            const int64_t live = left < 0 ? 0 : (left < rows ? left : rows);
+            for (int64_t i = 0; i < live; ++i) tok[(size_t)b * rows + i] = prompts[(int64_t)b * prompt_stride + c0 + i];
+            inc[b] = (int32_t)live;
+        }
+        if (hipMemcpy(m->tok, tok.data(), tok.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(d_inc, inc.data(), (size_t)B * 4, hipMemcpyHostToDevice) != hipSuccess) {
+            cs_set_error("cs_prefill_batch: copy to device failed");
+            rc = CS_E_DEVICE;
+            break;
+        }
+        rc = forward_layers(m, kv, rows, nullptr);
+        if (rc != CS_OK) break;
+        k_add_i32_vec<<<(unsigned)cs_ceil_div(B, 64), 64, 0, nullptr>>>(kv->d_len, d_inc, B);
+        rc = cs_launch_ok("k_add_i32_vec");
+        for (int b = 0; b < B; ++b) kv->h_len_ub[b] += inc[b];
+    }
+    if (hipDeviceSynchronize() != hipSuccess && rc == CS_OK) {
+        cs_set_error("cs_prefill_batch: device error");
+        rc = CS_E_DEVICE;
+    }
+    (void)hipFree(d_inc);
+    return rc;
+}
+
+extern "C" int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, int64_t prompt_stride,
+                               const int64_t* prompt_len, int64_t max_new, int32_t gamma, int32_t k,
+                               int32_t policy, int32_t eos_id, int32_t* out_tokens, int64_t* n_out,
+                               cs_stats* stats) {
+    CS_REQUIRE(out_tokens && n_out, CS_E_ARG, "cs_decode_batch: NULL output");
+    CS_REQUIRE(max_new >= 0, CS_E_ARG, "max_new must be >= 0");
+    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(check_verify_args(m, kv, k));
+    const int B = kv->B;
+    int64_t max_len = 0;
+    CS_TRY(check_prompts(m, kv, prompts, prompt_stride, prompt_len, &max_len));
+    CS_REQUIRE(max_len + max_new + k + 1 <= kv->cap, CS_E_CAPACITY,
+               "cache capacity %lld < longest prompt + max_new + k + 1", (long long)kv->cap);
+    std::vector<cs_stats> st((size_t)B, cs_stats{0, 0, 0, 0});
+    std::vector<int64_t> emitted((size_t)B, 0);
+    std::vector<char> active((size_t)B, max_new > 0 ? 1 : 0);
+    for (int b = 0; b < B; ++b) n_out[b] = 0;
+    CS_TRY(cs_prefill_batch(m, kv, prompts, prompt_stride, prompt_len));
+    const int64_t stride = cs_round_up(max_len + max_new + k + 2, 4);
+    CS_REQUIRE(stride < (int64_t)1 << 31, CS_E_ARG, "history too long");
+    // device state: histories, then [hist_len | room | accepted | next | draft_len] (B each),
+    // then the tokens of the last step [B][k+1]
+    const size_t n_state = (size_t)5 * B + (size_t)B * (k + 1);
+    int32_t* d = nullptr;
+    CS_HIP(hipMalloc(&d, ((size_t)B * stride + n_state) * 4));
+    int32_t* d_state = d + (size_t)B * stride;
+    int32_t* d_new = d_state + 5 * B;
+    std::vector<int32_t> h((size_t)n_state, 0);
+    for (int b = 0; b < B; ++b) {
+        h[b] = (int32_t)prompt_len[b];
+        h[B + b] = (int32_t)max_new;
+    }
+    int rc = CS_OK;
+    if (hipMemcpy2D(d, (size_t)stride * 4, prompts, (size_t)prompt_stride * 4, (size_t)max_len * 4, B,
+                    hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(d_state, h.data(), n_state * 4, hipMemcpyHostToDevice) != hipSuccess) {
+        cs_set_error("cs_decode_batch: copy to device failed");
+        rc = CS_E_DEVICE;
+    }
+    auto any_active = [&]() {
+        for (int b = 0; b < B; ++b)
+            if (active[b]) return true;
+        return false;
+    };
+    while (rc == CS_OK && any_active()) {
+        rc = cs_step(m, kv, d, stride, d_state, d_state + B, gamma, k, policy, d_state + 2 * B,
+                     d_state + 3 * B, d_state + 4 * B, nullptr);
+        if (rc != CS_OK) break;
+        k_emitted<<<B, 64, 0, nullptr>>>(d, stride, d_state, d_state + 2 * B, k, d_new);
+        rc = cs_launch_ok("k_emitted");
+        if (rc != CS_OK) break;
+        if (hipMemcpy(h.data(), d_state, n_state * 4, hipMemcpyDeviceToHost) != hipSuccess) {
+            cs_set_error("cs_decode_batch: copy from device failed");
+            rc = CS_E_DEVICE;
+            break;
+        }
+        for (int b = 0; b < B && rc == CS_OK; ++b) {
+            kv->h_len_ub[b] = h[b] - 1;           // true length: everything but the pending token
+            if (!active[b]) continue;
+            const int tau = h[2 * B + b], got = tau + 1, dl = h[4 * B + b];
+            const int32_t* fresh = h.data() + 5 * B + (size_t)b * (k + 1);
+            st[b].steps += 1;
+            if (dl > 0) { st[b].attempts += 1; st[b].drafted += dl; st[b].accepted += tau; }
+            int take = got;
+            for (int i = 0; i < got; ++i)
+                if (eos_id >= 0 && fresh[i] == eos_id) { take = i + 1; active[b] = 0; break; }
+            for (int i = 0; i < take; ++i) out_tokens[(int64_t)b * max_new + emitted[b] + i] = fresh[i];
+            emitted[b] += take;
+            if (emitted[b] >= max_new) active[b] = 0;
+            if (!active[b] && h[B + b] > 0) {     // stopped by eos: take its remaining budget away
+                const int32_t zero = 0;
+                if (hipMemcpy(d_state + B + b, &zero, 4, hipMemcpyHostToDevice) != hipSuccess) {
+                    cs_set_error("cs_decode_batch: copy to device failed");
+                    rc = CS_E_DEVICE;
+                }
+            }
+        }
+    }
+    (void)hipFree(d);
+    if (rc != CS_OK) return rc;
+    for (int b = 0; b < B; ++b) {
+        n_out[b] = emitted[b];
+        if (stats) stats[b] = st[b];
+    }
+    return CS_OK;
 }
 
 // -------------------------------------------------------------------------------------

@@ -236,6 +236,7 @@ __global__ __launch_bounds__(AM_THREADS) void k_argmax_partial(const float* __re
 }
 
 // One wave per stream.  a_i = argmax of row i; tau = leading agreement with the draft;
+// (a stream whose emission budget `room` is used up is skipped, see below)
 // next = a_tau; the KV length grows by tau+1 (App. B.2: truncation past the accepted rows);
 // the accepted drafts and the free token are appended to the history (App. B.3 step 2d).
 __global__ __launch_bounds__(64) void k_accept(const int32_t* __restrict__ part, int nch, int k,
@@ -273,6 +274,13 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t* __restrict__ part,
     }
     __syncthreads();
     if (lane == 0) {
+        if (room && room[b] <= 0) {
+            // a stream with no emission budget left takes no part: nothing is accepted,
+            // emitted or appended, and its cache length stays (the row it computed is dead)
+            accepted[b] = 0;
+            next_tok[b] = -1;
+            return;
+        }
         const int m = min(draft_len[b], k);
         int tau = 0;
         while (tau < m && row_argmax[b * rows + tau] == draft[(int64_t)b * k + tau]) ++tau;

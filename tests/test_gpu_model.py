@@ -384,3 +384,125 @@ def test_capacity_and_argument_errors(tiny):
     with pytest.raises(cs.CopySpecError):
         cs.KV(model, 2, 64)
     kv.destroy()
+
+
+# ----------------------------------------------------------------------------------------
+# all streams of a cache at once
+# ----------------------------------------------------------------------------------------
+
+def _follows_oracle(w, prompt, toks, margin, cap):
+    """Every emitted token is the oracle's greedy token wherever its top-2 margin is safe (and
+    within the margin of the maximum otherwise); returns the number of strict comparisons."""
+    okv = orc.KVCache(w["shape"], cap)
+    pending = orc.prefill(w, okv, prompt)
+    strict = 0
+    for i, t in enumerate(toks):
+        logits = orc.forward_block(w, okv, [pending])[0]
+        okv.truncate(okv.length + 1)
+        top = np.partition(logits, -2)[-2:]
+        if top[1] - top[0] > margin:
+            assert t == orc.argmax_first(logits), f"token {i}"
+            strict += 1
+        else:
+            assert logits[t] >= logits.max() - margin, f"token {i}"
+        pending = t
+    return strict
+
+
+def _ragged_prompts(vocab, lens, seed):
+    return [synth.planted_history(seed + b, n, vocab, (8, 24), density=0.25, end="span")["tokens"].tolist()
+            for b, n in enumerate(lens)]
+
+
+def test_decode_batch_equals_single_stream_decodes_and_oracle():
+    """Three prompts of different lengths through one cache: every stream's output is what the
+    single-stream loop gives for it, follows the oracle, and stops on its own at eos."""
+    w = synth.model_weights(synth.TINY, synth.seed_for(1), threads=8)
+    B, k, new = 3, 10, 40
+    model = cs.Model(w, max_batch=B, max_k=k)
+    prompts = [synth.history_cfg1()["tokens"].tolist()] + _ragged_prompts(1024, [203, 75], 4100)
+    cap = 512 + new + k + 8
+    kvb = cs.KV(model, B, cap)
+    toks, stats = cs.cs_decode_batch(model, kvb, prompts, new, 3, k)
+    kv1 = cs.KV(model, 1, cap)
+    for b in range(B):
+        single, st1 = cs.cs_decode(model, kv1, prompts[b], new, 3, k)
+        assert toks[b] == single and len(toks[b]) == new, f"stream {b}"
+        assert {n: stats[b][n] for n in st1} == st1
+        assert kvb.len(b) == len(prompts[b]) + new - 1
+        assert _follows_oracle(w, prompts[b], toks[b], FP32_MARGIN, cap) >= new // 2
+    assert stats[0]["attempts"] >= 1
+    # eos: a token that stream 1 emits in the middle; every stream is cut after its first one
+    eos = toks[1][new // 2]
+    cut, _ = cs.cs_decode_batch(model, kvb, prompts, new, 3, k, eos_id=eos)
+    for b in range(B):
+        want = toks[b][:toks[b].index(eos) + 1] if eos in toks[b] else toks[b]
+        assert cut[b] == want, f"stream {b}"
+    assert len(cut[1]) <= new // 2 + 1
+    # no budget: nothing is emitted, the caches hold the prompts
+    none, _ = cs.cs_decode_batch(model, kvb, prompts, 0, 3, k)
+    assert none == [[], [], []] and [kvb.len(b) for b in range(B)] == [len(p) - 1 for p in prompts]
+    kvb.destroy()
+    kv1.destroy()
+    model.destroy()
+
+
+def test_prefill_batch_and_decode_batch_bf16():
+    """Lock-step prompt ingestion of four ragged streams (the longest needs three passes) leaves
+    the oracle's cache rows; the batched decode follows the oracle under the margin rule."""
+    shape = MINI128
+    B, k, new = 4, 10, 32
+    w = synth.model_weights(shape, 8128, threads=4)
+    model = cs.Model(w, max_batch=B, max_k=k)
+    lens = [300, 41, 2, 157]
+    prompts = _ragged_prompts(shape.vocab, [300, 41, 41, 157], 5200)
+    prompts[2] = prompts[2][:2]
+    cap = max(lens) + new + k + 8
+    kv = cs.KV(model, B, cap)
+    cs.cs_prefill_batch(model, kv, prompts)
+    for b, n in enumerate(lens):
+        assert kv.len(b) == n - 1
+        okv = orc.KVCache(shape, cap)
+        orc.prefill(w, okv, prompts[b], chunk=64)
+        for layer in range(shape.n_layers):
+            if n > 1:
+                k_rows, v_rows = kv.read(layer, b, 0, n - 1)
+                assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :n - 1]).max() < 8e-2
+                assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :n - 1]).max() < 8e-2
+    toks, stats = cs.cs_decode_batch(model, kv, prompts, new, 3, k)
+    strict = 0
+    for b in range(B):
+        assert len(toks[b]) == new and stats[b]["steps"] <= new
+        strict += _follows_oracle(w, prompts[b], toks[b], MARGIN, cap)
+    assert strict >= B * new // 2
+    with pytest.raises(cs.CopySpecError):
+        cs.cs_decode_batch(model, kv, prompts, cap, 3, k)         # does not fit the cache
+    with pytest.raises(cs.CopySpecError):
+        cs.cs_decode_batch(model, kv, prompts[:3] + [[shape.vocab]], new, 3, k)
+    kv.destroy()
+    model.destroy()
+
+
+def test_decode_batch_full_acceptance_repeat_model():
+    """A model whose greedy token repeats its input: every history becomes x, x, x, ..., every
+    match is accepted whole, in every stream; steps, attempts and accepted counts are the
+    oracle's for both policies (the earliest match copies whole blocks, the rightmost one only
+    the gamma tokens that lie between it and the end of the history)."""
+    shape = SMALLF32
+    B, k, new = 2, 10, 45
+    w = _repeat_model(shape, 99)
+    model = cs.Model(w, max_batch=B, max_k=k)
+    prompts = [[3, 8, 8, 8, 8, 8, 8], [1, 2, 5]]
+    kv = cs.KV(model, B, 128)
+    for policy in ("rightmost", "first"):
+        toks, stats = cs.cs_decode_batch(model, kv, prompts, new, 3, k, policy)
+        assert toks[0] == [8] * new and toks[1] == [5] * new
+        for b in range(B):
+            otoks, ost = orc.copyspec_decode(w, prompts[b], new, 3, k, policy)
+            assert otoks == toks[b]
+            assert (stats[b]["steps"], stats[b]["attempts"], stats[b]["accepted"]) == \
+                   (ost["steps"], ost["attempts"], ost["accepted"]), (policy, b)
+            assert stats[b]["accepted"] == stats[b]["drafted"] > 0
+    assert stats[0]["accepted"] > 3 * stats[0]["attempts"]          # "first": long blocks
+    kv.destroy()
+    model.destroy()
