@@ -488,7 +488,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     const int ktok0 = 8 * (c >> 2) + (c & 3);
     if (wave == FA_QG) {
         // ---------------- producer: K/V blocks -> LDS ring ----------------
-        bf16x8 kr[2][2][KS], vr[2][MT];       // two blocks in flight in registers
+        bf16x8 kr[3][2][KS], vr[3][MT];       // three blocks in flight in registers (block j in slot j % 3)
         auto load = [&](int slot, int blk) {
             const int bl = blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0);   // clamped
             const int t0 = (nblocks > 0 ? t_begin : 0) + bl * 32;
@@ -527,20 +527,27 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
         // stores into stages nobody reads; the barrier count is the workgroup's, not the team's
         load(0, 0);
         load(1, 1);
+        load(2, 2);
         store(0, 0, 0);
-        load(0, 2);
+        load(0, 3);
         store(1, 1, 1);
-        load(1, 3);
+        load(1, 4);
         __syncthreads();                                   // stages 0, 1 and the query tiles are ready
-        for (int i = 0; i < nblocks_wg; i += 2) {
-            // consumer iteration i reads stages i and i+1: block i+2 (registers slot 0) goes to
-            // stage (i+2)%3, which held block i-1; refill the slot with block i+4
-            store(0, (i + 2) % FA_STAGES, i + 2);
-            load(0, i + 4);
+        static_assert(FA_STAGES == 3, "block j: register slot j % 3, LDS stage j % 3");
+        for (int i = 0; i < nblocks_wg; i += 3) {
+            // consumer iteration i reads stages i and i+1: block i+2 goes to stage (i+2)%3, which
+            // held block i-1; its register slot is refilled with block i+5, so blocks i+3, i+4
+            // and i+5 (48 KB) are in flight while block i is being multiplied
+            store(2, 2, i + 2);
+            load(2, i + 5);
             __syncthreads();
             if (i + 1 >= nblocks_wg) break;
-            store(1, (i + 3) % FA_STAGES, i + 3);
-            load(1, i + 5);
+            store(0, 0, i + 3);
+            load(0, i + 6);
+            __syncthreads();
+            if (i + 2 >= nblocks_wg) break;
+            store(1, 1, i + 4);
+            load(1, i + 7);
             __syncthreads();
         }
         return;
