@@ -21,7 +21,10 @@
  *     thread-local description of the most recent failure.  On an argument or capacity
  *     error nothing has been modified.
  *   - Calls on one handle are not re-entrant; calls that share a handle on different
- *     streams race.
+ *     streams race.  The match scans (cs_find_match*, cs_step and the decode loops) keep
+ *     their per-chunk results in one library-owned device buffer per process (grown on
+ *     demand, which synchronises the device): scans enqueued on different streams must
+ *     not overlap in time.  The instrumentation (cs_profile_*) is process-wide too.
  */
 #ifndef COPYSPEC_H
 #define COPYSPEC_H
