@@ -223,10 +223,10 @@ static int model_build(cs_model* m, const cs_weights* w) {
     const size_t a = m->asz;
     const int wide = d > nq ? d : nq;
     DEV_ALLOC(m->x, R * d * 4);
-    DEV_ALLOC(m->xn, R * wide * 4);
+    DEV_ALLOC(m->xn, R * wide * 4 > cs_xt_bytes(R, wide) ? R * wide * 4 : cs_xt_bytes(R, wide));
     DEV_ALLOC(m->q, R * nq * 4);
     if (!m->fast) DEV_ALLOC(m->gu, R * 2 * F * 4);
-    DEV_ALLOC(m->act, R * F * (a > 0 ? a : 4));
+    DEV_ALLOC(m->act, R * F * (a > 0 ? a : 4) > cs_xt_bytes(R, F) ? R * F * (a > 0 ? a : 4) : cs_xt_bytes(R, F));
     DEV_ALLOC(m->logits, (size_t)m->R_max * V * 4);
     const int widest = nqkv > d ? nqkv : d;
     m->part_floats = (size_t)16 * R * widest;
@@ -523,12 +523,12 @@ static int forward_layers(cs_model* m, cs_kv* kv, int rows, hipStream_t s) {
     int np_prev = 0, np = 1;
     for (int l = 0; l < c.n_layers; ++l) {
         const cs_layer_dev& L = m->layers[l];
-        CS_TRY(cs_addnorm_launch(m, m->part, np_prev, L.norm1, m->xn, R, s));
+        CS_TRY(cs_addnorm_launch(m, m->part, np_prev, L.norm1, m->xn, R, nqkv, s));
         CS_TRY(cs_gemm_launch(m, m->xn, L.wqkv, m->part, R, nqkv, d, CS_GEMM_STORE, 1, &np, s));
         CS_TRY(cs_rope_append_launch(m, kv, l, m->part, np, rows, s));
-        CS_TRY(cs_attention_launch(m, kv, l, rows, len_ub, s));
+        CS_TRY(cs_attention_launch(m, kv, l, rows, len_ub, 1, s));
         CS_TRY(cs_gemm_launch(m, m->xn, L.wo, m->part, R, d, nq, CS_GEMM_STORE, 1, &np, s));
-        CS_TRY(cs_addnorm_launch(m, m->part, np, L.norm2, m->xn, R, s));
+        CS_TRY(cs_addnorm_launch(m, m->part, np, L.norm2, m->xn, R, 2 * c.d_ff, s));
         if (m->fast) {
             CS_TRY(cs_gemm_launch(m, m->xn, L.wgu, nullptr, R, 2 * c.d_ff, d, CS_GEMM_SWIGLU, 0,
                                   nullptr, s));
@@ -538,7 +538,8 @@ static int forward_layers(cs_model* m, cs_kv* kv, int rows, hipStream_t s) {
         }
         CS_TRY(cs_gemm_launch(m, m->act, L.wd, m->part, R, d, c.d_ff, CS_GEMM_STORE, 1, &np_prev, s));
     }
-    return cs_addnorm_launch(m, m->part, np_prev, m->final_norm, m->xn, R, s);
+    // the final norm feeds the lm_head (callers that only fill the cache never read it)
+    return cs_addnorm_launch(m, m->part, np_prev, m->final_norm, m->xn, R, c.vocab, s);
 }
 
 static int verify_impl(cs_model* m, cs_kv* kv, const int32_t* d_pending, const int32_t* d_draft,
@@ -1007,11 +1008,17 @@ extern "C" int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void*
     CS_REQUIRE(m->fast, CS_E_STATE, "cs_op_gemm(bf16) needs a model that runs the bf16 kernels");
     // the tuned kernel reads W in its tiled fp16 layout and X as fp16: convert into temporaries
     void* wt = nullptr;
-    CS_HIP(hipMalloc(&wt, (size_t)N * K * 2 + (size_t)R * K * 2));
+    const size_t x_bytes = cs_xt_bytes(R, K);
+    CS_HIP(hipMalloc(&wt, (size_t)N * K * 2 + 2 * x_bytes));
     void* xt = (char*)wt + (size_t)N * K * 2;
     int rc = cs_tile_weights_launch(W, nullptr, N, K, 0, N, 0, wt, s);
     if (rc == CS_OK) rc = cs_convert_launch(X, CS_T_BF16, xt, CS_T_F16, (int64_t)R * K, s);
     X = xt;
+    if (rc == CS_OK && cs_gemm_x_tiled(R, N)) {            // the many-row kernel reads fragment order
+        void* xt2 = (char*)xt + x_bytes;
+        rc = cs_tile_x_launch(xt, xt2, R, K, s);
+        X = xt2;
+    }
     int np = 1;
     if (rc == CS_OK) {
         if ((size_t)R * N > m->part_floats) {   // too large for the workspace: no K split
@@ -1044,7 +1051,7 @@ extern "C" int cs_op_attention(cs_model* m, cs_kv* kv, int32_t layer, const floa
     CS_TRY(kv_check_room(kv, rows));
     const int64_t n = (int64_t)kv->B * rows * m->cfg.n_heads * m->cfg.head_dim;
     CS_TRY(cs_convert_launch(q, CS_T_F32, m->q, m->fast ? CS_T_BF16 : CS_T_F32, n, s));
-    CS_TRY(cs_attention_launch(m, kv, layer, rows, kv_max_ub(kv), s));
+    CS_TRY(cs_attention_launch(m, kv, layer, rows, kv_max_ub(kv), 0, s));
     return cs_convert_launch(m->xn, m->fast ? CS_T_F16 : CS_T_F32, out, CS_T_F32, n, s);
 }
 

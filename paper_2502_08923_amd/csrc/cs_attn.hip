@@ -715,7 +715,8 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
 #define FA_MAX_SPLIT 64
 template <typename OT>
 __global__ void k_attn_merge(const float* __restrict__ po, const float* __restrict__ pml, int rows,
-                             int H, int KVH, int HD, int nqg, int nsplit, OT* __restrict__ out) {
+                             int H, int KVH, int HD, int nqg, int nsplit, OT* __restrict__ out,
+                             int tiled) {
     const int n = blockIdx.x;                 // query row within the KV head: i*G + gq
     const int kvh = blockIdx.y, b = blockIdx.z;
     const int G = H / KVH;
@@ -752,12 +753,14 @@ __global__ void k_attn_merge(const float* __restrict__ po, const float* __restri
         float num = 0.f;
 #pragma unroll 8
         for (int w = 0; w < nsplit; ++w) num += wgt[w] * o[(int64_t)w * FA_QROWS * HD + d];
-        cs_st(out, ((int64_t)r * H + kvh * G + gq) * HD + d, num * inv);
+        // tiled: the output projection runs the many-row GEMM, which reads fragment order
+        const int col = (kvh * G + gq) * HD + d;
+        cs_st(out, tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col, num * inv);
     }
 }
 
 int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
-                        hipStream_t s) {
+                        int for_o_proj, hipStream_t s) {
     const cs_model_cfg& c = m->cfg;
     const int B = kv->B, H = c.n_heads, KVH = c.n_kv_heads, hd = c.head_dim;
     const int64_t per_layer = (int64_t)B * KVH * kv->cap * hd;
@@ -779,6 +782,9 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const int QR = G * rows;
     const int nqg = (int)cs_ceil_div(QR, FA_QROWS);
     const int64_t n_tok_ub = len_ub + rows;
+    // layout of the merged output: fragment order if the output projection (d_model outputs)
+    // of these B*rows rows runs the many-row GEMM
+    const int tiled = for_o_proj && cs_gemm_x_tiled(B * rows, c.d_model) ? 1 : 0;
     const bf16_t* kc = (const bf16_t*)kv->k + layer * per_layer;
     const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
     int nsplit;
@@ -812,7 +818,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
         dim3 mgrid(QR, KVH, B);
         const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
         k_attn_merge<f16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
-                                                              (f16_t*)m->xn);
+                                                              (f16_t*)m->xn, tiled);
         cs_prof_end(pm, s);
         return cs_launch_ok("k_attn_merge");
     }
@@ -844,7 +850,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     dim3 mgrid(QR, KVH, B);
     const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
     k_attn_merge<f16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
-                                                          (f16_t*)m->xn);
+                                                          (f16_t*)m->xn, tiled);
     cs_prof_end(pm, s);
     return cs_launch_ok("k_attn_merge");
 }

@@ -131,8 +131,9 @@ int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, 
 int cs_embed_launch(const cs_model* m, const int32_t* tok, int R, hipStream_t s);
 int cs_rope_table_launch(const cs_model* m, const int32_t* kv_len, int B, int rows, hipStream_t s);
 // x[r] += sum of nparts partial tiles (part[p][r][:]) and, if xn_out, xn_out[r] = rmsnorm(x[r])*gain
+// (next_N: output width of the GEMM that reads xn_out; it decides the layout of xn_out)
 int cs_addnorm_launch(const cs_model* m, const float* part, int nparts,
-                      const float* gain, void* xn_out, int R, hipStream_t s);
+                      const float* gain, void* xn_out, int R, int next_N, hipStream_t s);
 int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* qkv, int nparts,
                           int rows, hipStream_t s);
 int cs_swiglu_launch(const cs_model* m, int R, hipStream_t s);
@@ -153,13 +154,29 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
 int cs_gemm_plain_launch(int dtype, const float* X, const void* W, float* Y, int R, int N, int K,
                          hipStream_t s);
 
+// The many-row GEMM kernel reads its activations in MFMA fragment order as well:
+// X_t[r/16][k/32][lane = r%16 + 16*((k%32)/8)][k%8] (K = row length, row tiles padded to 16
+// rows), so that one direct-to-LDS request is 1 KB of contiguous memory, like a request for W.
+// cs_gemm_x_tiled says whether the GEMM of R rows by N outputs runs that kernel; the producer
+// of its X (norm, attention merge, SwiGLU epilogue) then writes this layout.  Four consecutive
+// k (k % 4 == 0) stay contiguous.
+bool cs_gemm_x_tiled(int R, int N);
+__host__ __device__ __forceinline__ int64_t cs_xt_index(int r, int k, int K) {
+    return ((int64_t)(r >> 4) * (K >> 5) + (k >> 5)) * 512 + (((r & 15) + 16 * ((k & 31) >> 3)) << 3) + (k & 7);
+}
+// bytes of an f16 activation matrix of R rows by K in that layout
+static inline size_t cs_xt_bytes(int64_t R, int64_t K) { return (size_t)((R + 15) / 16) * (K >> 5) * 1024; }
+// row-major f16 [R][K] -> that layout (single operations and tests)
+int cs_tile_x_launch(const void* src, void* dst, int R, int K, hipStream_t s);
+
 // bf16 weights of the tuned GEMM live in MFMA fragment order (see cs_gemm.hip)
 int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int rowmap, int N_total,
                            int n_off, void* dst, hipStream_t s);
 
-// attention: reads m->q, writes m->xn (GEMM-input type) as [R][H*hd]
+// attention: reads m->q, writes m->xn (GEMM-input type) as [R][H*hd], or, if for_o_proj, in
+// the layout the output projection's GEMM reads
 int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
-                        hipStream_t s);
+                        int for_o_proj, hipStream_t s);
 
 // conversion helpers
 // element type codes for cs_convert_launch

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
                                                           const float* __restrict__ part,
                                                           int nparts, int64_t part_stride, int d,
                                                           float eps, const float* __restrict__ gain,
-                                                          OutT* __restrict__ xn) {
+                                                          OutT* __restrict__ xn, int tiled) {
     const int r = blockIdx.x;
     const int nvec = d >> 2;                 // d is a multiple of 4 (checked on the host)
     float4 v[NORM_MAXV];
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
         const int c = threadIdx.x + u * NORM_THREADS;
         if (c < nvec) {
             const float4 gn = *reinterpret_cast<const float4*>(gain + 4 * c);
-            const int64_t off = (int64_t)r * d + 4 * c;
+            // tiled: the reader is the many-row GEMM, which wants fragment order
+            const int64_t off = tiled ? cs_xt_index(r, 4 * c, d) : (int64_t)r * d + 4 * c;
             cs_st(xn, off + 0, v[u].x * scale * gn.x);
             cs_st(xn, off + 1, v[u].y * scale * gn.y);
             cs_st(xn, off + 2, v[u].z * scale * gn.z);
@@ -336,15 +337,15 @@ int cs_embed_launch(const cs_model* m, const int32_t* tok, int R, hipStream_t s)
 }
 
 int cs_addnorm_launch(const cs_model* m, const float* part, int nparts,
-                      const float* gain, void* xn_out, int R, hipStream_t s) {
+                      const float* gain, void* xn_out, int R, int next_N, hipStream_t s) {
     const int d = m->cfg.d_model;
     const int64_t ps = (int64_t)R * d;
-    if (xn_out && m->fast)
+    if (xn_out && m->fast) {
         k_addnorm<f16_t><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
-                                                    (f16_t*)xn_out);
-    else
+                                                    (f16_t*)xn_out, cs_gemm_x_tiled(R, next_N) ? 1 : 0);
+    } else
         k_addnorm<float><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
-                                                    (float*)xn_out);
+                                                    (float*)xn_out, 0);
     return cs_launch_ok("k_addnorm");
 }
 

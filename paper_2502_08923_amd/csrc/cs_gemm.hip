@@ -68,7 +68,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
                                                             const f16_t* __restrict__ W,
                                                             float* __restrict__ Y,
                                                             f16_t* __restrict__ act, int R, int N,
-                                                            int K, int Ks, int RB) {
+                                                            int K, int Ks, int RB, int act_tiled) {
     __shared__ __attribute__((aligned(16))) unsigned char xs[2][16 * NT * GEMM_LDS_ROW];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -231,7 +231,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
                     const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
                     o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
                 }
-                *reinterpret_cast<f16x4*>(act + (int64_t)r * F + f) = o;
+                // act_tiled: the down projection runs the many-row GEMM (fragment order)
+                *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
             }
         }
     }
@@ -249,8 +250,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 // fragment reads are conflict-free without padding; the pre-tiled W is already stored that
 // way in memory.  The operands never pass through registers on their way in: every wave
 // issues 16-byte direct-to-LDS loads (lane l's 16 bytes land at the wave-uniform LDS address
-// in M0 plus 16*l, so one load fills one fragment block; an X block is gathered, lane l
-// fetching row l % 16 at K group l / 16).  K advances 32 at a time through a ring of four
+// in M0 plus 16*l, so one load fills one fragment block; X is stored in the same order by
+// whoever produces it, see cs_gemm_x_tiled).  K advances 32 at a time through a ring of four
 // LDS stages.  Chunk c+3 is requested
 // while chunk c is multiplied; one barrier per chunk publishes chunk c+1 and frees the stage
 // of chunk c-1, and the first fragments of chunk c+1 are read before that chunk's barrier so
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
                                                          const f16_t* __restrict__ W,
                                                          float* __restrict__ Y,
                                                          f16_t* __restrict__ act, int R, int N, int K,
-                                                         int Ks, int RB) {
+                                                         int Ks, int RB, int act_tiled) {
     constexpr int XT = 2 * NT;                        // X row tiles per workgroup
     constexpr int NBLK = 16 + XT;                     // 1 KB blocks per stage: 16 W tiles, then X tiles
     constexpr int XLD = (XT + 7) / 8;                 // X loads per wave per stage (the last may be partial)
@@ -302,36 +303,40 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
     const int n_tiles = N >> 4;
     const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;
 
-    // wave w requests W tiles w, w+8 and X tiles w, w+8, ... of every chunk.  Per-lane byte
-    // offsets (32 bits) are fixed; the chunk moves the uniform base.
-    unsigned woff[2], xoff[XLD];
+    // wave w requests W tiles w, w+8 and X tiles w, w+8, ... of every chunk.  Both operands are
+    // stored in fragment order (W: see k_tile_w; X: cs_xt_index), so every request is one 1 KB
+    // block: the lane offset is 16*lane for all of them and the block moves the uniform base.
+    const unsigned lane16 = lane * 16;
+    const int rt_tiles = (R + 15) >> 4;
+    const int64_t x_pitch = (int64_t)(K >> 5) * 512;                   // elements per X row tile
+    int tw[2], tx[XLD];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        int t = w_tile * 16 + wave + 8 * i;
-        t = t < n_tiles ? t : n_tiles - 1;
-        woff[i] = (unsigned)(t * 4 * 512 + lane * 8) * 2u;
+        const int t = w_tile * 16 + wave + 8 * i;
+        tw[i] = t < n_tiles ? t : n_tiles - 1;
     }
 #pragma unroll
     for (int i = 0; i < XLD; ++i) {
         int j = wave + 8 * i;
         j = j < XT ? j : XT - 1;
-        int r = r_base + j * 16 + lrow;
-        r = r < R ? r : R - 1;
-        xoff[i] = (unsigned)(r * K + k_begin + g * 8) * 2u;   // R*K < 2^31 (host check)
+        const int t = (r_base >> 4) + j;
+        tx[i] = t < rt_tiles ? t : rt_tiles - 1;
     }
     const f16_t* wbase = W + (int64_t)(k_begin / GEMM_KC) * chunk_stride;
+    const f16_t* xbase = X + (int64_t)(k_begin / TD_KC) * 512;
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
     // request chunk c into stage sb
     auto issue = [&](int sb, int c) {
         const unsigned dst = lds0 + sb * STAGE + wave * 1024;
         const f16_t* wc = wbase + (int64_t)(c >> 2) * chunk_stride + (c & 3) * 512;
-        const f16_t* xc = X + c * TD_KC;
+        const f16_t* xc = xbase + (int64_t)c * 512;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) cs_load_to_lds(woff[i], wc, dst + 8 * i * 1024);
+        for (int i = 0; i < 2; ++i) cs_load_to_lds(lane16, wc + (int64_t)tw[i] * 2048, dst + 8 * i * 1024);
 #pragma unroll
         for (int i = 0; i < XLD; ++i) {
-            if (8 * i + 7 < XT || wave + 8 * i < XT) cs_load_to_lds(xoff[i], xc, dst + (16 + 8 * i) * 1024);
+            if (8 * i + 7 < XT || wave + 8 * i < XT)
+                cs_load_to_lds(lane16, xc + tx[i] * x_pitch, dst + (16 + 8 * i) * 1024);
         }
     };
     const unsigned char* a_base = lds + wn * 4 * 1024 + lane * 16;
@@ -420,7 +425,7 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
                     const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
                     o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
                 }
-                *reinterpret_cast<f16x4*>(act + (int64_t)r * F + f) = o;
+                *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
             }
         }
     }
@@ -428,30 +433,30 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
 
 template <int NT>
 static int launch_tile(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K, int mode,
-                       int ksplit, hipStream_t s) {
-    CS_REQUIRE((int64_t)R * K < ((int64_t)1 << 31), CS_E_UNSUPPORTED, "R*K too large for the many-row GEMM");
+                       int ksplit, int act_tiled, hipStream_t s) {
+    CS_REQUIRE(((int64_t)R + 15) * K < ((int64_t)1 << 31), CS_E_UNSUPPORTED, "R*K too large for the many-row GEMM");
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     const int RB = (int)cs_ceil_div(R, 32 * NT);
     dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, TG_WROWS), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
-    if (mode == CS_GEMM_STORE) k_gemm_dma<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
-    else k_gemm_dma<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+    if (mode == CS_GEMM_STORE) k_gemm_dma<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+    else k_gemm_dma<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_dma");
 }
 
 template <int MT, int NT>
 static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K,
-                       int mode, int ksplit, hipStream_t s) {
+                       int mode, int ksplit, int act_tiled, hipStream_t s) {
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     const int RB = (int)cs_ceil_div(R, 16 * NT);
     dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, 64 * MT), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
     if (mode == CS_GEMM_STORE) {
-        k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+        k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     } else {
         if constexpr (MT % 2 == 0)
-            k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB);
+            k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     }
     cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_mfma");
@@ -503,6 +508,28 @@ int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int 
     return cs_launch_ok("k_tile_w");
 }
 
+bool cs_gemm_x_tiled(int R, int N) { return R > 96 && (cs_ceil_div(N, TG_WROWS) >= 192 || R > 288); }
+
+// f16 [R][K] row-major -> fragment order (cs_xt_index); rows of the last tile beyond R are zero
+__global__ void k_tile_x(const f16_t* __restrict__ src, f16_t* __restrict__ dst, int R, int K, int rt_tiles) {
+    // (one thread per 8 consecutive k of one row)
+    const int64_t n = (int64_t)rt_tiles * 16 * (K / 8);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int r = (int)(i / (K / 8)), k = (int)(i % (K / 8)) * 8;
+        f16x8 v = (f16x8){0, 0, 0, 0, 0, 0, 0, 0};
+        if (r < R) v = *reinterpret_cast<const f16x8*>(src + (int64_t)r * K + k);
+        *reinterpret_cast<f16x8*>(dst + cs_xt_index(r, k, K)) = v;
+    }
+}
+
+int cs_tile_x_launch(const void* src, void* dst, int R, int K, hipStream_t s) {
+    const int rt_tiles = (int)cs_ceil_div(R, 16);
+    const int64_t n = (int64_t)rt_tiles * 16 * (K / 8);
+    k_tile_x<<<(unsigned)(cs_ceil_div(n, 256) < 4096 ? cs_ceil_div(n, 256) : 4096), 256, 0, s>>>(
+        (const f16_t*)src, (f16_t*)dst, R, K, rt_tiles);
+    return cs_launch_ok("k_tile_x");
+}
+
 int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, int R, int N, int K,
                    int mode, int allow_split, int* nparts_out, hipStream_t s) {
     if (nparts_out) *nparts_out = 1;
@@ -530,7 +557,9 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     // steps at the 8B shapes it wins from 97 rows on for the lm_head (501 tiles) and from 289
     // rows on for every projection (at 168 and 264 rows the q/k/v and gate/up projections,
     // 24 and 112 tiles, are still faster through the weight-streaming kernel).
-    const bool tile = R > 96 && (cs_ceil_div(N, TG_WROWS) >= 192 || R > 288);
+    const bool tile = cs_gemm_x_tiled(R, N);
+    // the SwiGLU epilogue writes the input of the down projection (d_model outputs, same rows)
+    const int act_tiled = mode == CS_GEMM_SWIGLU && cs_gemm_x_tiled(R, m->cfg.d_model) ? 1 : 0;
     const int rt_total = (int)cs_ceil_div(R, 16);
     const int r_blocks = tile ? (int)cs_ceil_div(rt_total, 18) : (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;
@@ -551,21 +580,21 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     f16_t* act = (f16_t*)m->act;
     if (tile) {
         switch ((int)cs_ceil_div(rt, 2)) {           // 16-row X tiles per wave
-            case 1: case 2: case 3: case 4: return launch_tile<4>(x, w, Y, act, R, N, K, mode, nparts, s);
-            case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, s);
-            case 6: return launch_tile<6>(x, w, Y, act, R, N, K, mode, nparts, s);
-            case 7: return launch_tile<7>(x, w, Y, act, R, N, K, mode, nparts, s);
-            case 8: return launch_tile<8>(x, w, Y, act, R, N, K, mode, nparts, s);
-            default: return launch_tile<9>(x, w, Y, act, R, N, K, mode, nparts, s);
+            case 1: case 2: case 3: case 4: return launch_tile<4>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 6: return launch_tile<6>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 7: return launch_tile<7>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 8: return launch_tile<8>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            default: return launch_tile<9>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
         }
     }
     switch (rt) {
-        case 1: return launch_mfma<2, 1>(x, w, Y, act, R, N, K, mode, nparts, s);
-        case 2: return launch_mfma<2, 2>(x, w, Y, act, R, N, K, mode, nparts, s);
-        case 3: return launch_mfma<2, 3>(x, w, Y, act, R, N, K, mode, nparts, s);
-        case 4: return launch_mfma<2, 4>(x, w, Y, act, R, N, K, mode, nparts, s);
-        case 5: return launch_mfma<2, 5>(x, w, Y, act, R, N, K, mode, nparts, s);
-        default: return launch_mfma<2, 6>(x, w, Y, act, R, N, K, mode, nparts, s);
+        case 1: return launch_mfma<2, 1>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+        case 2: return launch_mfma<2, 2>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+        case 3: return launch_mfma<2, 3>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+        case 4: return launch_mfma<2, 4>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+        case 5: return launch_mfma<2, 5>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+        default: return launch_mfma<2, 6>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
     }
 }
 
