@@ -2,6 +2,7 @@
 // residual-add + RMSNorm, rotary + KV append, SwiGLU, greedy argmax + accept rule + KV
 // length update + history append (Sec. 3.2, App. B.2, App. B.3 step 2).
 #include "cs_common.h"
+#include <type_traits>
 
 // -------------------------------------------------------------------------------------
 // block tokens and rotary table
@@ -97,10 +98,16 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
             const float4 gn = *reinterpret_cast<const float4*>(gain + 4 * c);
             // tiled: the reader is the many-row GEMM, which wants fragment order
             const int64_t off = tiled ? cs_xt_index(r, 4 * c, d) : (int64_t)r * d + 4 * c;
-            cs_st(xn, off + 0, v[u].x * scale * gn.x);
-            cs_st(xn, off + 1, v[u].y * scale * gn.y);
-            cs_st(xn, off + 2, v[u].z * scale * gn.z);
-            cs_st(xn, off + 3, v[u].w * scale * gn.w);
+            if constexpr (std::is_same<OutT, f16_t>::value) {   // one 8-byte store
+                const f16x4 o = (f16x4){(f16_t)(v[u].x * scale * gn.x), (f16_t)(v[u].y * scale * gn.y),
+                                        (f16_t)(v[u].z * scale * gn.z), (f16_t)(v[u].w * scale * gn.w)};
+                *reinterpret_cast<f16x4*>(xn + off) = o;
+            } else {
+                cs_st(xn, off + 0, v[u].x * scale * gn.x);
+                cs_st(xn, off + 1, v[u].y * scale * gn.y);
+                cs_st(xn, off + 2, v[u].z * scale * gn.z);
+                cs_st(xn, off + 3, v[u].w * scale * gn.w);
+            }
         }
     }
 }
