@@ -255,6 +255,15 @@ def test_verify_llama8b_width_many_rows():
     assert worst <= 2e-2, worst
 
 
+def test_verify_llama8b_width_528_rows():
+    """8B width, batch 16, k = 32: with 528 block rows every projection runs the many-row kernel,
+    so every GEMM input (both norms, the merged attention output, the SwiGLU output) is written in
+    fragment order by its producer; 1 layer, short cache."""
+    shape = synth.LLAMA_8B.with_layers(1)
+    worst = _deep_verify(shape, 16, 300, 32, [3, 15], seed=synth.seed_for(5) + 1)
+    assert worst <= 2e-2, worst
+
+
 def test_verify_llama8b_width_batch8():
     """8B width, batch 8, 18431 cached rows, k = 10 (the benchmark's launch configuration),
     4 of the 32 layers; the oracle checks two sampled streams."""
