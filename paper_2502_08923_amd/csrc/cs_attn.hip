@@ -570,23 +570,27 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
-    float m_run[FA_NT];
+    float m_run[FA_NT], thr[FA_NT];
 #pragma unroll
-    for (int nt = 0; nt < FA_NT; ++nt) m_run[nt] = -INFINITY;
+    for (int nt = 0; nt < FA_NT; ++nt) m_run[nt] = thr[nt] = -INFINITY;
     const float scale2 = 1.4426950408889634f / sqrtf((float)HD);
+    const float inv_scale2 = sqrtf((float)HD) / 1.4426950408889634f;
     const bf16_t one = (bf16_t)1.0f;
     const bf16x8 ones = (bf16x8){one, one, one, one, one, one, one, one};
 
     // scores of one block: S^T = K Q^T from the K fragments of stage `sp`
     // the wave's query fragments stay in registers for the whole token range (read once from
     // the staged tile, after the first barrier below)
-    bf16x8 qreg[FA_NT][KS];
+    constexpr int QS_REG = KS;          // k-steps whose query fragments stay in registers (all of them fit)
+    bf16x8 qreg[FA_NT][QS_REG];
+    auto q_lds = [&](int nt, int s) {
+        return *reinterpret_cast<const bf16x8*>(myq + (nt * 16 + c) * QROW + s * 64 + g * 16);
+    };
     auto load_q = [&]() {
 #pragma unroll
         for (int nt = 0; nt < FA_NT; ++nt)
 #pragma unroll
-            for (int s = 0; s < KS; ++s)
-                qreg[nt][s] = *reinterpret_cast<const bf16x8*>(myq + (nt * 16 + c) * QROW + s * 64 + g * 16);
+            for (int s = 0; s < QS_REG; ++s) qreg[nt][s] = q_lds(nt, s);
     };
     auto scores = [&](const unsigned char* sp, f32x4 (&sacc)[2][FA_NT]) {
         // all K fragments of the block are requested at once (LDS latency is ~100 cycles and
@@ -602,8 +606,9 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
             f32x4 z0 = (f32x4){0.f, 0.f, 0.f, 0.f}, z1 = z0;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qreg[nt][s], z0, 0, 0, 0);
-                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qreg[nt][s], z1, 0, 0, 0);
+                const bf16x8 qf = s < QS_REG ? qreg[nt][s] : q_lds(nt, s);
+                z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf, z0, 0, 0, 0);
+                z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf, z1, 0, 0, 0);
             }
             sacc[0][nt] = z0;
             sacc[1][nt] = z1;
@@ -612,44 +617,60 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     // softmax update and O^T += V^T P^T for the block whose scores are in `sacc`
     auto finish = [&](const f32x4 (&sacc)[2][FA_NT], const unsigned char* sp, int t0, auto tail_tag) {
         constexpr bool TAIL = decltype(tail_tag)::value;
-        bool moved = false;
-        float alpha[FA_NT];
+        auto score = [&](int nt, int e) {                       // e = 4a + j
+            const float sc = sacc[e >> 2][nt][e & 3];
+            return (TAIL && (t0 + 8 * g + e > L + qi[nt])) ? -INFINITY : sc;
+        };
+        // Common case first: no score of the block is more than 2^8 above its row's reference
+        // maximum.  Then the reference stays, nothing is rescaled, and the exact row maximum
+        // (a reduction across the four lanes that share a row) is not needed at all: every lane
+        // only compares its own eight scores with the row's threshold.
+        bool calm = false;
+        if (!TAIL) {
+            bool over = false;
+#pragma unroll
+            for (int nt = 0; nt < FA_NT; ++nt) {
+                const float lm = fmaxf(fmaxf(fmaxf(sacc[0][nt][0], sacc[0][nt][1]), fmaxf(sacc[0][nt][2], sacc[0][nt][3])),
+                                       fmaxf(fmaxf(sacc[1][nt][0], sacc[1][nt][1]), fmaxf(sacc[1][nt][2], sacc[1][nt][3])));
+                over |= !(lm <= thr[nt]);          // also true while the reference is still -inf
+            }
+            calm = !__any(over);
+        }
+        if (!calm) {
+            bool moved = false;
+            float alpha[FA_NT];
+#pragma unroll
+            for (int nt = 0; nt < FA_NT; ++nt) {
+                float mx = fmaxf(fmaxf(score(nt, 0), score(nt, 1)), score(nt, 2));
+                mx = fmaxf(fmaxf(mx, score(nt, 3)), score(nt, 4));
+                mx = fmaxf(fmaxf(mx, score(nt, 5)), fmaxf(score(nt, 6), score(nt, 7)));
+                mx = fa_row4_max(mx);                              // over the lanes c, c+16, c+32, c+48
+                mx *= scale2;
+                const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;  // see k_attn_mfma
+                const float m_new = up ? mx : m_run[nt];
+                alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - ((m_new == -INFINITY) ? 0.f : m_new)) : 1.0f;
+                moved |= up;
+                m_run[nt] = m_new;
+                // scores above this leave the calm path (raw score units; -inf while no score has
+                // been seen, so that the comparison above fails)
+                thr[nt] = (m_new == -INFINITY) ? -INFINITY : (m_new + FA_RESCALE_LOG2) * inv_scale2;
+            }
+            if (__any(moved)) {
+#pragma unroll
+                for (int nt = 0; nt < FA_NT; ++nt) {
+                    lacc[nt] *= alpha[nt];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] *= alpha[nt];
+                }
+            }
+        }
         bf16x8 pb[FA_NT];
 #pragma unroll
         for (int nt = 0; nt < FA_NT; ++nt) {
-            float sv[8];
+            const float m_safe = (m_run[nt] == -INFINITY) ? 0.f : m_run[nt];
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float sc = sacc[a][nt][j];
-                    if (TAIL && (t0 + 8 * g + 4 * a + j > L + qi[nt])) sc = -INFINITY;
-                    sv[4 * a + j] = sc;
-                }
-            float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
-            mx = fmaxf(fmaxf(mx, sv[3]), sv[4]);
-            mx = fmaxf(fmaxf(mx, sv[5]), fmaxf(sv[6], sv[7]));
-            mx = fa_row4_max(mx);                                  // over the lanes c, c+16, c+32, c+48
-            mx *= scale2;
-            const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;      // see k_attn_mfma
-            const float m_new = up ? mx : m_run[nt];
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - m_safe) : 1.0f;
-            moved |= up;
-            m_run[nt] = m_new;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                pb[nt][j] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(sv[j], scale2, -m_safe));
-        }
-        if (__any(moved)) {
-#pragma unroll
-            for (int nt = 0; nt < FA_NT; ++nt) {
-                lacc[nt] *= alpha[nt];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    oacc[mt][nt] *= alpha[nt];
-                }
-            }
+            for (int e = 0; e < 8; ++e)
+                pb[nt][e] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(score(nt, e), scale2, -m_safe));
         }
         // V fragments are read three tiles ahead of the MFMAs that use them
         bf16x8 vf[4];

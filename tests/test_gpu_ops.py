@@ -133,13 +133,19 @@ def test_gemm_f32_plain(host_model):
 # block attention
 # ----------------------------------------------------------------------------------------
 
-def _attention_case(model, shape, lens, rows, sample, seed, poison=False):
+def _attention_case(model, shape, lens, rows, sample, seed, poison=False, k_ramp=None):
     B = len(lens)
     cap = max(lens) + rows + 5
     kv = cs.KV(model, B, cap)
     ks, vs = {}, {}
     for b, L in enumerate(lens):
         kr, vr = synth.random_kv(shape, L + rows, seed, 0, b)
+        if k_ramp is not None:
+            # keys scaled along the sequence: the scores, and with them the running maximum of
+            # the online softmax, drift by many powers of two over the cache
+            t = np.arange(L + rows, dtype=np.float32) / max(L + rows - 1, 1)
+            scale = (k_ramp[0] + (k_ramp[1] - k_ramp[0]) * t)[None, :, None]
+            kr = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(kr) * scale)
         kv.load(0, b, 0, kr, vr)
         if poison and L + rows + 3 <= cap:
             # rows past the block are dead: whatever they hold must not matter
@@ -149,6 +155,10 @@ def _attention_case(model, shape, lens, rows, sample, seed, poison=False):
         ks[b], vs[b] = kr, vr
     rng = np.random.default_rng(seed)
     q = rng.standard_normal((B, rows, shape.n_heads, shape.head_dim)).astype(np.float32)
+    if k_ramp is not None:
+        # with scores this large the rounding of the queries to bfloat16 (what the tuned kernels
+        # take) moves the softmax weights by percents: give both sides the rounded queries
+        q = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(q))
     out = cs.cs_op_attention(model, kv, 0, torch.from_numpy(q).to(DEV)).cpu().numpy()
     G = shape.n_heads // shape.n_kv_heads
     worst = 0.0
@@ -184,6 +194,17 @@ def test_attention_k32_block(host_model):
     """k = 32: 132 query rows per KV head, three query groups per workgroup column."""
     worst = _attention_case(host_model, HOST, [3000, 2999, 64, 7], 33,
                             [(0, 0), (0, 3), (1, 12), (2, 31), (3, 8)], seed=14)
+    assert worst < 1e-2, worst
+
+
+@pytest.mark.parametrize("rows", [11, 33])
+@pytest.mark.parametrize("k_ramp", [(0.05, 6.0), (6.0, 0.05)])
+def test_attention_drifting_maximum(host_model, rows, k_ramp):
+    """Keys that grow (shrink) 120-fold along the cache: the row maxima rise by far more than
+    the 2^8 slack of the lazily updated reference again and again (or sit at the start, with
+    everything after it far below), in both tuned kernels."""
+    worst = _attention_case(host_model, HOST, [2500, 777, 40], rows,
+                            [(0, 0), (0, 21), (1, 6), (1, 31), (2, 15)], seed=16, k_ramp=k_ramp)
     assert worst < 1e-2, worst
 
 
