@@ -734,50 +734,46 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
 
 // out[r][h*HD + d] = sum_s 2^(m_s - M) O_s[d] / sum_s 2^(m_s - M) l_s  over the splits
 #define FA_MAX_SPLIT 64
+// Four output columns per lane (16-byte loads of the partials), HD/4 lanes per query row, so a
+// 128-thread workgroup merges 512/HD rows.  Every lane derives the split weights of its row
+// itself from the (max, sum) pairs (the HD/4 lanes of a row read the same words, which the
+// cache broadcasts): no LDS, no barrier, and the same summation order in every lane.
+#define FA_MERGE_THREADS 128
 template <typename OT>
-__global__ void k_attn_merge(const float* __restrict__ po, const float* __restrict__ pml, int rows,
-                             int H, int KVH, int HD, int nqg, int nsplit, OT* __restrict__ out,
-                             int tiled) {
-    const int n = blockIdx.x;                 // query row within the KV head: i*G + gq
+__global__ __launch_bounds__(FA_MERGE_THREADS) void k_attn_merge(const float* __restrict__ po,
+                                                                 const float* __restrict__ pml,
+                                                                 int rows, int H, int KVH, int HD,
+                                                                 int nqg, int nsplit,
+                                                                 OT* __restrict__ out, int tiled) {
+    const int lpr = HD >> 2;                  // lanes per query row
+    const int n = blockIdx.x * (FA_MERGE_THREADS / lpr) + (int)threadIdx.x / lpr;   // row within the KV head: i*G + gq
+    const int d = ((int)threadIdx.x % lpr) * 4;
     const int kvh = blockIdx.y, b = blockIdx.z;
     const int G = H / KVH;
+    if (n >= G * rows) return;
     const int i = n / G, gq = n % G;
     const int qg = n / FA_QROWS, nl = n % FA_QROWS;
     const int64_t item = ((int64_t)b * KVH + kvh) * nqg + qg;
-    const float* __restrict__ ml = pml + (item * nsplit * FA_QROWS + nl) * 2;
-    const float* __restrict__ o = po + (item * nsplit * FA_QROWS + nl) * HD;
-    __shared__ float wgt[FA_MAX_SPLIT];
-    __shared__ float lsum[FA_MAX_SPLIT];
-    // one split per thread: the (max, sum) pairs are fetched side by side, not one after another
-    if ((int)threadIdx.x < nsplit) {
-        wgt[threadIdx.x] = ml[(int64_t)threadIdx.x * FA_QROWS * 2];
-        lsum[threadIdx.x] = ml[(int64_t)threadIdx.x * FA_QROWS * 2 + 1];
-    }
-    __syncthreads();
+    const float2* __restrict__ ml = reinterpret_cast<const float2*>(pml) + (item * nsplit * FA_QROWS + nl);
+    const float* __restrict__ o = po + (item * nsplit * FA_QROWS + nl) * HD + d;
     float M = -INFINITY;
-    for (int w = 0; w < nsplit; ++w) M = fmaxf(M, wgt[w]);
+    for (int w = 0; w < nsplit; ++w) M = fmaxf(M, ml[(int64_t)w * FA_QROWS].x);
     float den = 0.f;
-    for (int w = 0; w < nsplit; ++w) {                      // same order in every thread
-        const float mw = wgt[w];
-        den += ((mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M)) * lsum[w];
+    f32x4 num = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int w = 0; w < nsplit; ++w) {                      // same order in every lane
+        const float2 p = ml[(int64_t)w * FA_QROWS];
+        const float wgt = (p.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(p.x - M);
+        den += wgt * p.y;
+        num += wgt * *reinterpret_cast<const f32x4*>(o + (int64_t)w * FA_QROWS * HD);
     }
-    __syncthreads();
-    if ((int)threadIdx.x < nsplit) {
-        const float mw = wgt[threadIdx.x];
-        wgt[threadIdx.x] = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-    }
-    __syncthreads();
-    const float den_s = den;
-    const float inv = 1.0f / den_s;
+    const float inv = 1.0f / den;
     const int r = b * rows + i;
-    for (int d = threadIdx.x; d < HD; d += blockDim.x) {
-        float num = 0.f;
-#pragma unroll 8
-        for (int w = 0; w < nsplit; ++w) num += wgt[w] * o[(int64_t)w * FA_QROWS * HD + d];
-        // tiled: the output projection runs the many-row GEMM, which reads fragment order
-        const int col = (kvh * G + gq) * HD + d;
-        cs_st(out, tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col, num * inv);
-    }
+    // tiled: the output projection runs the many-row GEMM, which reads fragment order
+    const int col = (kvh * G + gq) * HD + d;
+    const int64_t off = tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) cs_st(out, off + j, num[j] * inv);
 }
 
 int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
@@ -836,9 +832,9 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
                                                             H, KVH, kv->cap, Tw, nqg, nqgw, nsplit, ranges, po, pml);
         cs_prof_end(pa, s);
         CS_TRY(cs_launch_ok("k_attn_lds"));
-        dim3 mgrid(QR, KVH, B);
+        dim3 mgrid((unsigned)cs_ceil_div(QR, FA_MERGE_THREADS / (hd / 4)), KVH, B);
         const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
-        k_attn_merge<f16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
+        k_attn_merge<f16_t><<<mgrid, FA_MERGE_THREADS, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
                                                               (f16_t*)m->xn, tiled);
         cs_prof_end(pm, s);
         return cs_launch_ok("k_attn_merge");
@@ -868,9 +864,9 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
                                              kv->cap, Tw, nqg, nsplit, po, pml);
     cs_prof_end(pa, s);
     CS_TRY(cs_launch_ok("k_attn_mfma"));
-    dim3 mgrid(QR, KVH, B);
+    dim3 mgrid((unsigned)cs_ceil_div(QR, FA_MERGE_THREADS / (hd / 4)), KVH, B);
     const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
-    k_attn_merge<f16_t><<<mgrid, hd < 64 ? 64 : hd, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
+    k_attn_merge<f16_t><<<mgrid, FA_MERGE_THREADS, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
                                                           (f16_t*)m->xn, tiled);
     cs_prof_end(pm, s);
     return cs_launch_ok("k_attn_merge");
