@@ -614,13 +614,15 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
             sacc[1][nt] = z1;
         }
     };
-    // softmax update and O^T += V^T P^T for the block whose scores are in `sacc`
-    auto finish = [&](const f32x4 (&sacc)[2][FA_NT], const unsigned char* sp, int t0, auto tail_tag) {
+    // ---- the pieces of one block's softmax and PV ----
+    auto score_of = [&](const f32x4 (&sacc)[2][FA_NT], int nt, int e, int t0, auto tail_tag) {   // e = 4a + j
         constexpr bool TAIL = decltype(tail_tag)::value;
-        auto score = [&](int nt, int e) {                       // e = 4a + j
-            const float sc = sacc[e >> 2][nt][e & 3];
-            return (TAIL && (t0 + 8 * g + e > L + qi[nt])) ? -INFINITY : sc;
-        };
+        const float sc = sacc[e >> 2][nt][e & 3];
+        return (TAIL && (t0 + 8 * g + e > L + qi[nt])) ? -INFINITY : sc;
+    };
+    // reference maxima: leaves m_run (and O, rescaled if a reference moved) ready for `prob`
+    auto reference = [&](const f32x4 (&sacc)[2][FA_NT], int t0, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         // Common case first: no score of the block is more than 2^8 above its row's reference
         // maximum.  Then the reference stays, nothing is rescaled, and the exact row maximum
         // (a reduction across the four lanes that share a row) is not needed at all: every lane
@@ -636,42 +638,41 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
             }
             calm = !__any(over);
         }
-        if (!calm) {
-            bool moved = false;
-            float alpha[FA_NT];
-#pragma unroll
-            for (int nt = 0; nt < FA_NT; ++nt) {
-                float mx = fmaxf(fmaxf(score(nt, 0), score(nt, 1)), score(nt, 2));
-                mx = fmaxf(fmaxf(mx, score(nt, 3)), score(nt, 4));
-                mx = fmaxf(fmaxf(mx, score(nt, 5)), fmaxf(score(nt, 6), score(nt, 7)));
-                mx = fa_row4_max(mx);                              // over the lanes c, c+16, c+32, c+48
-                mx *= scale2;
-                const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;  // see k_attn_mfma
-                const float m_new = up ? mx : m_run[nt];
-                alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - ((m_new == -INFINITY) ? 0.f : m_new)) : 1.0f;
-                moved |= up;
-                m_run[nt] = m_new;
-                // scores above this leave the calm path (raw score units; -inf while no score has
-                // been seen, so that the comparison above fails)
-                thr[nt] = (m_new == -INFINITY) ? -INFINITY : (m_new + FA_RESCALE_LOG2) * inv_scale2;
-            }
-            if (__any(moved)) {
-#pragma unroll
-                for (int nt = 0; nt < FA_NT; ++nt) {
-                    lacc[nt] *= alpha[nt];
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] *= alpha[nt];
-                }
-            }
-        }
-        bf16x8 pb[FA_NT];
+        if (calm) return;
+        bool moved = false;
+        float alpha[FA_NT];
 #pragma unroll
         for (int nt = 0; nt < FA_NT; ++nt) {
-            const float m_safe = (m_run[nt] == -INFINITY) ? 0.f : m_run[nt];
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                pb[nt][e] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(score(nt, e), scale2, -m_safe));
+            float mx = fmaxf(fmaxf(score_of(sacc, nt, 0, t0, tail_tag), score_of(sacc, nt, 1, t0, tail_tag)),
+                             score_of(sacc, nt, 2, t0, tail_tag));
+            mx = fmaxf(fmaxf(mx, score_of(sacc, nt, 3, t0, tail_tag)), score_of(sacc, nt, 4, t0, tail_tag));
+            mx = fmaxf(fmaxf(mx, score_of(sacc, nt, 5, t0, tail_tag)),
+                       fmaxf(score_of(sacc, nt, 6, t0, tail_tag), score_of(sacc, nt, 7, t0, tail_tag)));
+            mx = fa_row4_max(mx);                              // over the lanes c, c+16, c+32, c+48
+            mx *= scale2;
+            const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;  // see k_attn_mfma
+            const float m_new = up ? mx : m_run[nt];
+            alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - ((m_new == -INFINITY) ? 0.f : m_new)) : 1.0f;
+            moved |= up;
+            m_run[nt] = m_new;
+            // scores above this leave the calm path (raw score units; -inf while no score has
+            // been seen, so that the comparison above fails)
+            thr[nt] = (m_new == -INFINITY) ? -INFINITY : (m_new + FA_RESCALE_LOG2) * inv_scale2;
         }
+        if (__any(moved)) {
+#pragma unroll
+            for (int nt = 0; nt < FA_NT; ++nt) {
+                lacc[nt] *= alpha[nt];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] *= alpha[nt];
+            }
+        }
+    };
+    auto prob = [&](const f32x4 (&sacc)[2][FA_NT], int nt, int e, int t0, auto tail_tag) {
+        const float m_safe = (m_run[nt] == -INFINITY) ? 0.f : m_run[nt];
+        return (bf16_t)__builtin_amdgcn_exp2f(fmaf(score_of(sacc, nt, e, t0, tail_tag), scale2, -m_safe));
+    };
+    auto pv = [&](const unsigned char* sp, const bf16x8 (&pb)[FA_NT]) {
         // V fragments are read three tiles ahead of the MFMAs that use them
         bf16x8 vf[4];
 #pragma unroll
@@ -688,23 +689,73 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
             lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[nt], lacc[nt], 0, 0, 0);
         }
     };
+    // softmax update and O^T += V^T P^T for the block whose scores are in `sacc`
+    auto finish = [&](const f32x4 (&sacc)[2][FA_NT], const unsigned char* sp, int t0, auto tail_tag) {
+        reference(sacc, t0, tail_tag);
+        bf16x8 pb[FA_NT];
+#pragma unroll
+        for (int nt = 0; nt < FA_NT; ++nt)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pb[nt][e] = prob(sacc, nt, e, t0, tail_tag);
+        pv(sp, pb);
+    };
     const std::integral_constant<bool, false> main_tag;
     const std::integral_constant<bool, true> tail_tag;
+    // The hot path (this block and the next lie inside the old cache): the score MFMAs of block
+    // i+1 and the exponentials of block i do not depend on each other, so they are issued
+    // interleaved, two MFMAs per pair of probabilities, and the matrix cores work through the
+    // vector part of the softmax.  The scheduling fences keep the compiler from regrouping each
+    // kind into a run of its own.
+    auto fused = [&](const f32x4 (&cur)[2][FA_NT], f32x4 (&nxt)[2][FA_NT], const unsigned char* sp_cur,
+                     const unsigned char* sp_nxt) {
+        auto k_frag = [&](int a, int s) {
+            return *reinterpret_cast<const bf16x8*>(sp_nxt + ((a * KS + s) * 64 + lane) * 16);
+        };
+        bf16x8 k0 = k_frag(0, 0), k1 = k_frag(1, 0);           // in flight during the reference check
+        reference(cur, 0, main_tag);
+        bf16x8 pb[FA_NT];
+        constexpr int PER = 8 / KS;                            // probabilities per (s, nt) step
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            bf16x8 n0 = k0, n1 = k1;
+            if (s + 1 < KS) {
+                n0 = k_frag(0, s + 1);
+                n1 = k_frag(1, s + 1);
+            }
+#pragma unroll
+            for (int nt = 0; nt < FA_NT; ++nt) {
+                const bf16x8 qf = s < QS_REG ? qreg[nt][s] : q_lds(nt, s);
+                const f32x4 zero4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+                nxt[0][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf, s == 0 ? zero4 : nxt[0][nt], 0, 0, 0);
+                nxt[1][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf, s == 0 ? zero4 : nxt[1][nt], 0, 0, 0);
+                const int e0 = (s * FA_NT + nt) * PER;
+#pragma unroll
+                for (int u = 0; u < PER; ++u)
+                    pb[(e0 + u) / 8][(e0 + u) % 8] = prob(cur, (e0 + u) / 8, (e0 + u) % 8, 0, main_tag);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            k0 = n0;
+            k1 = n1;
+        }
+        pv(sp_cur, pb);
+    };
 
     __syncthreads();                                       // matches the producer's first barrier
-    // Software pipeline: the score MFMAs of block i+1 are issued in the same iteration as the
-    // softmax arithmetic of block i (they do not depend on each other), which lets the matrix
-    // cores work while the vector ALU does the exponentials.
+    static_assert(8 % KS == 0, "whole probabilities per interleaving step");
     f32x4 sa[2][FA_NT], sb[2][FA_NT];
     load_q();
     if (live && nblocks > 0) scores(stage[0], sa);
     // one block: softmax + PV of block i (scores in `cur`) and the scores of block i+1 (into
-    // `nxt`).  The two teams do them in opposite order, so that the two waves sharing a SIMD
-    // want different units after every barrier.
+    // `nxt`).  Off the hot path the two teams do the pieces in opposite order, so that the two
+    // waves sharing a SIMD want different units after every barrier.
     auto block = [&](f32x4 (&cur)[2][FA_NT], f32x4 (&nxt)[2][FA_NT], int i) {
         if (!(live && i < nblocks)) return;
         const int t0 = t_begin + i * 32;
         const bool has_next = i + 1 < nblocks;
+        if (has_next && t0 + 64 <= L) {
+            fused(cur, nxt, stage[i % FA_STAGES], stage[(i + 1) % FA_STAGES]);
+            return;
+        }
         if (team == 0 && has_next) scores(stage[(i + 1) % FA_STAGES], nxt);
         if (t0 + 32 > L) finish(cur, stage[i % FA_STAGES], t0, tail_tag);
         else finish(cur, stage[i % FA_STAGES], t0, main_tag);
