@@ -281,7 +281,16 @@ def main():
     acc = st["out"][0].cpu().numpy()
     dl = st["out"][2].cpu().numpy()
 
-    # second pass of the same steps with HIP-event timing of the kernel classes
+    # the same steps once more, each bracketed by a synchronize of its own: median and minimum
+    per_step = []
+    for _ in range(args.steps):
+        t1 = time.perf_counter()
+        one_step(st, cs)
+        torch.cuda.synchronize()
+        per_step.append(time.perf_counter() - t1)
+    per_step.sort()
+
+    # third pass of the same steps with HIP-event timing of the kernel classes
     classes = ["scan", "gemm", "attn", "attn_merge", "argmax", "lm_head"]
     cs.cs_profile_enable(classes)
     cs.cs_profile_reset()
@@ -349,6 +358,7 @@ def main():
         "kernels": kern,
         "step": {"algorithmic_GB": step_bytes / 1e9,
                  "whole_step_hbm_frac": step_bytes / t_step / 1e9 / HBM_PEAK_GBS,
+                 "ms_per_step_median": per_step[len(per_step) // 2] * 1e3, "ms_per_step_min": per_step[0] * 1e3,
                  "ms_per_step_with_event_timing": t_step_prof * 1e3,
                  "draft_len": dl.tolist(), "accepted_len": acc.tolist(),
                  "emitted_tokens_per_s": float((acc + 1).sum()) / t_step},
