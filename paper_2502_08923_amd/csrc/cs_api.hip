@@ -521,12 +521,18 @@ static int forward_layers(cs_model* m, cs_kv* kv, int rows, hipStream_t s) {
     CS_TRY(cs_rope_table_launch(m, kv->d_len, B, rows, s));
     CS_TRY(cs_embed_launch(m, m->tok, R, s));
     int np_prev = 0, np = 1;
+    // narrow blocks: the attention kernel rotates q and k and appends k, v itself
+    const bool fuse_rope = cs_attention_fuses_rope(m, rows);
     for (int l = 0; l < c.n_layers; ++l) {
         const cs_layer_dev& L = m->layers[l];
         CS_TRY(cs_addnorm_launch(m, m->part, np_prev, L.norm1, m->xn, R, nqkv, s));
         CS_TRY(cs_gemm_launch(m, m->xn, L.wqkv, m->part, R, nqkv, d, CS_GEMM_STORE, 1, &np, s));
-        CS_TRY(cs_rope_append_launch(m, kv, l, m->part, np, rows, s));
-        CS_TRY(cs_attention_launch(m, kv, l, rows, len_ub, 1, s));
+        if (fuse_rope) {
+            CS_TRY(cs_attention_launch(m, kv, l, rows, len_ub, 1, m->part, np, s));
+        } else {
+            CS_TRY(cs_rope_append_launch(m, kv, l, m->part, np, rows, s));
+            CS_TRY(cs_attention_launch(m, kv, l, rows, len_ub, 1, nullptr, 0, s));
+        }
         CS_TRY(cs_gemm_launch(m, m->xn, L.wo, m->part, R, d, nq, CS_GEMM_STORE, 1, &np, s));
         CS_TRY(cs_addnorm_launch(m, m->part, np, L.norm2, m->xn, R, 2 * c.d_ff, s));
         if (m->fast) {
@@ -1051,7 +1057,7 @@ extern "C" int cs_op_attention(cs_model* m, cs_kv* kv, int32_t layer, const floa
     CS_TRY(kv_check_room(kv, rows));
     const int64_t n = (int64_t)kv->B * rows * m->cfg.n_heads * m->cfg.head_dim;
     CS_TRY(cs_convert_launch(q, CS_T_F32, m->q, m->fast ? CS_T_BF16 : CS_T_F32, n, s));
-    CS_TRY(cs_attention_launch(m, kv, layer, rows, kv_max_ub(kv), 0, s));
+    CS_TRY(cs_attention_launch(m, kv, layer, rows, kv_max_ub(kv), 0, nullptr, 0, s));
     return cs_convert_launch(m->xn, m->fast ? CS_T_F16 : CS_T_F32, out, CS_T_F32, n, s);
 }
 

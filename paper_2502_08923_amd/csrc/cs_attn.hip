@@ -138,6 +138,20 @@ struct fa_vbuf { bf16x8 v[HD / 16]; };
 // where item = (b*KVH + kvh)*nqg + qg, split = workgroup index along the token axis and max2
 // is the reference maximum in base-2 scaled units.  A split whose token range is empty
 // writes (max2 = -inf, 0, 0).
+// With `fr.qkv` set the kernel also does what k_rope_append does, for what it needs itself:
+// the query tile is built from the split-K partial tiles of the q/k/v projection (summed in the
+// same order, rotated, rounded), and the workgroup that owns the token range of a new row
+// writes that row's K and V into the cache before anybody in the workgroup reads it.  Nobody
+// else needs the row in this launch: a workgroup only reads cache rows of its own ranges.
+struct fa_fused_rope {
+    const float* qkv;        // [nparts][R][(H + 2*KVH) * HD] partial tiles, or NULL: q is given
+    int nparts;
+    int64_t part_stride;
+    const float2* rope;      // [R][HD/2] (cos, sin)
+    bf16_t* kc_w;            // this layer's caches, writable
+    bf16_t* vc_w;
+};
+
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                                                    const bf16_t* __restrict__ kc,
@@ -145,7 +159,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                                                    const int32_t* __restrict__ kv_len, int rows,
                                                    int H, int KVH, int64_t cap, int Tw, int nqg,
                                                    int nsplit, float* __restrict__ po,
-                                                   float* __restrict__ pml) {
+                                                   float* __restrict__ pml, fa_fused_rope fr) {
     constexpr int KS = HD / 32;      // MFMA k-steps over the head dimension
     constexpr int MT = HD / 16;      // 16-row tiles of O^T
     constexpr int OROW = HD + FA_OPAD;
@@ -176,16 +190,83 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
 
     // stage the query tile: global qrow n = qg*48 + local row  <->  block row n / G, head n % G
-    for (int idx = tid; idx < FA_QROWS * (HD / 8); idx += 256) {
-        const int row = idx / (HD / 8), seg = idx % (HD / 8);
-        const int n = qg * FA_QROWS + row;
-        bf16x8 v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
-        if (n < QR) {
-            const int i = n / G, gq = n % G;
-            v = *reinterpret_cast<const bf16x8*>(
-                q + (((int64_t)(b * rows + i)) * H + kvh * G + gq) * HD + seg * 8);
+    if (fr.qkv == nullptr) {
+        for (int idx = tid; idx < FA_QROWS * (HD / 8); idx += 256) {
+            const int row = idx / (HD / 8), seg = idx % (HD / 8);
+            const int n = qg * FA_QROWS + row;
+            bf16x8 v = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+            if (n < QR) {
+                const int i = n / G, gq = n % G;
+                v = *reinterpret_cast<const bf16x8*>(
+                    q + (((int64_t)(b * rows + i)) * H + kvh * G + gq) * HD + seg * 8);
+            }
+            *reinterpret_cast<bf16x8*>(smem + row * QROW + seg * 16) = v;
         }
-        *reinterpret_cast<bf16x8*>(smem + row * QROW + seg * 16) = v;
+    } else {
+        constexpr int HALF = HD / 2, SEGS = HALF / 8;        // 8-element segments per half head
+        const int nqkv = (H + 2 * KVH) * HD;
+        // elements j0..j0+7 and HALF+j0..HALF+j0+7 of one head of block row r: partial tiles
+        // summed in order, the pair (j, HALF + j) rotated by the row's angle j
+        auto head_pair = [&](int r, int head, int j0, bool rotate, bf16x8& lo, bf16x8& hi) {
+            const float* __restrict__ src = fr.qkv + (int64_t)r * nqkv + (int64_t)head * HD + j0;
+            float a[8], cc[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = cc[u] = 0.f;
+            for (int p = 0; p < fr.nparts; ++p) {
+                const float* __restrict__ sp = src + p * fr.part_stride;
+                const f32x4 a0 = *reinterpret_cast<const f32x4*>(sp), a1 = *reinterpret_cast<const f32x4*>(sp + 4);
+                const f32x4 c0 = *reinterpret_cast<const f32x4*>(sp + HALF), c1 = *reinterpret_cast<const f32x4*>(sp + HALF + 4);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a[u] += a0[u];
+                    a[4 + u] += a1[u];
+                    cc[u] += c0[u];
+                    cc[4 + u] += c1[u];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                float x = a[u], y = cc[u];
+                if (rotate) {
+                    const float2 cs = fr.rope[(int64_t)r * HALF + j0 + u];
+                    const float rx = x * cs.x - y * cs.y;
+                    const float ry = y * cs.x + x * cs.y;
+                    x = rx;
+                    y = ry;
+                }
+                lo[u] = (bf16_t)x;
+                hi[u] = (bf16_t)y;
+            }
+        };
+        // first the new rows whose position lies in one of this workgroup's four token ranges:
+        // their stores complete while the query tile is being built
+        bf16_t* __restrict__ Kw = fr.kc_w + ((int64_t)b * KVH + kvh) * cap * HD;
+        bf16_t* __restrict__ Vw = fr.vc_w + ((int64_t)b * KVH + kvh) * HD * cap;
+        if (qg == 0) {
+            for (int idx = tid; idx < rows * SEGS; idx += 256) {
+                const int i = idx / SEGS, sg = idx % SEGS;
+                const int pos = L + i;
+                if ((pos / Tw) >> 2 != split) continue;
+                bf16x8 lo, hi;
+                head_pair(b * rows + i, H + kvh, sg * 8, true, lo, hi);
+                *reinterpret_cast<bf16x8*>(Kw + (int64_t)pos * HD + sg * 8) = lo;
+                *reinterpret_cast<bf16x8*>(Kw + (int64_t)pos * HD + HALF + sg * 8) = hi;
+                head_pair(b * rows + i, H + KVH + kvh, sg * 8, false, lo, hi);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    Vw[(int64_t)(sg * 8 + u) * cap + pos] = lo[u];
+                    Vw[(int64_t)(HALF + sg * 8 + u) * cap + pos] = hi[u];
+                }
+            }
+        }
+        for (int idx = tid; idx < FA_QROWS * SEGS; idx += 256) {
+            const int row = idx / SEGS, sg = idx % SEGS;
+            const int n = qg * FA_QROWS + row;
+            bf16x8 lo = (bf16x8){0, 0, 0, 0, 0, 0, 0, 0}, hi = lo;
+            if (n < QR) head_pair(b * rows + n / G, kvh * G + n % G, sg * 8, true, lo, hi);
+            *reinterpret_cast<bf16x8*>(smem + row * QROW + sg * 16) = lo;
+            *reinterpret_cast<bf16x8*>(smem + row * QROW + HD + sg * 16) = hi;
+        }
     }
     int qi[FA_NT];               // block row index of the lane's query row (for the causal mask)
 #pragma unroll
@@ -827,8 +908,12 @@ __global__ __launch_bounds__(FA_MERGE_THREADS) void k_attn_merge(const float* __
     for (int j = 0; j < 4; ++j) cs_st(out, off + j, num[j] * inv);
 }
 
+bool cs_attention_fuses_rope(const cs_model* m, int rows) {
+    return m->fast && (m->cfg.n_heads / m->cfg.n_kv_heads) * rows <= FA_QROWS;
+}
+
 int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
-                        int for_o_proj, hipStream_t s) {
+                        int for_o_proj, const float* qkv_part, int qkv_nparts, hipStream_t s) {
     const cs_model_cfg& c = m->cfg;
     const int B = kv->B, H = c.n_heads, KVH = c.n_kv_heads, hd = c.head_dim;
     const int64_t per_layer = (int64_t)B * KVH * kv->cap * hd;
@@ -855,6 +940,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const int tiled = for_o_proj && cs_gemm_x_tiled(B * rows, c.d_model) ? 1 : 0;
     const bf16_t* kc = (const bf16_t*)kv->k + layer * per_layer;
     const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
+    CS_REQUIRE(!qkv_part || nqg == 1, CS_E_STATE, "fused rotary embedding needs a narrow block");
     int nsplit;
     if (nqg > 1) {
         // wide block: consumers share the K/V stream of one producer wave through LDS
@@ -907,12 +993,21 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     float* pml = m->attn_part + items * FA_QROWS * hd;
     dim3 grid(nsplit * nqg, KVH, B);
     const int pa = cs_prof_begin(CS_PROF_ATTN, s);
+    fa_fused_rope fr = {nullptr, 0, 0, nullptr, nullptr, nullptr};
+    if (qkv_part) {
+        fr.qkv = qkv_part;
+        fr.nparts = qkv_nparts;
+        fr.part_stride = (int64_t)B * rows * (H + 2 * KVH) * hd;
+        fr.rope = m->rope;
+        fr.kc_w = (bf16_t*)kv->k + layer * per_layer;
+        fr.vc_w = (bf16_t*)kv->v + layer * per_layer;
+    }
     if (hd == 128)
         k_attn_mfma<128><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
-                                              kv->cap, Tw, nqg, nsplit, po, pml);
+                                              kv->cap, Tw, nqg, nsplit, po, pml, fr);
     else
         k_attn_mfma<64><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
-                                             kv->cap, Tw, nqg, nsplit, po, pml);
+                                             kv->cap, Tw, nqg, nsplit, po, pml, fr);
     cs_prof_end(pa, s);
     CS_TRY(cs_launch_ok("k_attn_mfma"));
     dim3 mgrid((unsigned)cs_ceil_div(QR, FA_MERGE_THREADS / (hd / 4)), KVH, B);

@@ -175,8 +175,12 @@ int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int 
 
 // attention: reads m->q, writes m->xn (GEMM-input type) as [R][H*hd], or, if for_o_proj, in
 // the layout the output projection's GEMM reads
+// If qkv_part is not NULL (allowed when cs_attention_fuses_rope(m, rows)), the kernel takes the
+// q/k/v projection's partial tiles instead of m->q and does the rotary embedding and the cache
+// append itself (no cs_rope_append_launch before it).
+bool cs_attention_fuses_rope(const cs_model* m, int rows);
 int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64_t len_ub,
-                        int for_o_proj, hipStream_t s);
+                        int for_o_proj, const float* qkv_part, int qkv_nparts, hipStream_t s);
 
 // conversion helpers
 // element type codes for cs_convert_launch
