@@ -27,7 +27,7 @@ EXPORTS = [
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
     "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_prefill_batch", "cs_decode_batch", "cs_index_create", "cs_index_destroy",
     "cs_index_reset", "cs_index_find_match_batch_dev", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
-    "cs_set_plain_kernels", "cs_kv_set_len_dev", "cs_profile_enable", "cs_profile_reset",
+    "cs_set_plain_kernels", "cs_set_prompt_block_rows", "cs_kv_set_len_dev", "cs_profile_enable", "cs_profile_reset",
     "cs_profile_read",
 ]
 
@@ -123,6 +123,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_profile_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.cs_set_plain_kernels.argtypes = [i32]
     lib.cs_set_plain_kernels.restype = None
+    lib.cs_set_prompt_block_rows.argtypes = [i32]
+    lib.cs_set_prompt_block_rows.restype = None
     for name in EXPORTS:
         getattr(lib, name)
     if path is None:
@@ -259,7 +261,7 @@ class Model:
     them into library-owned memory) and released."""
 
     def __init__(self, weights: dict, max_batch: int, max_k: int, plain: bool = False,
-                 device="cuda:0"):
+                 device="cuda:0", prompt_block_rows: int = 0):
         lib = load_library()
         sh = weights["shape"]
         self.shape = sh
@@ -286,11 +288,13 @@ class Model:
                        up(weights["final_norm"], False), layers)
         h = C.c_void_p()
         lib.cs_set_plain_kernels(1 if plain else 0)
+        lib.cs_set_prompt_block_rows(prompt_block_rows)
         try:
             torch.cuda.synchronize(dev)
             _check(lib.cs_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
         finally:
             lib.cs_set_plain_kernels(0)
+            lib.cs_set_prompt_block_rows(0)
         self.handle = h
         self.device = dev
         del keep

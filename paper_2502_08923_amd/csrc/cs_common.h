@@ -77,7 +77,7 @@ struct cs_model {
     int fast;           // 1: the MFMA kernels are in use (GEMM inputs are fp16, q is bf16)
     int R_max;          // max_batch * (max_k + 1)
     int rows_max;       // max_k + 1
-    int prefill_rows;   // rows of one prompt block (single stream): max(rows_max, 512)
+    int prefill_rows;   // rows of one prompt block (single stream): max(rows_max, cs_set_prompt_block_rows)
     size_t esz;         // bytes per weight / cache element
     size_t asz;         // bytes per activation element handed to a GEMM
     void* embed;

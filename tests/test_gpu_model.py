@@ -142,7 +142,7 @@ def test_long_prompt_goes_through_512_row_blocks(shape):
     attends to the rows before it): the cache rows and the logits of the following
     verify step match the oracle, which ingests the same prompt 32 rows at a time."""
     w = synth.model_weights(shape, 2024, threads=4)
-    model = cs.Model(w, max_batch=1, max_k=10)
+    model = cs.Model(w, max_batch=1, max_k=10, prompt_block_rows=512)
     g = synth.planted_history(23, 700, shape.vocab, (16, 32), density=0.2, end="span")
     prompt = g["tokens"].tolist()
     _, _, draft = orc.find_match_np(prompt, 3, 10)
@@ -152,6 +152,27 @@ def test_long_prompt_goes_through_512_row_blocks(shape):
         k_rows, v_rows = kv.read(layer, 0, 0, 699)
         assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :699]).max() < tol * 4
         assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :699]).max() < tol * 4
+    kv.destroy()
+    model.destroy()
+
+
+@pytest.mark.parametrize("shape", [MINI128, SMALLF32])
+def test_long_prompt_goes_through_default_blocks(shape):
+    """A 2300-token prompt with the default prompt block (2048 rows, then a ragged block of 251
+    that attends to the rows before it): cache rows and the logits of the following verify step
+    match the oracle."""
+    w = synth.model_weights(shape, 2025, threads=4)
+    model = cs.Model(w, max_batch=1, max_k=10)
+    n = 2300
+    g = synth.planted_history(29, n, shape.vocab, (16, 32), density=0.2, end="span")
+    prompt = g["tokens"].tolist()
+    _, _, draft = orc.find_match_np(prompt, 3, 10)
+    kv, okv, err = _verify_case(w, model, prompt, draft, 10, cap=2432)
+    tol = 2e-2 if shape.dtype == "bf16" else 1e-4
+    for layer in range(shape.n_layers):
+        k_rows, v_rows = kv.read(layer, 0, 0, n - 1)
+        assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :n - 1]).max() < tol * 4
+        assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :n - 1]).max() < tol * 4
     kv.destroy()
     model.destroy()
 
