@@ -535,19 +535,25 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int range = (slot / nqgw) * 8 + xcd;
     if (range >= ranges) return;                        // whole workgroup, before any barrier
-    const int qgw = slot % nqgw;                        // which group of FA_QG query groups
+    // which group of FA_QG query groups: the last rows of a block see the most tokens (see n_lim
+    // below), so they are dispatched first and the short ones fill the tail of the launch
+    const int qgw = nqgw - 1 - slot % nqgw;
     const int split = (range % nsp) * FA_TEAMS + team;  // each team owns one token range
     const int kvh = (range / nsp) % KVH, b = range / (nsp * KVH);
     const int G = H / KVH;
     const int QR = G * rows;
     const int L = kv_len[b];
     const int n_tok = L + rows;
-    const int t_begin = min(split * Tw, n_tok);
-    const int t_end = min(n_tok, t_begin + Tw);
+    // Causality: block row i sees the tokens up to L + i, so nothing beyond the last row of this
+    // workgroup's query groups is walked (long prompt blocks: the upper triangle of the block).
+    const int last_row = min(rows - 1, ((qgw + 1) * FA_QG * FA_QROWS - 1) / G);
+    const int n_lim = L + last_row + 1;
+    const int t_begin = min(split * Tw, n_lim);
+    const int t_end = min(n_lim, t_begin + Tw);
     const int nblocks = (t_end - t_begin + 31) / 32;
     // both teams pass the same number of barriers: the longer range of the two
-    const int t_begin0 = min((split - team) * Tw, n_tok);
-    const int nblocks_wg = (min(n_tok, t_begin0 + Tw) - t_begin0 + 31) / 32;
+    const int t_begin0 = min((split - team) * Tw, n_lim);
+    const int nblocks_wg = (min(n_lim, t_begin0 + Tw) - t_begin0 + 31) / 32;
     const bf16_t* __restrict__ K = kc + ((int64_t)b * KVH + kvh) * cap * HD;
     const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
 
