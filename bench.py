@@ -11,6 +11,7 @@ re-contains document spans (18432 tokens; the last one is pending, 18431 are cac
 gamma = 3, k = 10.  Weights, KV contents and token histories are seeded synthetic data.
 
 Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
+`--prefill N` times prompt ingestion instead (a separate line, not the headline metric).
 """
 from __future__ import annotations
 
@@ -211,6 +212,63 @@ def cpu_baseline(st, args):
                       f"scaled to {sh.n_layers} layers x {st['B']} streams"}
 
 
+def bench_prefill(args):
+    """Prompt ingestion alone (`--prefill N`): one stream, an N-token prompt through cs_prefill,
+    `steps` times into the same cache.  The projections of a prompt block are compute-bound, so
+    the roofline object is the MFMA one (all projection launches, HIP events)."""
+    import torch
+    import synth
+    from paper_2502_08923_amd import binding as cs
+    shape = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B}[args.shape]
+    if args.layers:
+        shape = shape.with_layers(args.layers)
+    n = args.prefill
+    model = cs.Model(synth.model_weights(shape, synth.seed_for(4), threads=16), max_batch=1, max_k=args.k)
+    kv = cs.KV(model, 1, n + 64)
+    prompt = synth.history_cfg4(0, vocab=shape.vocab, doc=args.doc, hist=max(n - args.doc, 0) + 64,
+                                k=args.k)["tokens"][:n].tolist()
+    for _ in range(max(args.warmup, 1)):
+        cs.cs_prefill(model, kv, 0, prompt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        cs.cs_prefill(model, kv, 0, prompt)
+    torch.cuda.synchronize()
+    t = (time.perf_counter() - t0) / args.steps
+    classes = ["gemm", "attn", "attn_merge"]
+    cs.cs_profile_enable(classes)
+    cs.cs_profile_reset()
+    for _ in range(args.steps):
+        cs.cs_prefill(model, kv, 0, prompt)
+    torch.cuda.synchronize()
+    prof = {c: cs.cs_profile_read(c) for c in classes}
+    cs.cs_profile_enable([])
+    d, hd, H, KVH, F = shape.d_model, shape.head_dim, shape.n_heads, shape.n_kv_heads, shape.d_ff
+    rows = n - 1                                          # the last prompt token stays pending
+    gemm_flops = 2.0 * rows * shape.n_layers * ((H + 2 * KVH) * hd * d + d * H * hd + 2 * F * d + d * F)
+    attn_flops = 4.0 * hd * H * shape.n_layers * rows * (rows + 1) / 2      # causal QK^T and PV
+    gemm_s = prof["gemm"][0] / args.steps * 1e-3
+    attn_s = prof["attn"][0] / args.steps * 1e-3
+    out = {
+        "metric": f"prompt tokens/sec/GPU ({args.shape.upper()} shape, {n}-token prompt)",
+        "value": rows / t, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1),
+        "ms_per_step": t * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"llama-{args.shape} shape x{shape.n_layers} layers, one stream, {n}-token prompt "
+                               f"ingested by cs_prefill (one whole prompt per step)", "prompt": n},
+        "roofline": {"bound": "mfma", "kernel": "k_gemm_dma (all projections of the prompt blocks)",
+                     "achieved": gemm_flops / gemm_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_flops / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "flops_per_step": gemm_flops, "ms_per_step": gemm_s * 1e3},
+        "kernels": {"attention": {"bound": "mfma", "ms_per_step": attn_s * 1e3,
+                                  "achieved_TFLOPs": attn_flops / attn_s / 1e12,
+                                  "frac": attn_flops / attn_s / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+                    "attn_merge": {"ms_per_step": prof["attn_merge"][0] / args.steps}},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def measured_traffic(kernel: str):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE +
     WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB device copy), or None.
@@ -241,6 +299,8 @@ def main():
     ap.add_argument("--cpu-streams", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-scan", action="store_true")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="time the ingestion of an N-token prompt (one stream) instead of the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="only run a 1 GiB device copy (yardstick for the HBM traffic counters)")
     args = ap.parse_args()
@@ -264,6 +324,10 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
         print(json.dumps({"calib_copy_bytes_read": n * 4, "calib_copy_bytes_written": n * 4}))
+        return
+
+    if args.prefill:
+        bench_prefill(args)
         return
 
     st = build_workload(args)
