@@ -161,6 +161,79 @@ __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qk
     }
 }
 
+// The same for blocks of many rows (wide verify blocks, prompt blocks), bf16 cache and queries:
+// a workgroup takes RA_ROWS consecutive block rows of one head, every thread four adjacent
+// elements of both rotary halves (16-byte loads of the partial tiles, 8-byte stores), and the V
+// rows, whose cache keeps the token index contiguous, go through an LDS tile so that the rows
+// of a workgroup are written as runs of consecutive tokens instead of one element per line.
+#define RA_ROWS 32
+#define RA_THREADS 256
+__global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
+    const float* __restrict__ qkv, int nparts, int64_t part_stride, const float2* __restrict__ rope,
+    const int32_t* __restrict__ kv_len, int rows, int R, int H, int KVH, int hd, int64_t cap,
+    bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, bf16_t* __restrict__ q) {
+    __shared__ bf16_t vt[256][RA_ROWS + 2];            // [d][row of the workgroup], hd <= 256
+    __shared__ int64_t voff[RA_ROWS];                  // cache offset of each row's token (v heads)
+    const int head = blockIdx.x;                       // q heads, then k heads, then v heads
+    const int rr = threadIdx.x >> 3, t8 = threadIdx.x & 7;
+    const int r = blockIdx.y * RA_ROWS + rr;
+    const int half = hd / 2;
+    const int nq = (H + 2 * KVH) * hd;
+    const bool live = r < R;
+    const int b = live ? r / rows : 0, i = live ? r % rows : 0;
+    const int64_t pos = live ? (int64_t)kv_len[b] + i : 0;
+    const bool is_v = head >= H + KVH;
+    if (is_v && t8 == 0) voff[rr] = live ? ((int64_t)b * KVH + (head - H - KVH)) * hd * cap + pos : -1;
+    if (live) {
+        for (int j = t8 * 4; j < half; j += 32) {
+            const int64_t i0 = (int64_t)r * nq + (int64_t)head * hd + j;
+            f32x4 a = (f32x4){0.f, 0.f, 0.f, 0.f}, c = a;
+            for (int p = 0; p < nparts; ++p) {         // in order: the same sums as the other kernels
+                a += *reinterpret_cast<const f32x4*>(qkv + p * part_stride + i0);
+                c += *reinterpret_cast<const f32x4*>(qkv + p * part_stride + i0 + half);
+            }
+            if (!is_v) {
+                const f32x4 cs0 = *reinterpret_cast<const f32x4*>(rope + (int64_t)r * half + j);
+                const f32x4 cs1 = *reinterpret_cast<const f32x4*>(rope + (int64_t)r * half + j + 2);
+                const f32x4 co = (f32x4){cs0[0], cs0[2], cs1[0], cs1[2]};
+                const f32x4 si = (f32x4){cs0[1], cs0[3], cs1[1], cs1[3]};
+                const f32x4 ra = a * co - c * si;
+                const f32x4 rc = c * co + a * si;
+                a = ra;
+                c = rc;
+            }
+            bf16x4 oa, oc;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                oa[u] = (bf16_t)a[u];
+                oc[u] = (bf16_t)c[u];
+            }
+            if (head < H) {
+                bf16_t* dst = q + ((int64_t)r * H + head) * hd + j;
+                *reinterpret_cast<bf16x4*>(dst) = oa;
+                *reinterpret_cast<bf16x4*>(dst + half) = oc;
+            } else if (!is_v) {
+                bf16_t* dst = kc + (((int64_t)b * KVH + (head - H)) * cap + pos) * hd + j;
+                *reinterpret_cast<bf16x4*>(dst) = oa;
+                *reinterpret_cast<bf16x4*>(dst + half) = oc;
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    vt[j + u][rr] = oa[u];
+                    vt[j + half + u][rr] = oc[u];
+                }
+            }
+        }
+    }
+    if (!is_v) return;                                 // uniform over the workgroup
+    __syncthreads();
+    // lane -> token of the workgroup, wave and step -> d: a wave writes 2 runs of 32 tokens
+    const int tok = threadIdx.x & (RA_ROWS - 1);
+    const int64_t off = voff[tok];
+    if (off < 0) return;
+    for (int d = threadIdx.x / RA_ROWS; d < hd; d += RA_THREADS / RA_ROWS) vc[off + (int64_t)d * cap] = vt[d][tok];
+}
+
 // -------------------------------------------------------------------------------------
 // SwiGLU on the interleaved gate/up projection (plain path): row layout of gu matches the
 // packed weight: index (f/16)*32 + 16*u + f%16.
@@ -367,7 +440,13 @@ int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* 
     if (c.dtype == CS_BF16) {
         bf16_t* kc = (bf16_t*)kv->k + layer * per_layer;
         bf16_t* vc = (bf16_t*)kv->v + layer * per_layer;
-        if (m->fast)
+        // many rows: the tiled version (needs 16-byte aligned quads: head_dim % 8 == 0)
+        if (m->fast && R >= 4 * RA_ROWS && c.head_dim % 8 == 0 && c.head_dim <= 256) {
+            dim3 grid(c.n_heads + 2 * c.n_kv_heads, (unsigned)cs_ceil_div(R, RA_ROWS));
+            k_rope_append_rows<<<grid, RA_THREADS, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows, R, c.n_heads,
+                                                          c.n_kv_heads, c.head_dim, kv->cap, kc, vc,
+                                                          (bf16_t*)m->q);
+        } else if (m->fast)
             k_rope_append<bf16_t, bf16_t><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                            c.n_heads, c.n_kv_heads, c.head_dim,
                                                            kv->cap, kc, vc, (bf16_t*)m->q);
