@@ -326,18 +326,23 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
     const f16_t* xbase = X + (int64_t)(k_begin / TD_KC) * 512;
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
-    // request chunk c into stage sb
-    auto issue = [&](int sb, int c) {
+    // request number `idx` (0, 1: W blocks; 2..: X blocks) of chunk c into stage sb
+    constexpr int NL = 2 + XLD;                       // requests per wave and chunk (the last may be void)
+    auto issue_one = [&](int sb, int c, int idx) {
         const unsigned dst = lds0 + sb * STAGE + wave * 1024;
-        const f16_t* wc = wbase + (int64_t)(c >> 2) * chunk_stride + (c & 3) * 512;
-        const f16_t* xc = xbase + (int64_t)c * 512;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) cs_load_to_lds(lane16, wc + (int64_t)tw[i] * 2048, dst + 8 * i * 1024);
-#pragma unroll
-        for (int i = 0; i < XLD; ++i) {
+        if (idx < 2) {
+            const f16_t* wc = wbase + (int64_t)(c >> 2) * chunk_stride + (c & 3) * 512;
+            cs_load_to_lds(lane16, wc + (int64_t)tw[idx] * 2048, dst + 8 * idx * 1024);
+        } else {
+            const int i = idx - 2;
+            const f16_t* xc = xbase + (int64_t)c * 512;
             if (8 * i + 7 < XT || wave + 8 * i < XT)
                 cs_load_to_lds(lane16, xc + tx[i] * x_pitch, dst + (16 + 8 * i) * 1024);
         }
+    };
+    auto issue = [&](int sb, int c) {
+#pragma unroll
+        for (int idx = 0; idx < NL; ++idx) issue_one(sb, c, idx);
     };
     const unsigned char* a_base = lds + wn * 4 * 1024 + lane * 16;
     const unsigned char* b_base = lds + (16 + wm * NT) * 1024 + lane * 16;
@@ -373,10 +378,20 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
             // are read at the end of this iteration; only chunk c+2 may still be in flight
             if (TAIL && u >= 2) TD_SYNC(0);
             else TD_SYNC(LDMIN);
-            if (!TAIL || u == 0) issue((u + 3) & 3, c0 + u + 3);  // stage of chunk c-1, free since the barrier
+            // chunk c+3 goes to the stage of chunk c-1, free since the barrier.  Its requests are
+            // spread over the iteration, one after every few MFMA groups: a wave issues in order,
+            // so a burst of requests that the memory pipeline takes one at a time would hold
+            // back the MFMAs behind it, in all eight waves at once right after the barrier.
+            const bool req = !TAIL || u == 0;
             const bool more = !TAIL || u < 3;
+            int next_req = 0;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
+                if (req && next_req < NL && nt == (next_req * NT) / NL) {
+                    issue_one((u + 3) & 3, c0 + u + 3, next_req);
+                    ++next_req;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 const int q = u * NT + nt;                        // position in the B fragment stream
                 if (nt + 3 < NT) bq[(q + 3) & 3] = b_frag(u, nt + 3);              // three tiles ahead
                 else if (more) bq[(q + 3) & 3] = b_frag((u + 1) & 3, nt + 3 - NT);
