@@ -362,7 +362,7 @@ void cs_set_plain_kernels(int32_t on);
 
 /* Rows of one prompt block for the following cs_model_create calls (the workspace of a model is
  * sized for it): cs_prefill ingests a prompt `rows` tokens at a time, cs_prefill_batch gives each
- * stream its share of them.  0 = the default (2048); other values are clamped to 16..8192.
+ * stream its share of them.  0 = the default (4096); other values are clamped to 16..8192.
  * A model whose max_k + 1 is larger uses that.  Results do not depend on it beyond rounding. */
 void cs_set_prompt_block_rows(int32_t rows);
 

@@ -870,6 +870,302 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     }
 }
 
+// -------------------------------------------------------------------------------------
+// kernel for prompt blocks (hundreds of rows per stream and more)
+//
+// There the pass is bound by the matrix cores, not by HBM: a block of 2048 rows has 8192 query
+// rows per KV head, and every cached token is used by all of them.  So the token axis is not
+// split at all: a workgroup of eight waves owns 384 query rows (48 each, the same register tile
+// as above), walks the tokens its rows can see once, and writes the normalised result itself
+// (no partial results, no merge).  All eight waves multiply; nobody is set aside to load: each
+// wave requests its share (1 KB fragment blocks) of every 32-token block with direct-to-LDS loads
+// into a ring of six stages, so four blocks are in flight while one is multiplied, and the
+// loads cost no registers.  The loads and the waits on them are inline assembly with exact
+// counts, as in the many-row GEMM: after the query fragments have arrived the kernel issues
+// no other vector memory load until its final stores.
+// Workgroups of one KV head get ids 8 apart (one XCD, one L2); the last rows of a block see the
+// most tokens and are dispatched first.
+// -------------------------------------------------------------------------------------
+#define PF_WAVES 8
+#define PF_THREADS (64 * PF_WAVES)
+#define PF_STAGES 6
+#define PF_NT 2             // 16-row query tiles per wave
+
+template <int HD, int NT, typename OT>
+__global__ __launch_bounds__(PF_THREADS) void k_attn_prefill(const bf16_t* __restrict__ q,
+                                                             const bf16_t* __restrict__ kc,
+                                                             const bf16_t* __restrict__ vc,
+                                                             const int32_t* __restrict__ kv_len,
+                                                             int rows, int H, int KVH, int64_t cap,
+                                                             int nqt, int ranges, int g_shift,
+                                                             OT* __restrict__ out, int tiled) {
+    constexpr int KS = HD / 32, MT = HD / 16;
+    constexpr int WQROWS = 16 * NT;                     // query rows per wave
+    constexpr int PF_QROWS = PF_WAVES * WQROWS;         // ... per workgroup
+    constexpr int K_BYTES = 2 * KS * 1024, V_BYTES = MT * 1024;
+    constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
+    constexpr int NLOAD = 2 * KS + MT;                  // 1 KB requests per 32-token block
+    constexpr int LD = NLOAD / PF_WAVES;                // ... per wave
+    static_assert(NLOAD % PF_WAVES == 0, "every wave issues the same number of requests");
+    __shared__ __attribute__((aligned(16))) unsigned char stage[PF_STAGES][STAGE_BYTES];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // uniform copy for the request addresses
+    const int c = lane & 15, g = lane >> 4;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int range = (slot / nqt) * 8 + xcd;           // (stream, KV head)
+    if (range >= ranges) return;                        // whole workgroup, before any barrier
+    const int qt = nqt - 1 - slot % nqt;                // heaviest first
+    const int kvh = range % KVH, b = range / KVH;
+    const int G = H / KVH;
+    const int QR = G * rows;
+    const int L = kv_len[b];
+    const int n_tok = L + rows;
+    // causality: nothing beyond the last row of this workgroup is walked
+    const int last_row = min(rows - 1, ((qt + 1) * PF_QROWS - 1) / G);
+    const int n_lim = L + last_row + 1;
+    const int nblocks = (n_lim + 31) / 32;              // >= 1
+    const bf16_t* __restrict__ K = kc + ((int64_t)b * KVH + kvh) * cap * HD;
+    const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
+
+    // query fragments: straight from memory into registers, once
+    // query row nt*16 + c of this wave is row n0 + nt*16 of the KV head: block row n >> g_shift,
+    // head n & (G - 1) of the group (G is a power of two here)
+    const int n0 = qt * PF_QROWS + wave * WQROWS + c;
+    bf16x8 qreg[NT][KS];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = n0 + nt * 16;
+        const bf16_t* qp = q + (((int64_t)(b * rows + (n < QR ? n >> g_shift : 0))) * H + kvh * G + (n < QR ? n & (G - 1) : 0)) * HD + g * 8;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            qreg[nt][s] = n < QR ? *reinterpret_cast<const bf16x8*>(qp + s * 32) : (bf16x8){0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    // they must have arrived before the first counted request below: the compiler waits for a
+    // load where its result is first used, which is here
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qreg[nt][s]));
+
+    // this wave's requests of a block: fragment block id = wave + 8*u; ids below 2*KS are K
+    // fragments (a = id / KS, s = id % KS), the others V fragments (mt = id - 2*KS).  Lane
+    // (c, g) of a K fragment holds token ktok0 + 4a, elements s*32 + g*8 ..; of a V fragment
+    // feature mt*16 + c, tokens 8g ...
+    const int ktok0 = 8 * (c >> 2) + (c & 3);
+    unsigned voff[LD];
+    const bf16_t* sbase[LD];
+    int tstep[LD];                                      // elements the uniform base advances per token
+#pragma unroll
+    for (int u = 0; u < LD; ++u) {
+        const int id = wave_s + PF_WAVES * u;
+        if (id < 2 * KS) {
+            voff[u] = (unsigned)(((ktok0 + 4 * (id / KS)) * HD + g * 8) * 2);
+            sbase[u] = K + (id % KS) * 32;
+            tstep[u] = HD;
+        } else {
+            voff[u] = (unsigned)((((int64_t)((id - 2 * KS) * 16 + c)) * cap + 8 * g) * 2);
+            sbase[u] = V;
+            tstep[u] = 1;
+        }
+    }
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)&stage[0][0];
+    // request block blk (clamped: a surplus request re-reads the last block into a stage nobody reads)
+    auto issue = [&](int blk, int st) {
+        const int t0 = (blk < nblocks ? blk : nblocks - 1) * 32;
+#pragma unroll
+        for (int u = 0; u < LD; ++u)
+            cs_load_to_lds(voff[u], sbase[u] + (int64_t)t0 * tstep[u], lds0 + st * STAGE_BYTES + (wave_s + PF_WAVES * u) * 1024);
+    };
+    // at most `n` of this wave's requests still in flight, then meet the other waves
+#define PF_SYNC(n) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(n) : "memory")
+
+    f32x4 oacc[MT][NT], lacc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        lacc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    float m_run[NT], thr[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) m_run[nt] = thr[nt] = -INFINITY;
+    const float scale2 = 1.4426950408889634f / sqrtf((float)HD);
+    const float inv_scale2 = sqrtf((float)HD) / 1.4426950408889634f;
+    const bf16_t one = (bf16_t)1.0f;
+    const bf16x8 ones = (bf16x8){one, one, one, one, one, one, one, one};
+
+    // ---- the pieces of one block (the same arithmetic as in k_attn_lds) ----
+    auto scores = [&](const unsigned char* sp, f32x4 (&sacc)[2][NT]) {
+        auto k_frag = [&](int a, int s) {
+            return *reinterpret_cast<const bf16x8*>(sp + ((a * KS + s) * 64 + lane) * 16);
+        };
+        bf16x8 k0 = k_frag(0, 0), k1 = k_frag(1, 0);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            bf16x8 n0 = k0, n1 = k1;
+            if (s + 1 < KS) {
+                n0 = k_frag(0, s + 1);
+                n1 = k_frag(1, s + 1);
+            }
+            const f32x4 zero4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                sacc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qreg[nt][s], s == 0 ? zero4 : sacc[0][nt], 0, 0, 0);
+                sacc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qreg[nt][s], s == 0 ? zero4 : sacc[1][nt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            k0 = n0;
+            k1 = n1;
+        }
+    };
+    auto score_of = [&](const f32x4 (&sacc)[2][NT], int nt, int e, int t0, auto tail_tag) {   // e = 4a + j
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const float sc = sacc[e >> 2][nt][e & 3];
+        return (TAIL && (t0 + 8 * g + e > L + ((n0 + nt * 16) >> g_shift))) ? -INFINITY : sc;
+    };
+    auto reference = [&](const f32x4 (&sacc)[2][NT], int t0, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        bool calm = false;
+        if (!TAIL) {
+            bool over = false;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const float lm = fmaxf(fmaxf(fmaxf(sacc[0][nt][0], sacc[0][nt][1]), fmaxf(sacc[0][nt][2], sacc[0][nt][3])),
+                                       fmaxf(fmaxf(sacc[1][nt][0], sacc[1][nt][1]), fmaxf(sacc[1][nt][2], sacc[1][nt][3])));
+                over |= !(lm <= thr[nt]);
+            }
+            calm = !__any(over);
+        }
+        if (calm) return;
+        bool moved = false;
+        float alpha[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float mx = fmaxf(fmaxf(score_of(sacc, nt, 0, t0, tail_tag), score_of(sacc, nt, 1, t0, tail_tag)),
+                             score_of(sacc, nt, 2, t0, tail_tag));
+            mx = fmaxf(fmaxf(mx, score_of(sacc, nt, 3, t0, tail_tag)), score_of(sacc, nt, 4, t0, tail_tag));
+            mx = fmaxf(fmaxf(mx, score_of(sacc, nt, 5, t0, tail_tag)),
+                       fmaxf(score_of(sacc, nt, 6, t0, tail_tag), score_of(sacc, nt, 7, t0, tail_tag)));
+            mx = fa_row4_max(mx);
+            mx *= scale2;
+            const bool up = mx > m_run[nt] + FA_RESCALE_LOG2;
+            const float m_new = up ? mx : m_run[nt];
+            alpha[nt] = up ? __builtin_amdgcn_exp2f(m_run[nt] - ((m_new == -INFINITY) ? 0.f : m_new)) : 1.0f;
+            moved |= up;
+            m_run[nt] = m_new;
+            thr[nt] = (m_new == -INFINITY) ? -INFINITY : (m_new + FA_RESCALE_LOG2) * inv_scale2;
+        }
+        if (__any(moved)) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                lacc[nt] *= alpha[nt];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) oacc[mt][nt] *= alpha[nt];
+            }
+        }
+    };
+    auto prob = [&](const f32x4 (&sacc)[2][NT], int nt, int e, int t0, auto tail_tag) {
+        const float m_safe = (m_run[nt] == -INFINITY) ? 0.f : m_run[nt];
+        return (bf16_t)__builtin_amdgcn_exp2f(fmaf(score_of(sacc, nt, e, t0, tail_tag), scale2, -m_safe));
+    };
+    // dead: the block reaches past the last appended row; cache rows there may hold anything, and
+    // 0 * garbage must stay 0
+    auto pv = [&](const unsigned char* sp, const bf16x8 (&pb)[NT], int t0, bool dead) {
+        bf16x8 vf[4];
+        auto v_frag = [&](int mt) {
+            bf16x8 v = *reinterpret_cast<const bf16x8*>(sp + K_BYTES + (mt * 64 + lane) * 16);
+            if (dead) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t0 + 8 * g + j >= n_tok) v[j] = (bf16_t)0.f;
+            }
+            return v;
+        };
+#pragma unroll
+        for (int mt = 0; mt < 3; ++mt) vf[mt] = v_frag(mt);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (mt + 3 < MT) vf[(mt + 3) & 3] = v_frag(mt + 3);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                oacc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[mt & 3], pb[nt], oacc[mt][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[nt], lacc[nt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto finish = [&](const f32x4 (&sacc)[2][NT], const unsigned char* sp, int t0, auto tail_tag) {
+        reference(sacc, t0, tail_tag);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 pb[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pb[nt][e] = prob(sacc, nt, e, t0, tail_tag);
+        __builtin_amdgcn_sched_barrier(0);
+        pv(sp, pb, t0, decltype(tail_tag)::value && t0 + 32 > n_tok);
+    };
+    const std::integral_constant<bool, false> main_tag;
+    const std::integral_constant<bool, true> tail_tag;
+    // Blocks 0 .. STAGES-2 are requested up front; iteration i requests block i+STAGES-1 into the
+    // stage block i-1 has left, works on block i, and ends when block i+1 has landed in every
+    // wave's share (its requests are followed by those of the STAGES-2 blocks that may still be
+    // in flight then).
+    constexpr int INFLIGHT = LD * (PF_STAGES - 2);
+#pragma unroll
+    for (int j = 0; j < PF_STAGES - 1; ++j) issue(j, j);
+    PF_SYNC(INFLIGHT);
+    int st_cur = 0, st_req = PF_STAGES - 1;                 // stage of block i; stage of the next request
+    // The loop bound and the cache length are taken from a vector register the compiler cannot
+    // see through: with provably uniform branches it splits the live ranges of the accumulators
+    // at every branch and ends up copying and spilling them (and a spill reload waits on the
+    // same counter as the requests); with branches it must treat as divergent, both sides of
+    // a branch work in place under the execution mask.
+    int vzero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+    const int nblocks_v = nblocks + vzero, L_v = L + vzero;
+    // this wave's rows see the tokens up to L + row_lo .. L + row_hi: a block entirely below
+    // needs no mask (and holds no dead token), a block entirely above is not computed
+    const int row_lo = (n0 - c) >> g_shift;
+    const int row_hi = min(rows - 1, (n0 - c + WQROWS - 1) >> g_shift);
+    f32x4 sa[2][NT];
+    for (int i = 0; i < nblocks_v; ++i) {
+        issue(i + PF_STAGES - 1, st_req);
+        st_req = st_req + 1 == PF_STAGES ? 0 : st_req + 1;
+        const int t0 = i * 32;
+        if (t0 <= L_v + row_hi) {
+            scores(stage[st_cur], sa);
+            if (t0 + 31 > L_v + row_lo) finish(sa, stage[st_cur], t0, tail_tag);
+            else finish(sa, stage[st_cur], t0, main_tag);
+        }
+        st_cur = st_cur + 1 == PF_STAGES ? 0 : st_cur + 1;
+        PF_SYNC(INFLIGHT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // surplus requests, before the LDS is given up
+#undef PF_SYNC
+
+    // out[r][head*HD + d] = O[d] / l: acc[mt][nt][j] holds O of query row nt*16 + c, feature mt*16 + 4g + j
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = n0 + nt * 16;
+        if (n >= QR) continue;
+        const int r = b * rows + (n >> g_shift);
+        const int col0 = (kvh * G + (n & (G - 1))) * HD + 4 * g;
+        const float inv = 1.0f / lacc[nt][0];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int col = col0 + mt * 16;
+            const int64_t off = tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cs_st(out, off + j, oacc[mt][nt][j] * inv);
+        }
+    }
+}
+
 // out[r][h*HD + d] = sum_s 2^(m_s - M) O_s[d] / sum_s 2^(m_s - M) l_s  over the splits
 #define FA_MAX_SPLIT 64
 // Four output columns per lane (16-byte loads of the partials), HD/4 lanes per query row, so a
@@ -948,6 +1244,26 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
     CS_REQUIRE(!qkv_part || nqg == 1, CS_E_STATE, "fused rotary embedding needs a narrow block");
     int nsplit;
+    // prompt blocks: enough query rows per KV head that a workgroup's 384 rows are all used and
+    // the token axis need not be split to fill the chip
+    const int pf_qrows = PF_WAVES * 16 * PF_NT;
+    const int nqt = (int)cs_ceil_div(QR, pf_qrows);
+    int g_shift = 0;
+    while ((1 << g_shift) < G) ++g_shift;
+    if (QR >= 2 * pf_qrows && (1 << g_shift) == G && (int64_t)B * KVH * nqt >= 40 &&
+        (int64_t)hd * kv->cap * 2 < ((int64_t)1 << 32)) {
+        const int ranges = B * KVH;
+        dim3 grid((unsigned)(cs_round_up(ranges, 8) * nqt));
+        const int pa = cs_prof_begin(CS_PROF_ATTN, s);
+        if (hd == 128)
+            k_attn_prefill<128, PF_NT, f16_t><<<grid, PF_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
+                                                                  kv->cap, nqt, ranges, g_shift, (f16_t*)m->xn, tiled);
+        else
+            k_attn_prefill<64, PF_NT, f16_t><<<grid, PF_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
+                                                                 kv->cap, nqt, ranges, g_shift, (f16_t*)m->xn, tiled);
+        cs_prof_end(pa, s);
+        return cs_launch_ok("k_attn_prefill");
+    }
     if (nqg > 1) {
         // wide block: consumers share the K/V stream of one producer wave through LDS
         const int nqgw = (int)cs_ceil_div(nqg, FA_QG);

@@ -190,6 +190,17 @@ int cs_convert_launch(const void* src, int src_type, void* dst, int dst_type, in
 int cs_fill_i32_launch(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 
 // ---- device helpers -----------------------------------------------------------------
+// request 16 bytes per lane from (uniform base + per-lane byte offset) into LDS at lds_addr + 16*lane.
+// M0 carries the LDS address.  The compiler reserves M0 and only ever sets it immediately before
+// an instruction of its own that reads it, so overwriting it here is safe; it still warns about
+// any reserved register in a clobber list, which is silenced for this one statement.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void cs_load_to_lds(unsigned voff, const void* sbase, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "m0");
+}
+#pragma clang diagnostic pop
+
 __device__ __forceinline__ float cs_ld(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float cs_ld(const bf16_t* p, int64_t i) { return (float)p[i]; }
 __device__ __forceinline__ void cs_st(float* p, int64_t i, float v) { p[i] = v; }

@@ -266,16 +266,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 #define TG_THREADS 512
 #define TG_WROWS 256
 
-// request 16 bytes per lane from (uniform base + per-lane byte offset) into LDS at lds_addr + 16*lane.
-// M0 carries the LDS address.  The compiler reserves M0 and only ever sets it immediately before
-// an instruction of its own that reads it, so overwriting it here is safe; it still warns about
-// any reserved register in a clobber list, which is silenced for this one statement.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void cs_load_to_lds(unsigned voff, const void* sbase, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "m0");
-}
-#pragma clang diagnostic pop
 
 template <int NT, int MODE>
 __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict__ X,

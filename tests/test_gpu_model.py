@@ -156,18 +156,17 @@ def test_long_prompt_goes_through_512_row_blocks(shape):
     model.destroy()
 
 
-@pytest.mark.parametrize("shape", [MINI128, SMALLF32])
-def test_long_prompt_goes_through_default_blocks(shape):
-    """A 2300-token prompt with the default prompt block (2048 rows, then a ragged block of 251
-    that attends to the rows before it): cache rows and the logits of the following verify step
-    match the oracle."""
+@pytest.mark.parametrize("shape,block_rows,n", [(MINI128, 2048, 2300), (SMALLF32, 2048, 2300), (MINI64, 0, 4300)])
+def test_long_prompt_goes_through_large_blocks(shape, block_rows, n):
+    """A prompt longer than one large prompt block (2048 rows, or the default 4096, then a ragged
+    block that attends to the rows before it; the bf16 shapes run the prompt-block attention
+    kernel): cache rows and the logits of the following verify step match the oracle."""
     w = synth.model_weights(shape, 2025, threads=4)
-    model = cs.Model(w, max_batch=1, max_k=10)
-    n = 2300
+    model = cs.Model(w, max_batch=1, max_k=10, prompt_block_rows=block_rows)
     g = synth.planted_history(29, n, shape.vocab, (16, 32), density=0.2, end="span")
     prompt = g["tokens"].tolist()
     _, _, draft = orc.find_match_np(prompt, 3, 10)
-    kv, okv, err = _verify_case(w, model, prompt, draft, 10, cap=2432)
+    kv, okv, err = _verify_case(w, model, prompt, draft, 10, cap=n + 128)
     tol = 2e-2 if shape.dtype == "bf16" else 1e-4
     for layer in range(shape.n_layers):
         k_rows, v_rows = kv.read(layer, 0, 0, n - 1)

@@ -208,6 +208,19 @@ def test_attention_drifting_maximum(host_model, rows, k_ramp):
     assert worst < 1e-2, worst
 
 
+@pytest.mark.parametrize("k_ramp", [None, (0.05, 6.0)])
+def test_attention_prompt_block(k_ramp):
+    """256 block rows per stream (1024 query rows per KV head): the kernel for prompt blocks, which
+    walks the tokens unsplit and writes the normalised rows itself.  Empty, short and long caches
+    under the block, rows past the block poisoned."""
+    w = synth.model_weights(HOST, 99, threads=16)
+    m = cs.Model(w, max_batch=3, max_k=255)
+    sample = [(0, 0), (0, 31), (1, 13), (2, 5), (2, 22)]
+    worst = _attention_case(m, HOST, [0, 700, 2049], 256, sample, seed=21, poison=True, k_ramp=k_ramp)
+    m.destroy()
+    assert worst < 1e-2, worst
+
+
 def test_attention_hd64():
     shape = ModelShape("w-hd64", 1, 2048, 32, 8, 64, 8192, 1024, 10000.0, 1e-5, "bf16")
     w = synth.model_weights(shape, 5, threads=16)
