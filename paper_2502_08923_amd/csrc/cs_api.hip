@@ -251,8 +251,10 @@ static int model_build(cs_model* m, const cs_weights* w) {
     if (m->fast) DEV_ALLOC(m->attn_part, m->attn_part_floats * 4);
     DEV_ALLOC(m->rope, R * (hd / 2) * sizeof(float2));
     DEV_ALLOC(m->tok, R * 4);
-    m->am_chunks = 64;
-    DEV_ALLOC(m->am_val_idx, (size_t)m->R_max * m->am_chunks * 2 * 4);
+    m->am_chunks = 64;                                   // column chunks of the stand-alone argmax
+    // ... or one pair per 128-column tile when the lm_head reduces its own tiles
+    const size_t am_tiles = cs_ceil_div(V, 128) > m->am_chunks ? (size_t)cs_ceil_div(V, 128) : (size_t)m->am_chunks;
+    DEV_ALLOC(m->am_val_idx, (size_t)m->R_max * am_tiles * 2 * 4);
     DEV_ALLOC(m->row_argmax, (size_t)m->R_max * 4);
     DEV_ALLOC(m->draft, (size_t)c.max_batch * (c.max_k > 0 ? c.max_k : 1) * 4);
     DEV_ALLOC(m->draft_len, (size_t)c.max_batch * 4);
@@ -568,11 +570,22 @@ static int verify_impl(cs_model* m, cs_kv* kv, const int32_t* d_pending, const i
     CS_TRY(cs_tokens_launch(m, d_pending, d_draft, d_draft_len, B, k, s));
     CS_TRY(forward_layers(m, kv, rows, s));
     const int pl = cs_prof_begin(CS_PROF_LMHEAD, s);
-    CS_TRY(cs_gemm_launch(m, m->xn, m->lm_head, m->logits, R, V, m->cfg.d_model, CS_GEMM_STORE, 0,
-                          nullptr, s));
-    cs_prof_end(pl, s);
-    CS_TRY(cs_argmax_accept_launch(m, m->logits, B, k, V, d_draft, d_draft_len, d_accepted, d_next,
-                                   nullptr, kv->d_len, hist, hist_stride, hist_len, room, s));
+    if (m->fast && !d_logits_out) {
+        // nobody wants the logits: the lm_head keeps them in its accumulators and hands over the
+        // largest entry of every row per column tile; the accept kernel finishes the argmax
+        int nch = 0;
+        CS_TRY(cs_gemm_launch(m, m->xn, m->lm_head, nullptr, R, V, m->cfg.d_model, CS_GEMM_ARGMAX, 0,
+                              &nch, s));
+        cs_prof_end(pl, s);
+        CS_TRY(cs_accept_launch(m, nch, B, k, d_draft, d_draft_len, d_accepted, d_next, nullptr,
+                                kv->d_len, hist, hist_stride, hist_len, room, s));
+    } else {
+        CS_TRY(cs_gemm_launch(m, m->xn, m->lm_head, m->logits, R, V, m->cfg.d_model, CS_GEMM_STORE, 0,
+                              nullptr, s));
+        cs_prof_end(pl, s);
+        CS_TRY(cs_argmax_accept_launch(m, m->logits, B, k, V, d_draft, d_draft_len, d_accepted, d_next,
+                                       nullptr, kv->d_len, hist, hist_stride, hist_len, room, s));
+    }
     if (d_logits_out)
         CS_HIP(hipMemcpyAsync(d_logits_out, m->logits, (size_t)R * V * 4, hipMemcpyDeviceToDevice, s));
     for (int b = 0; b < B; ++b) kv->h_len_ub[b] += rows;

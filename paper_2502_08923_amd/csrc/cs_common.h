@@ -139,6 +139,11 @@ int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* 
 int cs_swiglu_launch(const cs_model* m, int R, hipStream_t s);
 int cs_tokens_launch(const cs_model* m, const int32_t* pending, const int32_t* draft,
                      const int32_t* draft_len, int B, int k, hipStream_t s);
+// accept rule, state update from the argmax partials m->am_val_idx[row][nch]
+int cs_accept_launch(const cs_model* m, int nch, int B, int k, const int32_t* draft,
+                     const int32_t* draft_len, int32_t* accepted, int32_t* next_tok,
+                     int32_t* row_argmax_out, int32_t* kv_len, int32_t* hist, int64_t hist_stride,
+                     int32_t* hist_len, int32_t* room, hipStream_t s);
 int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k, int V,
                             const int32_t* draft, const int32_t* draft_len, int32_t* accepted,
                             int32_t* next_tok, int32_t* row_argmax_out, int32_t* kv_len,
@@ -147,8 +152,11 @@ int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k
 
 // GEMM: Y = X * W^T.  mode 0: float32 result [R][N] written to Y (nparts_out tells how many
 // split-K partial tiles were written, each [R_stride][N]); mode 1: SwiGLU epilogue into
-// m->act (W is the interleaved gate/up matrix).
-enum { CS_GEMM_STORE = 0, CS_GEMM_SWIGLU = 1 };
+// m->act (W is the interleaved gate/up matrix); mode 2 (tuned kernels only): nothing is stored
+// but, per row and column tile of a workgroup, the largest value and its lowest column, as
+// (float bits, column) pairs m->am_val_idx[row][tile] (nparts_out tells the number of tiles):
+// the greedy argmax of the lm_head without the logits ever reaching memory.
+enum { CS_GEMM_STORE = 0, CS_GEMM_SWIGLU = 1, CS_GEMM_ARGMAX = 2 };
 int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, int R, int N, int K,
                    int mode, int allow_split, int* nparts_out, hipStream_t s);
 int cs_gemm_plain_launch(int dtype, const float* X, const void* W, float* Y, int R, int N, int K,
@@ -207,6 +215,11 @@ __device__ __forceinline__ void cs_st(float* p, int64_t i, float v) { p[i] = v; 
 __device__ __forceinline__ void cs_st(bf16_t* p, int64_t i, float v) { p[i] = (bf16_t)v; }
 __device__ __forceinline__ float cs_ld(const f16_t* p, int64_t i) { return (float)p[i]; }
 __device__ __forceinline__ void cs_st(f16_t* p, int64_t i, float v) { p[i] = (f16_t)v; }
+
+// running (largest value, lowest index) pair of an argmax
+__device__ __forceinline__ void cs_am_take(float& bv, int& bi, float v, int i) {
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
 
 __device__ __forceinline__ float cs_wave_sum(float v) {
 #pragma unroll

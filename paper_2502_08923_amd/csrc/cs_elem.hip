@@ -252,9 +252,7 @@ __global__ void k_swiglu(const float* __restrict__ gu, int F, AT* __restrict__ a
 // greedy argmax (lowest index on ties) in two stages + accept rule + state update
 // -------------------------------------------------------------------------------------
 #define AM_THREADS 256
-__device__ __forceinline__ void am_take(float& bv, int& bi, float v, int i) {
-    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-}
+__device__ __forceinline__ void am_take(float& bv, int& bi, float v, int i) { cs_am_take(bv, bi, v, i); }
 
 __global__ __launch_bounds__(AM_THREADS) void k_argmax_partial(const float* __restrict__ logits,
                                                                int V, int Vc, int vec_ok,
@@ -316,31 +314,42 @@ __global__ __launch_bounds__(AM_THREADS) void k_argmax_partial(const float* __re
     }
 }
 
-// One wave per stream.  a_i = argmax of row i; tau = leading agreement with the draft;
+// One workgroup per stream.  a_i = argmax of row i; tau = leading agreement with the draft;
 // (a stream whose emission budget `room` is used up is skipped, see below)
 // next = a_tau; the KV length grows by tau+1 (App. B.2: truncation past the accepted rows);
 // the accepted drafts and the free token are appended to the history (App. B.3 step 2d).
-__global__ __launch_bounds__(64) void k_accept(const int32_t* __restrict__ part, int nch, int k,
-                                               const int32_t* __restrict__ draft,
-                                               const int32_t* __restrict__ draft_len,
-                                               int32_t* __restrict__ accepted,
-                                               int32_t* __restrict__ next_tok,
-                                               int32_t* __restrict__ row_argmax,
-                                               int32_t* __restrict__ row_argmax_out,
-                                               int32_t* __restrict__ kv_len,
-                                               int32_t* __restrict__ hist, int64_t hist_stride,
-                                               int32_t* __restrict__ hist_len,
-                                               int32_t* __restrict__ room) {
+// The four waves share the rows; a wave reduces the nch partial pairs of a row (up to one per
+// 128 vocabulary entries when the lm_head produced them itself) with four loads in flight per lane.
+#define ACC_THREADS 256
+__global__ __launch_bounds__(ACC_THREADS) void k_accept(const int32_t* __restrict__ part, int nch, int k,
+                                                        const int32_t* __restrict__ draft,
+                                                        const int32_t* __restrict__ draft_len,
+                                                        int32_t* __restrict__ accepted,
+                                                        int32_t* __restrict__ next_tok,
+                                                        int32_t* __restrict__ row_argmax,
+                                                        int32_t* __restrict__ row_argmax_out,
+                                                        int32_t* __restrict__ kv_len,
+                                                        int32_t* __restrict__ hist, int64_t hist_stride,
+                                                        int32_t* __restrict__ hist_len,
+                                                        int32_t* __restrict__ room) {
     const int b = blockIdx.x;
     const int rows = k + 1;
-    const int lane = threadIdx.x;
-    for (int i = 0; i < rows; ++i) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = wave; i < rows; i += ACC_THREADS / 64) {
         const int r = b * rows + i;
+        const int2* __restrict__ p = reinterpret_cast<const int2*>(part) + (int64_t)r * nch;
         float bv = -INFINITY;
         int bi = 0x7fffffff;
-        for (int c = lane; c < nch; c += 64)
-            am_take(bv, bi, __int_as_float(part[((int64_t)r * nch + c) * 2]),
-                    part[((int64_t)r * nch + c) * 2 + 1]);
+        for (int c0 = 0; c0 < nch; c0 += 256) {
+            int2 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + lane + 64 * u;
+                v[u] = c < nch ? p[c] : make_int2(__float_as_int(-INFINITY), 0x7fffffff);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) am_take(bv, bi, __int_as_float(v[u].x), v[u].y);
+        }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
             const float ov = __shfl_xor(bv, o, 64);
@@ -354,7 +363,7 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t* __restrict__ part,
         }
     }
     __syncthreads();
-    if (lane == 0) {
+    if (threadIdx.x == 0) {
         if (room && room[b] <= 0) {
             // a stream with no emission budget left takes no part: nothing is accepted,
             // emitted or appended, and its cache length stays (the row it computed is dead)
@@ -488,9 +497,17 @@ int cs_argmax_accept_launch(const cs_model* m, const float* logits, int B, int k
     k_argmax_partial<<<grid, AM_THREADS, 0, s>>>(logits, V, Vc, vec_ok, m->am_val_idx);
     cs_prof_end(pa, s);
     CS_TRY(cs_launch_ok("k_argmax_partial"));
-    k_accept<<<B, 64, 0, s>>>(m->am_val_idx, nch, k, draft, draft_len, accepted, next_tok,
-                              m->row_argmax, row_argmax_out, kv_len, hist, hist_stride, hist_len,
-                              room);
+    return cs_accept_launch(m, nch, B, k, draft, draft_len, accepted, next_tok, row_argmax_out, kv_len, hist,
+                            hist_stride, hist_len, room, s);
+}
+
+int cs_accept_launch(const cs_model* m, int nch, int B, int k, const int32_t* draft,
+                     const int32_t* draft_len, int32_t* accepted, int32_t* next_tok,
+                     int32_t* row_argmax_out, int32_t* kv_len, int32_t* hist, int64_t hist_stride,
+                     int32_t* hist_len, int32_t* room, hipStream_t s) {
+    k_accept<<<B, ACC_THREADS, 0, s>>>(m->am_val_idx, nch, k, draft, draft_len, accepted, next_tok,
+                                       m->row_argmax, row_argmax_out, kv_len, hist, hist_stride, hist_len,
+                                       room);
     return cs_launch_ok("k_accept");
 }
 

@@ -128,6 +128,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
             __syncthreads();
         }
         if (c < nchunks) __syncthreads();
+        if (MODE == CS_GEMM_ARGMAX) {                      // the two barriers of the consumers' epilogue
+            __syncthreads();
+            __syncthreads();
+        }
         return;
     }
 
@@ -212,6 +216,50 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
                 const int n = n_wave + mt * 16 + 4 * g;
                 if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
             }
+        }
+    } else if (MODE == CS_GEMM_ARGMAX) {
+        // Per row, the largest of this workgroup's 64*MT columns and its column (the lowest on
+        // ties): over the lane's own columns in increasing order, over the four lanes that share
+        // a row, then over the four waves through LDS (the X buffers are free).  Y carries the
+        // pair buffer [R][tiles][2], act_tiled the number of tiles per row.
+        int32_t* __restrict__ am = reinterpret_cast<int32_t*>(Y);
+        const int nch = act_tiled;
+        float* rv = reinterpret_cast<float*>(&xs[0][0]);                 // [4 waves][16*NT rows]
+        int* ri = reinterpret_cast<int*>(&xs[0][0]) + 4 * 16 * NT;
+        __syncthreads();                                    // every wave is past its last X fragment
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if (n_wave + mt * 16 >= N) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float v = acc[mt][nt][j];
+                    if (v > bv) { bv = v; bi = n_wave + mt * 16 + 4 * g + j; }
+                }
+            }
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                const float ov = __shfl_xor(bv, o, 64);
+                const int oi = __shfl_xor(bi, o, 64);
+                cs_am_take(bv, bi, ov, oi);
+            }
+            if (g == 0) {
+                rv[wave * 16 * NT + nt * 16 + lrow] = bv;
+                ri[wave * 16 * NT + nt * 16 + lrow] = bi;
+            }
+        }
+        __syncthreads();
+        if (tid < 16 * NT && r_base + tid < R) {
+            float bv = rv[tid];
+            int bi = ri[tid];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) cs_am_take(bv, bi, rv[w * 16 * NT + tid], ri[w * 16 * NT + tid]);
+            const int64_t o = ((int64_t)(r_base + tid) * nch + w_tile) * 2;
+            am[o] = __float_as_int(bv);
+            am[o + 1] = bi;
         }
     } else {
         // W rows alternate 16 gate rows / 16 up rows of the same 16 FFN channels
@@ -413,6 +461,47 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
                 if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
             }
         }
+    } else if (MODE == CS_GEMM_ARGMAX) {
+        // as in k_gemm_mfma: the largest of the workgroup's 256 columns per row, lowest column on ties
+        int32_t* __restrict__ am = reinterpret_cast<int32_t*>(Y);
+        const int nch = act_tiled;
+        float* rv = reinterpret_cast<float*>(lds);                        // [4 column waves][32*NT rows]
+        int* ri = reinterpret_cast<int*>(lds) + 4 * 32 * NT;
+        __syncthreads();                                    // every wave is past its last fragment
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                if (n_wave + mt * 16 >= N) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float v = acc[mt][nt][j];
+                    if (v > bv) { bv = v; bi = n_wave + mt * 16 + 4 * g + j; }
+                }
+            }
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                const float ov = __shfl_xor(bv, o, 64);
+                const int oi = __shfl_xor(bi, o, 64);
+                cs_am_take(bv, bi, ov, oi);
+            }
+            if (g == 0) {
+                rv[wn * 32 * NT + (wm * NT + nt) * 16 + lrow] = bv;
+                ri[wn * 32 * NT + (wm * NT + nt) * 16 + lrow] = bi;
+            }
+        }
+        __syncthreads();
+        if (tid < 32 * NT && r_base + tid < R) {
+            float bv = rv[tid];
+            int bi = ri[tid];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) cs_am_take(bv, bi, rv[w * 32 * NT + tid], ri[w * 32 * NT + tid]);
+            const int64_t o = ((int64_t)(r_base + tid) * nch + w_tile) * 2;
+            am[o] = __float_as_int(bv);
+            am[o + 1] = bi;
+        }
     } else {
         const int F = N / 2;
 #pragma unroll
@@ -445,6 +534,7 @@ static int launch_tile(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int
     dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, TG_WROWS), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
     if (mode == CS_GEMM_STORE) k_gemm_dma<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+    else if (mode == CS_GEMM_ARGMAX) k_gemm_dma<NT, CS_GEMM_ARGMAX><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     else k_gemm_dma<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_dma");
@@ -459,6 +549,8 @@ static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
     if (mode == CS_GEMM_STORE) {
         k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+    } else if (mode == CS_GEMM_ARGMAX) {
+        k_gemm_mfma<MT, NT, CS_GEMM_ARGMAX><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     } else {
         if constexpr (MT % 2 == 0)
             k_gemm_mfma<MT, NT, CS_GEMM_SWIGLU><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
@@ -564,7 +656,13 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     // 24 and 112 tiles, are still faster through the weight-streaming kernel).
     const bool tile = cs_gemm_x_tiled(R, N);
     // the SwiGLU epilogue writes the input of the down projection (d_model outputs, same rows)
-    const int act_tiled = mode == CS_GEMM_SWIGLU && cs_gemm_x_tiled(R, m->cfg.d_model) ? 1 : 0;
+    int act_tiled = mode == CS_GEMM_SWIGLU && cs_gemm_x_tiled(R, m->cfg.d_model) ? 1 : 0;
+    if (mode == CS_GEMM_ARGMAX) {
+        // one (value, column) pair per row and workgroup column tile, in place of Y
+        CS_REQUIRE(!allow_split && nparts_out, CS_E_STATE, "argmax epilogue: no K split, tile count wanted");
+        act_tiled = (int)cs_ceil_div(N, tile ? TG_WROWS : 128);
+        Y = reinterpret_cast<float*>(m->am_val_idx);
+    }
     const int rt_total = (int)cs_ceil_div(R, 16);
     const int r_blocks = tile ? (int)cs_ceil_div(rt_total, 18) : (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;
@@ -578,7 +676,7 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     if (ksplit > 1) CS_REQUIRE(allow_split, CS_E_STATE, "K split without a partial-tile buffer");
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
     const int nparts = (int)cs_ceil_div(K, Ks);
-    if (nparts_out) *nparts_out = nparts;
+    if (nparts_out) *nparts_out = mode == CS_GEMM_ARGMAX ? act_tiled : nparts;
     const int rt = (int)cs_ceil_div(rt_total, r_blocks);
     const f16_t* x = (const f16_t*)X;
     const f16_t* w = (const f16_t*)W;

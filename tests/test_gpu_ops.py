@@ -256,6 +256,16 @@ def _deep_verify(shape, B, L, k, check_streams, seed):
         kv.set_len(b, L)
     acc, nxt, logits = cs.cs_verify(model, kv, t32(pending), t32(draft), t32(dlen), k, want_logits=True)
     torch.cuda.synchronize()
+    # the same step without the logits: the lm_head then takes the argmax in its own epilogue and
+    # writes no logits; every stream must come out identical (same accumulators, same tie rule)
+    for b in range(B):
+        kv.set_len(b, L)
+    acc2, nxt2, _ = cs.cs_verify(model, kv, t32(pending), t32(draft), t32(dlen), k, want_logits=False)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, acc2) and torch.equal(nxt, nxt2)
+    for b in range(B):
+        row = logits[b, int(acc2[b])]
+        assert float(row[int(nxt2[b])]) == float(row.max())
     logits = logits.cpu().numpy()
     worst = 0.0
     for b in check_streams:
