@@ -1190,16 +1190,34 @@ __global__ __launch_bounds__(FA_MERGE_THREADS) void k_attn_merge(const float* __
     const int64_t item = ((int64_t)b * KVH + kvh) * nqg + qg;
     const float2* __restrict__ ml = reinterpret_cast<const float2*>(pml) + (item * nsplit * FA_QROWS + nl);
     const float* __restrict__ o = po + (item * nsplit * FA_QROWS + nl) * HD + d;
+    // eight splits at a time, all their loads issued before the first is used: with many splits
+    // (one stream: 32) and few workgroups this kernel is nothing but load latency
     float M = -INFINITY;
-    for (int w = 0; w < nsplit; ++w) M = fmaxf(M, ml[(int64_t)w * FA_QROWS].x);
+    for (int w0 = 0; w0 < nsplit; w0 += 8) {
+        float mx[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mx[u] = w0 + u < nsplit ? ml[(int64_t)(w0 + u) * FA_QROWS].x : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, mx[u]);
+    }
     float den = 0.f;
     f32x4 num = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int w = 0; w < nsplit; ++w) {                      // same order in every lane
-        const float2 p = ml[(int64_t)w * FA_QROWS];
-        const float wgt = (p.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(p.x - M);
-        den += wgt * p.y;
-        num += wgt * *reinterpret_cast<const f32x4*>(o + (int64_t)w * FA_QROWS * HD);
+    for (int w0 = 0; w0 < nsplit; w0 += 8) {                // same order in every lane
+        float2 p[8];
+        f32x4 ov[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool in = w0 + u < nsplit;
+            p[u] = in ? ml[(int64_t)(w0 + u) * FA_QROWS] : make_float2(-INFINITY, 0.f);
+            ov[u] = in ? *reinterpret_cast<const f32x4*>(o + (int64_t)(w0 + u) * FA_QROWS * HD)
+                       : (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float wgt = (p[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(p[u].x - M);
+            den += wgt * p[u].y;
+            num += wgt * ov[u];
+        }
     }
     const float inv = 1.0f / den;
     const int r = b * rows + i;
