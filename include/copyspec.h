@@ -298,7 +298,7 @@ int cs_decode_merged(cs_model* target, cs_kv* target_kv, cs_model* draft, cs_kv*
                      cs_merged_stats* stats /*may be NULL*/);
 
 /* Run prompt[0 .. n-1) of one stream through the model, in blocks of up to
- * max(512, max_k + 1) rows, so that its cache holds them and its length is n-1 (the last
+ * max(prompt block rows, max_k + 1) rows (cs_set_prompt_block_rows, 4096 by default), so that its cache holds them and its length is n-1 (the last
  * prompt token stays pending).  Resets the stream's length first.  Single-stream caches
  * only (stream_idx == 0).  prompt: host.  Synchronous. */
 int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int32_t* prompt /*host*/,
