@@ -182,10 +182,18 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     const int QR = G * rows;
     const int L = kv_len[b];
     const int n_tok = L + rows;
-    const int t_begin = min(wg * Tw, n_tok);
-    const int t_end = min(n_tok, t_begin + Tw);         // empty range for waves past the end
+    // The workgroup's token range is 4*Tw long; its four waves take the 32-token blocks of it in
+    // turn (wave w: blocks w, w+4, ...), so that at any time the workgroup reads neighbouring
+    // blocks: the four 64-byte pieces a V row contributes then form one 256-byte run.
+    constexpr int STEP = 4 * 32;
+    const int w_begin = min(split * 4 * Tw, n_tok);
+    const int t_end = min(n_tok, w_begin + 4 * Tw);
+    const int t_begin = w_begin + 32 * wave;            // may lie past t_end: no blocks then
     // blocks that lie completely inside the old cache need neither mask nor clean-up
-    const int t_split = max(t_begin, min(t_end, (L / 32) * 32));
+    const int t_split = max(w_begin, min(t_end, (L / 32) * 32));
+    // first block of this wave at or beyond t_split
+    const int t_tail = t_begin >= t_split ? t_begin : t_begin + (t_split - t_begin + STEP - 1) / STEP * STEP;
+    (void)wg;
     const bf16_t* __restrict__ K = kc + ((int64_t)b * KVH + kvh) * cap * HD;
     const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
 
@@ -409,23 +417,23 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
         const int e = t_split;
         load_k(k0, t_begin, e);
         load_v(v0, t_begin, e);
-        load_k(k1, t_begin + 32, e);
-        for (int t0 = t_begin; t0 < e; t0 += 192) {
-            load_v(v1, t0 + 32, e);  load_k(k2, t0 + 64, e);   compute(k0, v0, t0, main_tag);
-            if (t0 + 32 >= e) break;
-            load_v(v0, t0 + 64, e);  load_k(k0, t0 + 96, e);   compute(k1, v1, t0 + 32, main_tag);
-            if (t0 + 64 >= e) break;
-            load_v(v1, t0 + 96, e);  load_k(k1, t0 + 128, e);  compute(k2, v0, t0 + 64, main_tag);
-            if (t0 + 96 >= e) break;
-            load_v(v0, t0 + 128, e); load_k(k2, t0 + 160, e);  compute(k0, v1, t0 + 96, main_tag);
-            if (t0 + 128 >= e) break;
-            load_v(v1, t0 + 160, e); load_k(k0, t0 + 192, e);  compute(k1, v0, t0 + 128, main_tag);
-            if (t0 + 160 >= e) break;
-            load_v(v0, t0 + 192, e); load_k(k1, t0 + 224, e);  compute(k2, v1, t0 + 160, main_tag);
+        load_k(k1, t_begin + STEP, e);
+        for (int t0 = t_begin; t0 < e; t0 += 6 * STEP) {
+            load_v(v1, t0 + STEP, e);      load_k(k2, t0 + 2 * STEP, e);  compute(k0, v0, t0, main_tag);
+            if (t0 + STEP >= e) break;
+            load_v(v0, t0 + 2 * STEP, e);  load_k(k0, t0 + 3 * STEP, e);  compute(k1, v1, t0 + STEP, main_tag);
+            if (t0 + 2 * STEP >= e) break;
+            load_v(v1, t0 + 3 * STEP, e);  load_k(k1, t0 + 4 * STEP, e);  compute(k2, v0, t0 + 2 * STEP, main_tag);
+            if (t0 + 3 * STEP >= e) break;
+            load_v(v0, t0 + 4 * STEP, e);  load_k(k2, t0 + 5 * STEP, e);  compute(k0, v1, t0 + 3 * STEP, main_tag);
+            if (t0 + 4 * STEP >= e) break;
+            load_v(v1, t0 + 5 * STEP, e);  load_k(k0, t0 + 6 * STEP, e);  compute(k1, v0, t0 + 4 * STEP, main_tag);
+            if (t0 + 5 * STEP >= e) break;
+            load_v(v0, t0 + 6 * STEP, e);  load_k(k1, t0 + 7 * STEP, e);  compute(k2, v1, t0 + 5 * STEP, main_tag);
         }
     }
     // the few blocks that touch the new rows or the dead region: masked, not pipelined
-    for (int t0 = t_split; t0 < t_end; t0 += 32) {
+    for (int t0 = t_tail; t0 < t_end; t0 += STEP) {
         fa_kbuf<HD> kt;
         fa_vbuf<HD> vt;
         load_k(kt, t0, t_end);
