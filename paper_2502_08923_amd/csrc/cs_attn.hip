@@ -556,12 +556,16 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     // workgroup's query groups is walked (long prompt blocks: the upper triangle of the block).
     const int last_row = min(rows - 1, ((qgw + 1) * FA_QG * FA_QROWS - 1) / G);
     const int n_lim = L + last_row + 1;
-    const int t_begin = min(split * Tw, n_lim);
-    const int t_end = min(n_lim, t_begin + Tw);
-    const int nblocks = (t_end - t_begin + 31) / 32;
-    // both teams pass the same number of barriers: the longer range of the two
-    const int t_begin0 = min((split - team) * Tw, n_lim);
-    const int nblocks_wg = (min(n_lim, t_begin0 + Tw) - t_begin0 + 31) / 32;
+    // The two teams share the workgroup's token range of FA_TEAMS*Tw and take its 32-token blocks
+    // in turn (team t: blocks t, t+2, ...), so the workgroup reads neighbouring blocks together.
+    // `split` still numbers the partial result: (range, team).
+    constexpr int TSTEP = 32 * FA_TEAMS;
+    const int w_begin = min((split - team) * Tw, n_lim);
+    const int w_blocks = (min(n_lim, w_begin + FA_TEAMS * Tw) - w_begin + 31) / 32;
+    const int t_begin = w_begin + 32 * team;
+    const int nblocks = (w_blocks - team + FA_TEAMS - 1) / FA_TEAMS;
+    // both teams pass the same number of barriers: team 0's count
+    const int nblocks_wg = (w_blocks + FA_TEAMS - 1) / FA_TEAMS;
     const bf16_t* __restrict__ K = kc + ((int64_t)b * KVH + kvh) * cap * HD;
     const bf16_t* __restrict__ V = vc + ((int64_t)b * KVH + kvh) * HD * cap;
 
@@ -586,7 +590,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
         bf16x8 kr[3][2][KS], vr[3][MT];       // three blocks in flight in registers (block j in slot j % 3)
         auto load = [&](int slot, int blk) {
             const int bl = blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0);   // clamped
-            const int t0 = (nblocks > 0 ? t_begin : 0) + bl * 32;
+            const int t0 = (nblocks > 0 ? t_begin : 0) + bl * TSTEP;
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
                 const bf16_t* kp = K + (int64_t)(t0 + ktok0 + 4 * a) * HD + g * 8;
@@ -599,7 +603,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
                 vr[slot][mt] = *reinterpret_cast<const bf16x8*>(V + (int64_t)(mt * 16 + c) * cap + t0 + 8 * g);
         };
         auto store = [&](int slot, int st, int blk) {
-            const int t0 = (nblocks > 0 ? t_begin : 0) + (blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0)) * 32;
+            const int t0 = (nblocks > 0 ? t_begin : 0) + (blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0)) * TSTEP;
             unsigned char* sp = stage[st];
 #pragma unroll
             for (int a = 0; a < 2; ++a)
@@ -845,9 +849,9 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     // waves sharing a SIMD want different units after every barrier.
     auto block = [&](f32x4 (&cur)[2][FA_NT], f32x4 (&nxt)[2][FA_NT], int i) {
         if (!(live && i < nblocks)) return;
-        const int t0 = t_begin + i * 32;
+        const int t0 = t_begin + i * TSTEP;
         const bool has_next = i + 1 < nblocks;
-        if (has_next && t0 + 64 <= L) {
+        if (has_next && t0 + TSTEP + 32 <= L) {
             fused(cur, nxt, stage[i % FA_STAGES], stage[(i + 1) % FA_STAGES]);
             return;
         }
