@@ -16,8 +16,8 @@
 // lane); V is cached transposed (token index contiguous) so its A operand is one 16-byte
 // load per lane.  Softmax runs online in float32 (base 2), the row maximum is shared by the
 // four lanes that hold a query row, and O is only rescaled when some maximum moved.
-// The token range of a stream is split over waves; a merge kernel combines the partial
-// (max, sum, O) triples.
+// The token range of a stream is split over workgroups, whose waves take its 32-token blocks in
+// turn; a merge kernel combines the partial (max, sum, O) triples.
 #include <type_traits>
 
 #include "cs_common.h"
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                 hi[u] = (bf16_t)y;
             }
         };
-        // first the new rows whose position lies in one of this workgroup's four token ranges:
+        // first the new rows whose position lies in this workgroup's token range (4*Tw long):
         // their stores complete while the query tile is being built
         bf16_t* __restrict__ Kw = fr.kc_w + ((int64_t)b * KVH + kvh) * cap * HD;
         bf16_t* __restrict__ Vw = fr.vc_w + ((int64_t)b * KVH + kvh) * HD * cap;
@@ -546,7 +546,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     // which group of FA_QG query groups: the last rows of a block see the most tokens (see n_lim
     // below), so they are dispatched first and the short ones fill the tail of the launch
     const int qgw = nqgw - 1 - slot % nqgw;
-    const int split = (range % nsp) * FA_TEAMS + team;  // each team owns one token range
+    const int split = (range % nsp) * FA_TEAMS + team;  // number of this team's partial result
     const int kvh = (range / nsp) % KVH, b = range / (nsp * KVH);
     const int G = H / KVH;
     const int QR = G * rows;
