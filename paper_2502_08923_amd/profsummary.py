@@ -1,6 +1,6 @@
 """Turn a rocprofv3 `--kernel-trace` result database into a short per-kernel text table.
 
-    python -m paper_2502_08923_amd.profsummary gpurun_out/prof/bench_results.db [--skip N]
+    python -m paper_2502_08923_amd.profsummary <output dir>/bench_results.db [--skip N]
 
 Only reads the database rocprofv3 wrote; runs nothing on the GPU.
 """
