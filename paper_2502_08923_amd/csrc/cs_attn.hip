@@ -414,22 +414,37 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     {
         fa_kbuf<HD> k0, k1, k2;
         fa_vbuf<HD> v0, v1;
+        // this wave's unmasked blocks are t_begin + j*STEP, j < n.  Every workgroup starts at a
+        // different j (and wraps): the workgroups of a launch run in step, and with all of them at
+        // the same relative position some cache pitches put them on the same memory channels
         const int e = t_split;
-        load_k(k0, t_begin, e);
-        load_v(v0, t_begin, e);
-        load_k(k1, t_begin + STEP, e);
-        for (int t0 = t_begin; t0 < e; t0 += 6 * STEP) {
-            load_v(v1, t0 + STEP, e);      load_k(k2, t0 + 2 * STEP, e);  compute(k0, v0, t0, main_tag);
-            if (t0 + STEP >= e) break;
-            load_v(v0, t0 + 2 * STEP, e);  load_k(k0, t0 + 3 * STEP, e);  compute(k1, v1, t0 + STEP, main_tag);
-            if (t0 + 2 * STEP >= e) break;
-            load_v(v1, t0 + 3 * STEP, e);  load_k(k1, t0 + 4 * STEP, e);  compute(k2, v0, t0 + 2 * STEP, main_tag);
-            if (t0 + 3 * STEP >= e) break;
-            load_v(v0, t0 + 4 * STEP, e);  load_k(k2, t0 + 5 * STEP, e);  compute(k0, v1, t0 + 3 * STEP, main_tag);
-            if (t0 + 4 * STEP >= e) break;
-            load_v(v1, t0 + 5 * STEP, e);  load_k(k0, t0 + 6 * STEP, e);  compute(k1, v0, t0 + 4 * STEP, main_tag);
-            if (t0 + 5 * STEP >= e) break;
-            load_v(v0, t0 + 6 * STEP, e);  load_k(k1, t0 + 7 * STEP, e);  compute(k2, v1, t0 + 5 * STEP, main_tag);
+        const int n = t_begin < e ? (e - t_begin + STEP - 1) / STEP : 0;
+        const int wg_id = (b * KVH + kvh) * nsplit + split;
+        const int n_wg = w_begin < e ? (e - w_begin + STEP - 1) / STEP : 0;       // wave 0's count
+        const int rot_wg = n_wg > 0 ? (int)(((int64_t)wg_id * 2654435761LL >> 8) % n_wg) : 0;
+        const int rot = n > 0 ? min(rot_wg, n - 1) : 0;     // the same round for all four waves
+        auto at = [&](int i) {
+            int j = i + rot;
+            j = j >= n ? j - n : j;
+            return t_begin + j * STEP;
+        };
+        auto ldk = [&](fa_kbuf<HD>& buf, int i) { if (i < n) load_k(buf, at(i), e); };
+        auto ldv = [&](fa_vbuf<HD>& buf, int i) { if (i < n) load_v(buf, at(i), e); };
+        ldk(k0, 0);
+        ldv(v0, 0);
+        ldk(k1, 1);
+        for (int i = 0; i < n; i += 6) {
+            ldv(v1, i + 1);  ldk(k2, i + 2);  compute(k0, v0, 0, main_tag);
+            if (i + 1 >= n) break;
+            ldv(v0, i + 2);  ldk(k0, i + 3);  compute(k1, v1, 0, main_tag);
+            if (i + 2 >= n) break;
+            ldv(v1, i + 3);  ldk(k1, i + 4);  compute(k2, v0, 0, main_tag);
+            if (i + 3 >= n) break;
+            ldv(v0, i + 4);  ldk(k2, i + 5);  compute(k0, v1, 0, main_tag);
+            if (i + 4 >= n) break;
+            ldv(v1, i + 5);  ldk(k0, i + 6);  compute(k1, v0, 0, main_tag);
+            if (i + 5 >= n) break;
+            ldv(v0, i + 6);  ldk(k1, i + 7);  compute(k2, v1, 0, main_tag);
         }
     }
     // the few blocks that touch the new rows or the dead region: masked, not pipelined
