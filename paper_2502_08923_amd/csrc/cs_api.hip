@@ -87,13 +87,13 @@ extern "C" int cs_profile_read(int32_t cls, double* total_ms, int64_t* launches)
 // -------------------------------------------------------------------------------------
 // small kernels used only here
 // -------------------------------------------------------------------------------------
-// interleave gate and up rows in blocks of 8: dst row (f/8)*16 + 8*u + f%8
+// interleave gate and up rows in blocks of 16: dst row (f/16)*32 + 16*u + f%16
 template <typename T>
 __global__ void k_pack_gu(const T* __restrict__ wg, const T* __restrict__ wu, int F, int d,
                           T* __restrict__ dst) {
     const int row = blockIdx.x;               // destination row
-    const int f = (row / 16) * 8 + row % 8;
-    const T* __restrict__ src = ((row / 8) % 2 ? wu : wg) + (int64_t)f * d;
+    const int f = (row / 32) * 16 + row % 16;
+    const T* __restrict__ src = ((row / 16) % 2 ? wu : wg) + (int64_t)f * d;
     for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(int64_t)row * d + c] = src[c];
 }
 

@@ -65,7 +65,7 @@ void cs_prof_end(int slot, hipStream_t s);
 struct cs_layer_dev {
     void* wqkv;    // [(H+2KVH)*hd][d]   rows: q heads, k heads, v heads
     void* wo;      // [d][H*hd]
-    void* wgu;     // [2F][d]; row (f/8)*16 + 8*u + f%8 holds gate (u=0) or up (u=1) of f
+    void* wgu;     // [2F][d]; row (f/16)*32 + 16*u + f%16 holds gate (u=0) or up (u=1) of f
     void* wd;      // [d][F]
     float* norm1;
     float* norm2;

@@ -236,15 +236,15 @@ __global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
 
 // -------------------------------------------------------------------------------------
 // SwiGLU on the interleaved gate/up projection (plain path): row layout of gu matches the
-// packed weight: index (f/8)*16 + 8*u + f%8.
+// packed weight: index (f/16)*32 + 16*u + f%16.
 // -------------------------------------------------------------------------------------
 template <typename AT>
 __global__ void k_swiglu(const float* __restrict__ gu, int F, AT* __restrict__ act) {
     const int r = blockIdx.y;
     const int f = blockIdx.x * blockDim.x + threadIdx.x;
     if (f >= F) return;
-    const int64_t base = (int64_t)r * 2 * F + (f / 8) * 16 + (f % 8);
-    const float g = gu[base], u = gu[base + 8];
+    const int64_t base = (int64_t)r * 2 * F + (f / 16) * 32 + (f % 16);
+    const float g = gu[base], u = gu[base + 16];
     cs_st(act, (int64_t)r * F + f, g / (1.0f + expf(-g)) * u);
 }
 

@@ -262,24 +262,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
             am[o + 1] = bi;
         }
     } else {
-        // every 16-row W tile holds 8 gate rows, then the 8 up rows of the same 8 FFN channels:
-        // lanes g = 0, 1 hold the gates of channels 4g..4g+3, lanes g + 2 the matching ups
+        // W rows alternate 16 gate rows / 16 up rows of the same 16 FFN channels
         const int F = N / 2;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int r = r_base + nt * 16 + lrow;
+            if (r >= R) continue;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int n = n_wave + mt * 16;
+            for (int mp = 0; mp < MT / 2; ++mp) {
+                const int n = n_wave + mp * 32;
+                if (n >= N) continue;
+                const int f = n / 2 + 4 * g;
                 f16x4 o;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float gt = acc[mt][nt][j];
-                    const float up = __shfl_xor(gt, 32, 64);    // whole wave takes part
+                    const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
                     o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
                 }
-                if (r >= R || n >= N || g >= 2) continue;
-                const int f = n / 2 + 4 * g;
                 // act_tiled: the down projection runs the many-row GEMM (fragment order)
                 *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
             }
@@ -504,23 +503,22 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
             am[o + 1] = bi;
         }
     } else {
-        // (gate, up) pairs inside every 16-row W tile, as in k_gemm_mfma
         const int F = N / 2;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int r = r_base + (wm * NT + nt) * 16 + lrow;
+            if (r >= R) continue;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const int n = n_wave + mt * 16;
+            for (int mp = 0; mp < 2; ++mp) {
+                const int n = n_wave + mp * 32;
+                if (n >= N) continue;
+                const int f = n / 2 + 4 * g;
                 f16x4 o;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float gt = acc[mt][nt][j];
-                    const float up = __shfl_xor(gt, 32, 64);
+                    const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
                     o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
                 }
-                if (r >= R || n >= N || g >= 2) continue;
-                const int f = n / 2 + 4 * g;
                 *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
             }
         }
@@ -566,7 +564,7 @@ static bool mfma_shape_ok(int N, int K) { return K % GEMM_KC == 0 && N % 16 == 0
 // dst[k/128][n/16][(k%128)/32][lane l][8]: lane l (row n%16 = l%16, k-group l/16) holds the 8
 // elements W[n][(k/32)*32 + (l/16)*8 ..].  N_total/n_off place a block of rows inside a taller
 // matrix (the fused q,k,v projection).  rowmap 0: source row = n.  rowmap 1: rows alternate
-// 8 gate rows (src) / 8 up rows (src2), so every 16-row tile holds both halves of 8 channels.
+// 16 gate rows (src) / 16 up rows (src2).
 __global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restrict__ src2, int N, int K,
                          int rowmap, int N_total, int n_off, f16_t* __restrict__ dst) {
     const int64_t nvec = (int64_t)N * K / 8;
@@ -582,8 +580,8 @@ __global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restric
         const int k = kc * 128 + s * 32 + (lane >> 4) * 8;
         const bf16_t* sp = src + (int64_t)n * K;
         if (rowmap == 1) {
-            const int f = (n >> 4) * 8 + (n & 7);
-            sp = (((n >> 3) & 1) ? src2 : src) + (int64_t)f * K;
+            const int f = (n >> 5) * 16 + (n & 15);
+            sp = (((n >> 4) & 1) ? src2 : src) + (int64_t)f * K;
         }
         const int64_t o = ((((int64_t)kc * nt_total + (n_off >> 4) + nt) * 4 + s) * 64 + lane) * 8;
         // bfloat16 -> float16: exact for 2^-17 <= |w| < 65504 (8 significant bits fit the
@@ -642,7 +640,7 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
                 (const float*)X, (const float*)W, Y, R, N, K);
         return cs_launch_ok("k_gemm_plain");
     }
-    CS_REQUIRE(mfma_shape_ok(N, K), CS_E_UNSUPPORTED,
+    CS_REQUIRE(mfma_shape_ok(N, K) && (mode != CS_GEMM_SWIGLU || N % 32 == 0), CS_E_UNSUPPORTED,
                "bf16 GEMM needs N %% 16 == 0 and K %% 128 == 0 (N=%d K=%d)", N, K);
     // Shape of the launch.  One workgroup (6 waves, ~250 registers) fills a compute unit.  Wide
     // projections (gate/up, lm_head) have enough 128-row tiles.  Narrow ones (q/k/v, o, down)
