@@ -900,16 +900,19 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
 // -------------------------------------------------------------------------------------
 // kernel for prompt blocks (hundreds of rows per stream and more)
 //
-// There the pass is bound by the matrix cores, not by HBM: a block of 2048 rows has 8192 query
-// rows per KV head, and every cached token is used by all of them.  So the token axis is not
-// split at all: a workgroup of eight waves owns 384 query rows (48 each, the same register tile
-// as above), walks the tokens its rows can see once, and writes the normalised result itself
-// (no partial results, no merge).  All eight waves multiply; nobody is set aside to load: each
-// wave requests its share (1 KB fragment blocks) of every 32-token block with direct-to-LDS loads
-// into a ring of six stages, so four blocks are in flight while one is multiplied, and the
-// loads cost no registers.  The loads and the waits on them are inline assembly with exact
-// counts, as in the many-row GEMM: after the query fragments have arrived the kernel issues
-// no other vector memory load until its final stores.
+// There the pass is bound by the matrix cores and the vector unit, not by HBM: a block of 4096
+// rows has 16384 query rows per KV head, and every cached token is used by all of them.  So the
+// token axis is not split at all: a workgroup of eight waves owns 256 query rows (32 each: with
+// 48, the register tile of the kernels above, a 2048-row block gives 176 workgroups for 256
+// compute units and is slower), walks the tokens its rows can see once, and writes the
+// normalised result itself (no partial results, no merge).  All eight waves multiply; nobody
+// is set aside to load: each wave requests its share (1 KB fragment blocks) of every 32-token
+// block with direct-to-LDS loads into a ring of six stages, so four blocks are in flight while
+// one is multiplied, and the loads cost no registers.  The loads and the waits on them are
+// inline assembly with exact counts, as in the many-row GEMM: after the query fragments have
+// arrived the kernel issues no other vector memory load until its final stores.  Per block a
+// wave runs scores -> softmax -> PV in sequence (the other wave of its SIMD fills the gaps);
+// interleaving them inside the wave, or across the two waves of a SIMD, was slower or spilled.
 // Workgroups of one KV head get ids 8 apart (one XCD, one L2); the last rows of a block see the
 // most tokens and are dispatched first.
 // -------------------------------------------------------------------------------------
@@ -1289,7 +1292,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     const bf16_t* vc = (const bf16_t*)kv->v + layer * per_layer;
     CS_REQUIRE(!qkv_part || nqg == 1, CS_E_STATE, "fused rotary embedding needs a narrow block");
     int nsplit;
-    // prompt blocks: enough query rows per KV head that a workgroup's 384 rows are all used and
+    // prompt blocks: enough query rows per KV head that a workgroup's 256 rows are all used and
     // the token axis need not be split to fill the chip
     const int pf_qrows = PF_WAVES * 16 * PF_NT;
     const int nqt = (int)cs_ceil_div(QR, pf_qrows);
