@@ -97,7 +97,7 @@ __global__ void k_pack_gu(const T* __restrict__ wg, const T* __restrict__ wu, in
     for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(int64_t)row * d + c] = src[c];
 }
 
-// V rows [KVH][n][hd] <-> transposed cache [KVH][hd][cap]
+// V rows [KVH][n][hd] <-> cache [KVH][cap/128][hd][128] (cs_v_index)
 template <typename T, int TO_CACHE>
 __global__ void k_v_transpose(T* __restrict__ cache, T* __restrict__ rows, int64_t cap, int hd,
                               int64_t pos0, int64_t n) {
@@ -106,7 +106,7 @@ __global__ void k_v_transpose(T* __restrict__ cache, T* __restrict__ rows, int64
          idx += (int64_t)gridDim.x * blockDim.x) {
         const int64_t t = idx / hd;
         const int d = (int)(idx % hd);
-        T* c = cache + ((int64_t)g * hd + d) * cap + pos0 + t;
+        T* c = cache + (int64_t)g * hd * cap + cs_v_index(pos0 + t, d, hd);
         T* r = rows + ((int64_t)g * n + t) * hd + d;
         if (TO_CACHE) *c = *r; else *r = *c;
     }
@@ -319,7 +319,8 @@ extern "C" int cs_kv_create(const cs_model* m, int32_t batch, int64_t capacity, 
     CS_REQUIRE(kv, CS_E_DEVICE, "out of host memory");
     kv->m = m;
     kv->B = batch;
-    kv->cap = cs_round_up(capacity, 64);
+    kv->limit = cs_round_up(capacity, 64);          // what the capacity checks go by
+    kv->cap = cs_round_up(capacity, CS_VBLK);       // what is allocated (the V cache is laid out in blocks)
     const cs_model_cfg& c = m->cfg;
     const size_t bytes = (size_t)c.n_layers * batch * c.n_kv_heads * kv->cap * c.head_dim * m->esz;
     kv->h_len_ub = (int64_t*)calloc(batch, sizeof(int64_t));
@@ -355,7 +356,7 @@ extern "C" void cs_kv_destroy(cs_kv* kv) {
 extern "C" int cs_kv_set_len(cs_kv* kv, int32_t b, int64_t len) {
     CS_REQUIRE(kv, CS_E_ARG, "cs_kv_set_len: NULL handle");
     CS_REQUIRE(b >= 0 && b < kv->B, CS_E_ARG, "cs_kv_set_len: stream %d out of range", b);
-    CS_REQUIRE(len >= 0 && len <= kv->cap, CS_E_CAPACITY, "cs_kv_set_len: length %lld > capacity",
+    CS_REQUIRE(len >= 0 && len <= kv->limit, CS_E_CAPACITY, "cs_kv_set_len: length %lld > capacity",
                (long long)len);
     const int32_t v = (int32_t)len;
     CS_HIP(hipDeviceSynchronize());
@@ -366,7 +367,7 @@ extern "C" int cs_kv_set_len(cs_kv* kv, int32_t b, int64_t len) {
 
 extern "C" int cs_kv_set_len_dev(cs_kv* kv, const int32_t* d_len, int64_t ub, void* stream) {
     CS_REQUIRE(kv && d_len, CS_E_ARG, "cs_kv_set_len_dev: NULL argument");
-    CS_REQUIRE(ub >= 0 && ub <= kv->cap, CS_E_CAPACITY, "cs_kv_set_len_dev: bound %lld > capacity",
+    CS_REQUIRE(ub >= 0 && ub <= kv->limit, CS_E_CAPACITY, "cs_kv_set_len_dev: bound %lld > capacity",
                (long long)ub);
     CS_HIP(hipMemcpyAsync(kv->d_len, d_len, (size_t)kv->B * 4, hipMemcpyDeviceToDevice,
                           (hipStream_t)stream));
@@ -395,9 +396,9 @@ static int kv_io(cs_kv* kv, int layer, int b, int64_t pos0, int64_t n, void* k_r
     const cs_model_cfg& c = kv->m->cfg;
     CS_REQUIRE(layer >= 0 && layer < c.n_layers && b >= 0 && b < kv->B, CS_E_ARG,
                "cs_kv_load/read: layer or stream out of range");
-    CS_REQUIRE(pos0 >= 0 && n >= 0 && pos0 + n <= kv->cap, CS_E_CAPACITY,
+    CS_REQUIRE(pos0 >= 0 && n >= 0 && pos0 + n <= kv->limit, CS_E_CAPACITY,
                "cs_kv_load/read: rows [%lld, %lld) exceed capacity %lld", (long long)pos0,
-               (long long)(pos0 + n), (long long)kv->cap);
+               (long long)(pos0 + n), (long long)kv->limit);
     if (n == 0) return CS_OK;
     const size_t e = kv->m->esz;
     const int hd = c.head_dim, KVH = c.n_kv_heads;
@@ -518,10 +519,10 @@ static int64_t kv_max_ub(const cs_kv* kv) {
 
 // every stream must have room for `rows` more rows; refreshes the host bounds if needed
 static int kv_check_room(cs_kv* kv, int rows) {
-    if (kv_max_ub(kv) + rows > kv->cap) CS_TRY(kv_sync_lengths(kv));
-    CS_REQUIRE(kv_max_ub(kv) + rows <= kv->cap, CS_E_CAPACITY,
+    if (kv_max_ub(kv) + rows > kv->limit) CS_TRY(kv_sync_lengths(kv));
+    CS_REQUIRE(kv_max_ub(kv) + rows <= kv->limit, CS_E_CAPACITY,
                "KV cache full: length %lld + %d rows > capacity %lld", (long long)kv_max_ub(kv), rows,
-               (long long)kv->cap);
+               (long long)kv->limit);
     return CS_OK;
 }
 
@@ -647,7 +648,7 @@ extern "C" int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int3
     CS_REQUIRE(kv->B == 1 && stream_idx == 0, CS_E_UNSUPPORTED,
                "cs_prefill supports single-stream caches only");
     CS_REQUIRE(prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
-    CS_REQUIRE(prompt_len - 1 <= kv->cap, CS_E_CAPACITY, "prompt longer than the cache");
+    CS_REQUIRE(prompt_len - 1 <= kv->limit, CS_E_CAPACITY, "prompt longer than the cache");
     for (int64_t i = 0; i < prompt_len; ++i)
         CS_REQUIRE(prompt[i] >= 0 && prompt[i] < m->cfg.vocab, CS_E_ARG,
                    "prompt token %lld out of vocabulary", (long long)i);
@@ -674,8 +675,8 @@ static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t pr
     CS_TRY(check_verify_args(m, kv, k));
     CS_REQUIRE(kv->B == 1, CS_E_UNSUPPORTED, "cs_decode needs a single-stream cache");
     CS_REQUIRE(prompt && prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
-    CS_REQUIRE(prompt_len + max_new + k + 1 <= kv->cap, CS_E_CAPACITY,
-               "cache capacity %lld < prompt_len + max_new + k + 1", (long long)kv->cap);
+    CS_REQUIRE(prompt_len + max_new + k + 1 <= kv->limit, CS_E_CAPACITY,
+               "cache capacity %lld < prompt_len + max_new + k + 1", (long long)kv->limit);
     cs_stats st = {0, 0, 0, 0};
     *n_out = 0;
     CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));
@@ -752,7 +753,7 @@ static int check_prompts(const cs_model* m, const cs_kv* kv, const int32_t* prom
     for (int b = 0; b < kv->B; ++b) {
         CS_REQUIRE(prompt_len[b] >= 1, CS_E_ARG, "prompt %d must hold at least one token", b);
         CS_REQUIRE(prompt_len[b] <= stride, CS_E_ARG, "prompt %d is longer than prompt_stride", b);
-        CS_REQUIRE(prompt_len[b] - 1 <= kv->cap, CS_E_CAPACITY, "prompt %d longer than the cache", b);
+        CS_REQUIRE(prompt_len[b] - 1 <= kv->limit, CS_E_CAPACITY, "prompt %d longer than the cache", b);
         max_len = prompt_len[b] > max_len ? prompt_len[b] : max_len;
         for (int64_t i = 0; i < prompt_len[b]; ++i) {
             const int32_t t = prompts[(int64_t)b * stride + i];
@@ -824,8 +825,8 @@ extern "C" int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, i
     const int B = kv->B;
     int64_t max_len = 0;
     CS_TRY(check_prompts(m, kv, prompts, prompt_stride, prompt_len, &max_len));
-    CS_REQUIRE(max_len + max_new + k + 1 <= kv->cap, CS_E_CAPACITY,
-               "cache capacity %lld < longest prompt + max_new + k + 1", (long long)kv->cap);
+    CS_REQUIRE(max_len + max_new + k + 1 <= kv->limit, CS_E_CAPACITY,
+               "cache capacity %lld < longest prompt + max_new + k + 1", (long long)kv->limit);
     std::vector<cs_stats> st((size_t)B, cs_stats{0, 0, 0, 0});
     std::vector<int64_t> emitted((size_t)B, 0);
     std::vector<char> active((size_t)B, max_new > 0 ? 1 : 0);
@@ -920,10 +921,10 @@ extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv
     CS_REQUIRE(kv->B == 1 && dkv->B == 1, CS_E_UNSUPPORTED, "cs_decode_merged needs single-stream caches");
     CS_REQUIRE(prompt && prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
     const int kmax = k > delta ? k : delta;
-    CS_REQUIRE(prompt_len + max_new + kmax + 1 <= kv->cap, CS_E_CAPACITY,
-               "target cache capacity %lld < prompt_len + max_new + max(k, delta) + 1", (long long)kv->cap);
-    CS_REQUIRE(prompt_len + max_new + delta + 1 <= dkv->cap, CS_E_CAPACITY,
-               "draft cache capacity %lld < prompt_len + max_new + delta + 1", (long long)dkv->cap);
+    CS_REQUIRE(prompt_len + max_new + kmax + 1 <= kv->limit, CS_E_CAPACITY,
+               "target cache capacity %lld < prompt_len + max_new + max(k, delta) + 1", (long long)kv->limit);
+    CS_REQUIRE(prompt_len + max_new + delta + 1 <= dkv->limit, CS_E_CAPACITY,
+               "draft cache capacity %lld < prompt_len + max_new + delta + 1", (long long)dkv->limit);
     cs_merged_stats st = {0, 0, 0, 0, 0, 0, 0, 0};
     *n_out = 0;
     CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));

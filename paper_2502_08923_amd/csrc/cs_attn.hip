@@ -13,7 +13,7 @@
 //   O^T[hd][qrow]   += V^T[hd][token] * P^T[token][qrow]                         A = V^T rows
 // K rows are fed in a permuted token order chosen so that the S^T accumulator layout of two
 // 16-token tiles is exactly the B-operand layout of the PV product (8 consecutive tokens per
-// lane); V is cached transposed (token index contiguous) so its A operand is one 16-byte
+// lane); V is cached transposed in 128-token blocks (token index contiguous) so its A operand is one 16-byte
 // load per lane.  Softmax runs online in float32 (base 2), the row maximum is shared by the
 // four lanes that hold a query row, and O is only rescaled when some maximum moved.
 // The token range of a stream is split over workgroups, whose waves take its 32-token blocks in
@@ -93,8 +93,7 @@ __global__ __launch_bounds__(PA_THREADS) void k_attn_plain(const QT* __restrict_
         const float lc = block_sum(lsum, wred);   // its barriers also publish sc[]
         l_run = l_run * alpha + lc;
         float acc = 0.f;
-        const WT* __restrict__ vr = V + (int64_t)d * cap + c0;
-        for (int t = part; t < cn; t += nparts) acc += sc[t] * cs_ld(vr, t);
+        for (int t = part; t < cn; t += nparts) acc += sc[t] * cs_ld(V, cs_v_index(c0 + t, d, hd));
         o = o * alpha + acc;
         m_run = m_new;
         __syncthreads();
@@ -262,8 +261,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                 head_pair(b * rows + i, H + KVH + kvh, sg * 8, false, lo, hi);
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    Vw[(int64_t)(sg * 8 + u) * cap + pos] = lo[u];
-                    Vw[(int64_t)(HALF + sg * 8 + u) * cap + pos] = hi[u];
+                    Vw[cs_v_index(pos, sg * 8 + u, HD)] = lo[u];
+                    Vw[cs_v_index(pos, HALF + sg * 8 + u, HD)] = hi[u];
                 }
             }
         }
@@ -315,7 +314,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
         if (t0 >= limit) return;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            buf.v[mt] = *reinterpret_cast<const bf16x8*>(V + (int64_t)(mt * 16 + c) * cap + t0 + 8 * g);
+            buf.v[mt] = *reinterpret_cast<const bf16x8*>(V + cs_v_index(t0 + 8 * g, mt * 16 + c, HD));
     };
 
     auto compute = [&](fa_kbuf<HD>& kb, fa_vbuf<HD>& vb, int t0, auto tail_tag) {
@@ -615,7 +614,7 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
             }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                vr[slot][mt] = *reinterpret_cast<const bf16x8*>(V + (int64_t)(mt * 16 + c) * cap + t0 + 8 * g);
+                vr[slot][mt] = *reinterpret_cast<const bf16x8*>(V + cs_v_index(t0 + 8 * g, mt * 16 + c, HD));
         };
         auto store = [&](int slot, int st, int blk) {
             const int t0 = (nblocks > 0 ? t_begin : 0) + (blk < nblocks ? blk : (nblocks > 0 ? nblocks - 1 : 0)) * TSTEP;
@@ -995,9 +994,9 @@ __global__ __launch_bounds__(PF_THREADS) void k_attn_prefill(const bf16_t* __res
             sbase[u] = K + (id % KS) * 32;
             tstep[u] = HD;
         } else {
-            voff[u] = (unsigned)((((int64_t)((id - 2 * KS) * 16 + c)) * cap + 8 * g) * 2);
+            voff[u] = (unsigned)((((id - 2 * KS) * 16 + c) * CS_VBLK + 8 * g) * 2);
             sbase[u] = V;
-            tstep[u] = 1;
+            tstep[u] = 0;                               // V: the block address is not linear in t0, see issue
         }
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)&stage[0][0];
@@ -1006,7 +1005,9 @@ __global__ __launch_bounds__(PF_THREADS) void k_attn_prefill(const bf16_t* __res
         const int t0 = (blk < nblocks ? blk : nblocks - 1) * 32;
 #pragma unroll
         for (int u = 0; u < LD; ++u)
-            cs_load_to_lds(voff[u], sbase[u] + (int64_t)t0 * tstep[u], lds0 + st * STAGE_BYTES + (wave_s + PF_WAVES * u) * 1024);
+            cs_load_to_lds(voff[u],
+                           tstep[u] ? sbase[u] + (int64_t)t0 * tstep[u] : sbase[u] + cs_v_index(t0, 0, HD),
+                           lds0 + st * STAGE_BYTES + (wave_s + PF_WAVES * u) * 1024);
     };
     // at most `n` of this wave's requests still in flight, then meet the other waves
 #define PF_SYNC(n) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(n) : "memory")

@@ -109,9 +109,10 @@ struct cs_model {
 struct cs_kv {
     const cs_model* m;
     int B;
-    int64_t cap;        // positions per stream (multiple of 64)
+    int64_t cap;        // allocated positions per stream (multiple of 128): the pitch of the caches
+    int64_t limit;      // positions a stream may use: the requested capacity rounded up to 64
     void* k;            // [layer][B][KVH][cap][hd]
-    void* v;            // [layer][B][KVH][hd][cap]   (token index contiguous)
+    void* v;            // [layer][B][KVH][cap/128][hd][128]  (cs_v_index: 128-token blocks, token index contiguous)
     int32_t* d_len;     // device [B]
     int64_t* h_len_ub;  // host [B] upper bound of each length
 };
@@ -176,6 +177,16 @@ __host__ __device__ __forceinline__ int64_t cs_xt_index(int r, int k, int K) {
 static inline size_t cs_xt_bytes(int64_t R, int64_t K) { return (size_t)((R + 15) / 16) * (K >> 5) * 1024; }
 // row-major f16 [R][K] -> that layout (single operations and tests)
 int cs_tile_x_launch(const void* src, void* dst, int R, int K, hipStream_t s);
+
+// V cache of one (stream, KV head): element (token t, feature d) of [cap/128][hd][128].  Within a
+// block of 128 tokens every feature row is contiguous in the token index (what the PV product's
+// A operand wants), and the 128 feature rows of a block are one contiguous 128*hd-element region
+// (what the memory system wants: a workgroup walking the tokens reads 32 KB regions instead of
+// hd runs a whole cache row apart).
+#define CS_VBLK 128
+__host__ __device__ __forceinline__ int64_t cs_v_index(int64_t t, int d, int hd) {
+    return ((t >> 7) * hd + d) * CS_VBLK + (t & (CS_VBLK - 1));
+}
 
 // bf16 weights of the tuned GEMM live in MFMA fragment order (see cs_gemm.hip)
 int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int rowmap, int N_total,

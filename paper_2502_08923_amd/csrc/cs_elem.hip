@@ -115,7 +115,7 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
 // -------------------------------------------------------------------------------------
 // rotary + KV append.  qkv[r] = sum_p part[p][r][:] holds q heads, k heads, v heads.
 // q -> rotated, stored [R][H][hd] (QT); k -> rotated, rounded to the cache type, stored at
-// cache row kv_len[b]+i; v -> stored transposed (token index contiguous).
+// cache row kv_len[b]+i; v -> stored transposed in 128-token blocks (cs_v_index).
 // -------------------------------------------------------------------------------------
 template <typename WT, typename QT>
 __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qkv, int nparts,
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qk
         } else {
             const int g = head - H - KVH;
             WT* __restrict__ base = vc + ((int64_t)b * KVH + g) * hd * cap;
-            cs_st(base, (int64_t)j * cap + pos, a);
-            cs_st(base, (int64_t)(j + half) * cap + pos, c);
+            cs_st(base, cs_v_index(pos, j, hd), a);
+            cs_st(base, cs_v_index(pos, j + half, hd), c);
         }
     }
 }
@@ -164,8 +164,8 @@ __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qk
 // The same for blocks of many rows (wide verify blocks, prompt blocks), bf16 cache and queries:
 // a workgroup takes RA_ROWS consecutive block rows of one head, every thread four adjacent
 // elements of both rotary halves (16-byte loads of the partial tiles, 8-byte stores), and the V
-// rows, whose cache keeps the token index contiguous, go through an LDS tile so that the rows
-// of a workgroup are written as runs of consecutive tokens instead of one element per line.
+// rows, whose cache keeps the token index contiguous (cs_v_index), go through an LDS tile so that
+// the rows of a workgroup are written as runs of consecutive tokens instead of one element per line.
 #define RA_ROWS 32
 #define RA_THREADS 256
 __global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
     const int b = live ? r / rows : 0, i = live ? r % rows : 0;
     const int64_t pos = live ? (int64_t)kv_len[b] + i : 0;
     const bool is_v = head >= H + KVH;
-    if (is_v && t8 == 0) voff[rr] = live ? ((int64_t)b * KVH + (head - H - KVH)) * hd * cap + pos : -1;
+    if (is_v && t8 == 0) voff[rr] = live ? ((int64_t)b * KVH + (head - H - KVH)) * hd * cap + cs_v_index(pos, 0, hd) : -1;
     if (live) {
         for (int j = t8 * 4; j < half; j += 32) {
             const int64_t i0 = (int64_t)r * nq + (int64_t)head * hd + j;
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
     const int tok = threadIdx.x & (RA_ROWS - 1);
     const int64_t off = voff[tok];
     if (off < 0) return;
-    for (int d = threadIdx.x / RA_ROWS; d < hd; d += RA_THREADS / RA_ROWS) vc[off + (int64_t)d * cap] = vt[d][tok];
+    for (int d = threadIdx.x / RA_ROWS; d < hd; d += RA_THREADS / RA_ROWS) vc[off + (int64_t)d * CS_VBLK] = vt[d][tok];
 }
 
 // -------------------------------------------------------------------------------------
