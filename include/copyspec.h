@@ -21,10 +21,14 @@
  *     thread-local description of the most recent failure.  On an argument or capacity
  *     error nothing has been modified.
  *   - Calls on one handle are not re-entrant; calls that share a handle on different
- *     streams race.  The match scans (cs_find_match*, cs_step and the decode loops) keep
- *     their per-chunk results in one library-owned device buffer per process (grown on
- *     demand, which synchronises the device): scans enqueued on different streams must
- *     not overlap in time.  The instrumentation (cs_profile_*) is process-wide too.
+ *     streams race.  Different handles are independent: each cs_kv carries the scratch of its
+ *     own match scans, each cs_model its own workspace, so two models with their caches may
+ *     step on two streams (or from two threads) at the same time.  The handle-less
+ *     cs_find_match_batch_dev keeps one scratch buffer per (device, stream) it was ever called
+ *     on: calls on different streams may overlap, calls on one stream are ordered by it.  That
+ *     buffer is allocated by the first call on a stream and replaced by a larger one when a
+ *     later call needs it (which waits for that stream only); buffers live until the process
+ *     ends.  Only the instrumentation (cs_profile_*) is process-wide.
  */
 #ifndef COPYSPEC_H
 #define COPYSPEC_H
@@ -54,7 +58,7 @@ const char* cs_version(void);
 
 /* ------------------------------------------------------------------------------------
  * Match search and draft extraction  (Sec. 3.1; Sec. 3.2 first paragraph and footnote;
- * App. B.1 "Match location p", "Chunk size m"; App. B.3 step 1)
+ * App. B.1, the definitions of the match location p and the chunk size m; App. B.3 step 1)
  *
  *   M = { p : 0 <= p <= n - 2*gamma  and  h[p+j] == h[n-gamma+j] for all 0 <= j < gamma }
  *
@@ -84,15 +88,17 @@ int cs_find_match_ex(const int32_t* history /*host [len]*/, int64_t len, int32_t
 /* B histories resident on the device: stream b is d_hist[b*stride .. b*stride + d_len[b]).
  * Outputs (device): d_match_pos[B] (may be NULL), d_src_pos[B] (may be NULL),
  * d_draft[B][k], d_draft_len[B].  Requires 1 <= gamma <= 16, 0 <= k <= 256, B >= 0,
- * stride >= every length.  B == 0 is a no-op.  Asynchronous on `stream`. */
+ * stride >= every length, B <= 65535.  B == 0 is a no-op.  Asynchronous on `stream` (see the
+ * conventions above for its scratch buffer). */
 int cs_find_match_batch_dev(const int32_t* d_hist /*device*/, int64_t stride,
                             const int32_t* d_len /*device [B]*/, int32_t B, int32_t gamma,
                             int32_t k, int32_t policy, int32_t* d_match_pos, int32_t* d_src_pos,
                             int32_t* d_draft, int32_t* d_draft_len, void* stream);
 
 /* ------------------------------------------------------------------------------------
- * Gamma-gram index  (Sec. 3.1: "a dictionary of all gamma-token subsequences and their
- * locations, updated as tokens are appended"; App. B.1 "Dictionary D"; App. B.3 steps 1b, 2d)
+ * Gamma-gram index  (Sec. 3.1: the dictionary that maps every gamma-token subsequence to the
+ * places where it occurs and grows with the sequence; App. B.1, dictionary D; App. B.3 steps
+ * 1b and 2d)
  *
  * The paper's own data structure as an alternative to the scan, for very long histories:
  * one hash table per stream on the device, keyed by the gamma tokens themselves (entries
@@ -202,8 +208,11 @@ int cs_verify(cs_model* m, cs_kv* kv, const int32_t* d_pending /*[B]*/,
  * One whole copy-and-verify step on device-resident state  (App. B.3 steps 1, 2, 4)
  *
  * d_hist[b*stride .. +d_hist_len[b]) is the token sequence of stream b (prompt plus
- * everything emitted, Sec. 3.2 third paragraph); its last token is the pending token and
- * kv length must be d_hist_len[b] - 1.  The call searches each history (gamma, policy),
+ * everything emitted, Sec. 3.2 third paragraph); its last token is the pending token.
+ * Contract: d_hist_len[b] >= 1 and the cache length of stream b equals d_hist_len[b] - 1 (the
+ * cache holds every token but the pending one).  The library cannot check this without a host
+ * round trip; a history longer than that is still searched in full, but the block is placed at
+ * the cache length, not at the history length.  The call searches each history (gamma, policy),
  * drafts up to k tokens, clamps the draft to d_room[b] - 1 if d_room != NULL (room =
  * tokens the stream may still emit), verifies, then appends draft[0..tau) and next to the
  * history and advances d_hist_len[b] by tau+1 and d_room[b] by -(tau+1).  A stream with
@@ -225,7 +234,7 @@ typedef struct cs_stats {
 } cs_stats;
 
 /* ------------------------------------------------------------------------------------
- * Decode loops  (Sec. 3.2; App. B.3 step 4 "repeat until a stopping criterion")
+ * Decode loops  (Sec. 3.2; App. B.3 step 4: the procedure repeats until a stopping criterion)
  *
  * cs_decode: stream 0 of `kv` is reset, the prompt (host, >= 1 token) is run through the
  * model in blocks, then cs_step repeats until exactly max_new tokens are emitted or
@@ -356,12 +365,13 @@ void cs_profile_enable(int32_t class_mask);
 void cs_profile_reset(void);
 int cs_profile_read(int32_t cls, double* total_ms, int64_t* launches);
 
-/* Select kernel variants for the following cs_model_create calls: 0 = tuned kernels where
- * the shape allows (default), 1 = plain reference kernels everywhere. */
+/* Select kernel variants for the following cs_model_create calls of the calling thread (the
+ * setting is thread-local and read at creation only): 0 = tuned kernels where the shape allows
+ * (default), 1 = plain reference kernels everywhere. */
 void cs_set_plain_kernels(int32_t on);
 
-/* Rows of one prompt block for the following cs_model_create calls (the workspace of a model is
- * sized for it): cs_prefill ingests a prompt `rows` tokens at a time, cs_prefill_batch gives each
+/* Rows of one prompt block for the following cs_model_create calls of the calling thread
+ * (thread-local, read at creation only; the workspace of a model is sized for it): cs_prefill ingests a prompt `rows` tokens at a time, cs_prefill_batch gives each
  * stream its share of them.  0 = the default (4096); other values are clamped to 16..8192.
  * A model whose max_k + 1 is larger uses that.  Results do not depend on it beyond rounding. */
 void cs_set_prompt_block_rows(int32_t rows);

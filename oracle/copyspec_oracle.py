@@ -129,7 +129,7 @@ def find_match_np(h, gamma: int, k: int, policy: str = "rightmost"):
 
 
 class GammaGramDict:
-    """The paper's own data structure (Sec. 3.1, App. B.1 "Dictionary D"): a hash map
+    """The paper's own data structure (Sec. 3.1; the dictionary D of App. B.1): a hash map
     from every gamma-token subsequence to the positions where it starts, updated as
     tokens are appended (App. B.3 step 2d).  Used as a second, independently written
     formulation of the match search."""

@@ -22,7 +22,7 @@ void cs_set_error(const char* fmt, ...) {
 extern "C" const char* cs_last_error(void) { return g_err; }
 extern "C" const char* cs_version(void) { return "copyspec-gfx950 0.1"; }
 
-static int g_plain = 0;
+static thread_local int g_plain = 0;
 extern "C" void cs_set_plain_kernels(int32_t on) { g_plain = on ? 1 : 0; }
 
 // Rows of one prompt block.  With thousands of rows the projections of a block are compute-bound
@@ -30,7 +30,7 @@ extern "C" void cs_set_plain_kernels(int32_t on) { g_plain = on ? 1 : 0; }
 // measured at the 8B shape, a prompt goes in 65 % faster in 4096-row blocks than in 512-row
 // blocks (2048: 4 % slower than 4096; 6144 and 8192: no faster).
 #define CS_PROMPT_BLOCK_ROWS 4096
-static int g_prompt_rows = 0;
+static thread_local int g_prompt_rows = 0;
 extern "C" void cs_set_prompt_block_rows(int32_t rows) {
     g_prompt_rows = rows <= 0 ? 0 : (rows < 16 ? 16 : (rows > 8192 ? 8192 : rows));
 }
@@ -115,7 +115,8 @@ __global__ void k_v_transpose(T* __restrict__ cache, T* __restrict__ rows, int64
 __global__ void k_pending(const int32_t* __restrict__ hist, int64_t stride,
                           const int32_t* __restrict__ hist_len, int B, int32_t* __restrict__ pending) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B) pending[b] = hist[(int64_t)b * stride + hist_len[b] - 1];
+    // (an empty history has no pending token: token 0 keeps the block well-formed)
+    if (b < B) pending[b] = hist_len[b] >= 1 ? hist[(int64_t)b * stride + hist_len[b] - 1] : 0;
 }
 
 __global__ void k_add_i32(int32_t* p, int32_t v, int n) {
@@ -329,6 +330,9 @@ extern "C" int cs_kv_create(const cs_model* m, int32_t batch, int64_t capacity, 
     if (rc == CS_OK) rc = dev_alloc(&kv->k, bytes);
     if (rc == CS_OK) rc = dev_alloc(&kv->v, bytes);
     if (rc == CS_OK) rc = dev_alloc((void**)&kv->d_len, (size_t)batch * 4);
+    // a history is one token longer than its cache, so the scan of cs_step sees at most limit+1 tokens
+    kv->scan_slots = cs_scan_slots(kv->limit + 1);
+    if (rc == CS_OK) rc = dev_alloc((void**)&kv->scan_keys, (size_t)batch * kv->scan_slots * sizeof(int64_t));
     // dead rows must hold finite numbers (they are multiplied by zero probabilities)
     if (rc == CS_OK && hipMemset(kv->k, 0, bytes) != hipSuccess) rc = CS_E_DEVICE;
     if (rc == CS_OK && hipMemset(kv->v, 0, bytes) != hipSuccess) rc = CS_E_DEVICE;
@@ -349,6 +353,7 @@ extern "C" void cs_kv_destroy(cs_kv* kv) {
     if (kv->k) (void)hipFree(kv->k);
     if (kv->v) (void)hipFree(kv->v);
     if (kv->d_len) (void)hipFree(kv->d_len);
+    if (kv->scan_keys) (void)hipFree(kv->scan_keys);
     free(kv->h_len_ub);
     free(kv);
 }
@@ -436,7 +441,7 @@ extern "C" int cs_kv_read(cs_kv* kv, int32_t layer, int32_t b, int64_t pos0, int
 // -------------------------------------------------------------------------------------
 // match search entry points
 // -------------------------------------------------------------------------------------
-static int check_scan_args(int gamma, int k, int policy) {
+int cs_check_scan_args(int gamma, int k, int policy) {
     CS_REQUIRE(gamma >= 1 && gamma <= 16, CS_E_ARG, "gamma must be in 1..16 (got %d)", gamma);
     CS_REQUIRE(k >= 0 && k <= 256, CS_E_ARG, "k must be in 0..256 (got %d)", k);
     CS_REQUIRE(policy == CS_POLICY_RIGHTMOST || policy == CS_POLICY_FIRST || policy == CS_POLICY_CONTEXT,
@@ -448,32 +453,39 @@ extern "C" int cs_find_match_batch_dev(const int32_t* d_hist, int64_t stride, co
                                        int32_t B, int32_t gamma, int32_t k, int32_t policy,
                                        int32_t* d_match_pos, int32_t* d_src_pos, int32_t* d_draft,
                                        int32_t* d_draft_len, void* stream) {
-    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
     CS_REQUIRE(B >= 0, CS_E_ARG, "B must be >= 0");
     if (B == 0) return CS_OK;
     CS_REQUIRE(d_hist && d_len && d_draft_len && (d_draft || k == 0), CS_E_ARG,
                "cs_find_match_batch_dev: NULL pointer");
-    CS_REQUIRE(stride >= 1 && stride < (int64_t)1 << 31, CS_E_ARG, "stride out of range");
-    return cs_scan_launch(d_hist, stride, d_len, B, gamma, k, policy, stride, d_match_pos, d_src_pos,
+    CS_REQUIRE(stride >= 1 && stride <= CS_MAX_STRIDE, CS_E_ARG, "stride out of range");
+    CS_REQUIRE(B <= 65535, CS_E_ARG, "at most 65535 histories per call");
+    const int nslots = cs_scan_slots(stride);
+    int64_t* keys = nullptr;
+    CS_TRY(cs_scan_stream_keys((size_t)B * nslots, (hipStream_t)stream, &keys));
+    return cs_scan_launch(d_hist, stride, d_len, B, gamma, k, policy, keys, nslots, d_match_pos, d_src_pos,
                           d_draft, d_draft_len, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int cs_find_match_ex(const int32_t* history, int64_t len, int32_t gamma, int32_t k,
                                 int32_t policy, int64_t* match_pos, int64_t* src_pos, int32_t* draft,
                                 int32_t* draft_len) {
-    CS_TRY(check_scan_args(gamma, k, policy));
-    CS_REQUIRE(len >= 0 && len < (int64_t)1 << 31, CS_E_ARG, "history length out of range");
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
+    CS_REQUIRE(len >= 0 && len <= CS_MAX_STRIDE, CS_E_ARG, "history length out of range");
     CS_REQUIRE(history || len == 0, CS_E_ARG, "cs_find_match: NULL history");
     int32_t out[3] = {-1, -1, 0};
     std::vector<int32_t> hdraft((size_t)(k > 0 ? k : 1), -1);
     if (len >= 2 * (int64_t)gamma) {
         const int64_t stride = cs_round_up(len, 4);
         int32_t* d = nullptr;
-        const size_t words = (size_t)stride + 4 + (size_t)(k > 0 ? k : 1);
-        CS_HIP(hipMalloc(&d, words * 4));
+        // history | len, match, src, draft_len | draft | per-chunk keys (8-byte aligned)
+        const int nslots = cs_scan_slots(len);
+        const size_t words = (size_t)cs_round_up(stride + 4 + (k > 0 ? k : 1), 2);
+        CS_HIP(hipMalloc(&d, words * 4 + (size_t)nslots * sizeof(int64_t)));
         int32_t* d_len = d + stride;
         int32_t* d_out = d_len + 1;         // match, src, draft_len
         int32_t* d_draft = d_out + 3;
+        int64_t* d_keys = reinterpret_cast<int64_t*>(d + words);
         const int32_t n32 = (int32_t)len;
         int rc = CS_OK;
         if (hipMemcpy(d, history, (size_t)len * 4, hipMemcpyHostToDevice) != hipSuccess ||
@@ -482,8 +494,8 @@ extern "C" int cs_find_match_ex(const int32_t* history, int64_t len, int32_t gam
             rc = CS_E_DEVICE;
         }
         if (rc == CS_OK)
-            rc = cs_scan_launch(d, stride, d_len, 1, gamma, k, policy, len, d_out, d_out + 1, d_draft,
-                                d_out + 2, nullptr, nullptr);
+            rc = cs_scan_launch(d, stride, d_len, 1, gamma, k, policy, d_keys, nslots, d_out, d_out + 1,
+                                d_draft, d_out + 2, nullptr, nullptr);
         if (rc == CS_OK && (hipMemcpy(out, d_out, 12, hipMemcpyDeviceToHost) != hipSuccess ||
                             (k > 0 && hipMemcpy(hdraft.data(), d_draft, (size_t)k * 4,
                                                 hipMemcpyDeviceToHost) != hipSuccess))) {
@@ -515,6 +527,12 @@ static int64_t kv_max_ub(const cs_kv* kv) {
     int64_t mx = 0;
     for (int b = 0; b < kv->B; ++b) mx = kv->h_len_ub[b] > mx ? kv->h_len_ub[b] : mx;
     return mx;
+}
+
+// key slots per stream for a scan of this cache's histories (one token longer than the cache rows)
+static int kv_scan_slots(const cs_kv* kv) {
+    const int want = cs_scan_slots(kv_max_ub(kv) + 1);
+    return want < kv->scan_slots ? want : kv->scan_slots;
 }
 
 // every stream must have room for `rows` more rows; refreshes the host bounds if needed
@@ -615,9 +633,9 @@ extern "C" int cs_step(cs_model* m, cs_kv* kv, int32_t* d_hist, int64_t stride, 
                        int32_t* d_accepted_len, int32_t* d_next_token, int32_t* d_draft_len_out,
                        void* stream) {
     CS_TRY(check_verify_args(m, kv, k));
-    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
     CS_REQUIRE(d_hist && d_hist_len && d_accepted_len && d_next_token, CS_E_ARG, "cs_step: NULL pointer");
-    CS_REQUIRE(stride >= 1 && stride < (int64_t)1 << 31, CS_E_ARG, "stride out of range");
+    CS_REQUIRE(stride >= 1 && stride <= CS_MAX_STRIDE, CS_E_ARG, "stride out of range");
     hipStream_t s = (hipStream_t)stream;
     const int B = kv->B;
     CS_TRY(kv_check_room(kv, k + 1));
@@ -625,8 +643,8 @@ extern "C" int cs_step(cs_model* m, cs_kv* kv, int32_t* d_hist, int64_t stride, 
     CS_REQUIRE(kv_max_ub(kv) + 1 + k + 1 <= stride, CS_E_CAPACITY,
                "history buffer (stride %lld) may overflow", (long long)stride);
     if (k > 0) {
-        CS_TRY(cs_scan_launch(d_hist, stride, d_hist_len, B, gamma, k, policy, kv_max_ub(kv) + 1,
-                              m->match_pos, nullptr, m->draft, m->draft_len, d_room, s));
+        CS_TRY(cs_scan_launch(d_hist, stride, d_hist_len, B, gamma, k, policy, kv->scan_keys,
+                              kv_scan_slots(kv), m->match_pos, nullptr, m->draft, m->draft_len, d_room, s));
     } else {
         CS_TRY(cs_fill_i32_launch(m->draft_len, 0, B, s));
     }
@@ -732,7 +750,7 @@ static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t pr
 extern "C" int cs_decode(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t prompt_len,
                          int64_t max_new, int32_t gamma, int32_t k, int32_t policy, int32_t eos_id,
                          int32_t* out_tokens, int64_t* n_out, cs_stats* stats) {
-    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
     return decode_impl(m, kv, prompt, prompt_len, max_new, gamma, k, policy, eos_id, out_tokens, n_out,
                        stats);
 }
@@ -820,7 +838,7 @@ extern "C" int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, i
                                cs_stats* stats) {
     CS_REQUIRE(out_tokens && n_out, CS_E_ARG, "cs_decode_batch: NULL output");
     CS_REQUIRE(max_new >= 0, CS_E_ARG, "max_new must be >= 0");
-    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
     CS_TRY(check_verify_args(m, kv, k));
     const int B = kv->B;
     int64_t max_len = 0;
@@ -910,7 +928,7 @@ extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv
                                 int64_t* n_out, cs_merged_stats* stats) {
     CS_REQUIRE(out_tokens && n_out, CS_E_ARG, "cs_decode_merged: NULL output");
     CS_REQUIRE(max_new >= 0, CS_E_ARG, "max_new must be >= 0");
-    CS_TRY(check_scan_args(gamma, k, policy));
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
     CS_TRY(check_verify_args(m, kv, k));
     CS_REQUIRE(dm && dkv && dkv->m == dm, CS_E_ARG, "cs_decode_merged: draft model and its cache do not match");
     CS_REQUIRE(dm != m && dkv != kv, CS_E_ARG, "the draft model needs a model handle and a cache of its own");
@@ -954,8 +972,8 @@ extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv
         CS_REQUIRE(kv_max_ub(kv) + 1 + kmax + 1 <= stride, CS_E_CAPACITY, "history buffer may overflow");
         // step 1: copy opportunity
         if (k > 0) {
-            CS_TRY(cs_scan_launch(d, stride, d_len, 1, gamma, k, policy, n, m->match_pos, nullptr, m->draft,
-                                  m->draft_len, d_len + 1, s));
+            CS_TRY(cs_scan_launch(d, stride, d_len, 1, gamma, k, policy, kv->scan_keys, kv_scan_slots(kv),
+                                  m->match_pos, nullptr, m->draft, m->draft_len, d_len + 1, s));
             CS_HIP(hipMemcpy(&dl, m->draft_len, 4, hipMemcpyDeviceToHost));
         }
         k_pending<<<1, 64, 0, s>>>(d, stride, d_len, 1, m->pending);

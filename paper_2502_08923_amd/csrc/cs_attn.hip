@@ -247,8 +247,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
         };
         // first the new rows whose position lies in this workgroup's token range (4*Tw long):
         // their stores complete while the query tile is being built
-        bf16_t* __restrict__ Kw = fr.kc_w + ((int64_t)b * KVH + kvh) * cap * HD;
-        bf16_t* __restrict__ Vw = fr.vc_w + ((int64_t)b * KVH + kvh) * HD * cap;
+        bf16_t* Kw = fr.kc_w + ((int64_t)b * KVH + kvh) * cap * HD;
+        bf16_t* Vw = fr.vc_w + ((int64_t)b * KVH + kvh) * HD * cap;
         if (qg == 0) {
             for (int idx = tid; idx < rows * SEGS; idx += 256) {
                 const int i = idx / SEGS, sg = idx % SEGS;
@@ -300,22 +300,24 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
 
     // K tile a, MFMA row m=c  <->  token t0 + 8*(c/4) + 4a + c%4
     const int ktok0 = 8 * (c >> 2) + (c & 3);
-    auto load_k = [&](fa_kbuf<HD>& buf, int t0, int limit) {
+    auto load_k_from = [&](const bf16_t* Kb, fa_kbuf<HD>& buf, int t0, int limit) {
         if (t0 >= limit) return;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             // the four lanes of a token row read 64 contiguous bytes per k-step
-            const bf16_t* kp = K + (int64_t)(t0 + ktok0 + 4 * a) * HD + g * 8;
+            const bf16_t* kp = Kb + (int64_t)(t0 + ktok0 + 4 * a) * HD + g * 8;
 #pragma unroll
             for (int s = 0; s < KS; ++s) buf.k[a][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
         }
     };
-    auto load_v = [&](fa_vbuf<HD>& buf, int t0, int limit) {
+    auto load_v_from = [&](const bf16_t* Vb, fa_vbuf<HD>& buf, int t0, int limit) {
         if (t0 >= limit) return;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            buf.v[mt] = *reinterpret_cast<const bf16x8*>(V + cs_v_index(t0 + 8 * g, mt * 16 + c, HD));
+            buf.v[mt] = *reinterpret_cast<const bf16x8*>(Vb + cs_v_index(t0 + 8 * g, mt * 16 + c, HD));
     };
+    auto load_k = [&](fa_kbuf<HD>& buf, int t0, int limit) { load_k_from(K, buf, t0, limit); };
+    auto load_v = [&](fa_vbuf<HD>& buf, int t0, int limit) { load_v_from(V, buf, t0, limit); };
 
     auto compute = [&](fa_kbuf<HD>& kb, fa_vbuf<HD>& vb, int t0, auto tail_tag) {
         constexpr bool TAIL = decltype(tail_tag)::value;
@@ -447,11 +449,16 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
         }
     }
     // the few blocks that touch the new rows or the dead region: masked, not pipelined
+    // With the fused append the rows at and beyond L were written by this workgroup, above, through
+    // the writable cache pointers; K and V promise the compiler memory that nobody writes, so these
+    // blocks are read through pointers derived from the writable ones (after the barrier above).
+    const bf16_t* K_tail = fr.qkv ? fr.kc_w + ((int64_t)b * KVH + kvh) * cap * HD : K;
+    const bf16_t* V_tail = fr.qkv ? fr.vc_w + ((int64_t)b * KVH + kvh) * HD * cap : V;
     for (int t0 = t_tail; t0 < t_end; t0 += STEP) {
         fa_kbuf<HD> kt;
         fa_vbuf<HD> vt;
-        load_k(kt, t0, t_end);
-        load_v(vt, t0, t_end);
+        load_k_from(K_tail, kt, t0, t_end);
+        load_v_from(V_tail, vt, t0, t_end);
         compute(kt, vt, t0, tail_tag);
     }
     __syncthreads();             // every wave is done with the query tile: LDS changes hands

@@ -17,6 +17,8 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define CS_WAVE 64
+// longest history row (tokens): positions and their chunk-rounded bounds must fit an int32
+#define CS_MAX_STRIDE ((int64_t)0x7fffffff - 8192)
 
 // ---- error plumbing -----------------------------------------------------------------
 void cs_set_error(const char* fmt, ...);
@@ -115,6 +117,8 @@ struct cs_kv {
     void* v;            // [layer][B][KVH][cap/128][hd][128]  (cs_v_index: 128-token blocks, token index contiguous)
     int32_t* d_len;     // device [B]
     int64_t* h_len_ub;  // host [B] upper bound of each length
+    int64_t* scan_keys; // device [B][scan_slots]: per-chunk results of the match scan of cs_step
+    int scan_slots;
 };
 
 // ---- kernels' host launchers (defined in the .hip files) ------------------------------
@@ -123,10 +127,13 @@ int cs_gather_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len
                      int policy, const int64_t* d_keys, int nchunks, const int32_t* d_room,
                      int32_t* d_match_pos, int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
                      hipStream_t s);
+int cs_check_scan_args(int gamma, int k, int policy);     // CS_E_ARG with a message, or CS_OK
+int cs_scan_slots(int64_t max_len);
 int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B,
-                   int gamma, int k, int policy, int64_t max_len, int32_t* d_match_pos,
+                   int gamma, int k, int policy, int64_t* keys, int nslots, int32_t* d_match_pos,
                    int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
                    const int32_t* d_room, hipStream_t s);
+int cs_scan_stream_keys(size_t need, hipStream_t s, int64_t** out);
 
 // elementwise / small
 int cs_embed_launch(const cs_model* m, const int32_t* tok, int R, hipStream_t s);

@@ -1,6 +1,6 @@
 // Device-resident gamma-gram index: the paper's own data structure (Sec. 3.1: a map from
 // every gamma-token subsequence to where it occurs, updated as tokens are appended; App. B.1
-// "Dictionary D", App. B.3 steps 1b and 2d) as an alternative to the linear scan.
+// dictionary D, App. B.3 steps 1b and 2d) as an alternative to the linear scan.
 //
 // One open-addressing table per stream.  A slot is claimed by the first position whose gram
 // hashes there (`rep`, compare-and-swap); every later position with the same tokens (verified

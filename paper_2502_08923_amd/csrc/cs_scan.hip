@@ -12,6 +12,10 @@
 // ranks candidates by how many tokens before them agree with the tokens before the suffix
 // (the match-selection refinement the paper's Limitations section leaves open) and takes the
 // rightmost among equals.
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "cs_common.h"
 
 #define SCAN_THREADS 256
@@ -41,23 +45,24 @@ __device__ __forceinline__ bool rest_matches(const int32_t* __restrict__ h, int 
     return true;
 }
 
-// chunk_best[b][c] = best key in chunk c, -1 if none
+// chunk_best[b][s] = best key among the chunks s, s + gridDim.x, ... of stream b, -1 if none.
+// A workgroup walks its chunks with a stride of the grid width, so every candidate position is
+// visited whatever the number of slots the launch was given.
 template <int POLICY>
 __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict__ hist,
                                                        int64_t stride,
                                                        const int32_t* __restrict__ len, int gamma,
                                                        int vec_ok, int64_t* __restrict__ chunk_best,
-                                                       int nchunks) {
+                                                       int nslots) {
     const int b = blockIdx.y;
-    const int c = blockIdx.x;
     const int n = len[b];
     const int32_t* __restrict__ h = hist + (int64_t)b * stride;
     const int cnt = n - 2 * gamma + 1;            // candidate starts are 0 .. cnt-1
-    const int begin = c * SCAN_CHUNK;
     int64_t best = -1;
-    if (begin < cnt) {
-        const int end = min(cnt, begin + SCAN_CHUNK);
-        const int s0 = h[n - gamma];
+    const int s0 = cnt > 0 ? h[n - gamma] : 0;
+    for (int64_t begin64 = (int64_t)blockIdx.x * SCAN_CHUNK; begin64 < cnt; begin64 += (int64_t)nslots * SCAN_CHUNK) {
+        const int begin = (int)begin64;
+        const int end = (int)min((int64_t)cnt, begin64 + SCAN_CHUNK);
         // every lane runs every iteration (positions past the end just never hit), so the wave
         // stays converged for the cooperative context measurement
         for (int it = 0; it < SCAN_CHUNK / (SCAN_THREADS * 4); ++it) {
@@ -110,11 +115,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
         int64_t r = wave_best[0];
 #pragma unroll
         for (int w = 1; w < SCAN_THREADS / CS_WAVE; ++w) r = key_better<POLICY>(r, wave_best[w]);
-        chunk_best[(int64_t)b * nchunks + c] = r;
+        chunk_best[(int64_t)b * nslots + blockIdx.x] = r;
     }
 }
 
-// One wave per stream: reduce the chunk results, then copy the draft (App. B.1 "Chunk").
+// One wave per stream: reduce the chunk results, then copy the draft (App. B.1, the chunk that follows the match).
 __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist, int64_t stride,
                                                const int32_t* __restrict__ len, int gamma, int k,
                                                int policy, const int64_t* __restrict__ chunk_best,
@@ -148,41 +153,62 @@ __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist,
     for (int i = threadIdx.x; i < k; i += 64) draft[(int64_t)b * k + i] = i < dl ? h[src + i] : -1;
 }
 
-// library-owned scratch for the per-chunk results; grown on demand (synchronises then)
-static int64_t* g_chunk_best = nullptr;
-static size_t g_chunk_best_n = 0;
+// Number of key slots per stream a scan over histories of up to max_len tokens wants (one per
+// chunk).  Fewer slots are always correct (the workgroups then walk several chunks each).
+int cs_scan_slots(int64_t max_len) { return (int)cs_ceil_div(max_len > 0 ? max_len : 1, SCAN_CHUNK); }
 
+// keys: device scratch of B * nslots int64 (every slot is written by k_scan before k_gather reads
+// it, so it needs no clearing).  The caller says where it lives: a cache handle's own buffer, the
+// per-stream buffers below, or the static array of the entry point that allocates nothing.
 int cs_scan_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len, int B, int gamma,
-                   int k, int policy, int64_t max_len, int32_t* d_match_pos, int32_t* d_src_pos,
+                   int k, int policy, int64_t* keys, int nslots, int32_t* d_match_pos, int32_t* d_src_pos,
                    int32_t* d_draft, int32_t* d_draft_len, const int32_t* d_room, hipStream_t s) {
     if (B == 0) return CS_OK;
-    const int nchunks = (int)cs_ceil_div(max_len > 0 ? max_len : 1, SCAN_CHUNK);
-    const size_t need = (size_t)B * nchunks;
-    if (need > g_chunk_best_n) {
-        CS_HIP(hipDeviceSynchronize());
-        if (g_chunk_best) CS_HIP(hipFree(g_chunk_best));
-        g_chunk_best = nullptr;
-        g_chunk_best_n = 0;
-        CS_HIP(hipMalloc(&g_chunk_best, need * sizeof(int64_t)));
-        g_chunk_best_n = need;
-    }
+    CS_REQUIRE(keys && nslots >= 1 && B <= 65535, CS_E_ARG, "scan: no key buffer, or more than 65535 histories");
     const int vec_ok = ((reinterpret_cast<uintptr_t>(d_hist) & 15) == 0) && (stride % 4 == 0);
-    dim3 grid(nchunks, B);
+    dim3 grid(nslots, B);
     const int ps = cs_prof_begin(CS_PROF_SCAN, s);
     if (policy == CS_POLICY_RIGHTMOST)
-        k_scan<CS_POLICY_RIGHTMOST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
-                                                                 g_chunk_best, nchunks);
+        k_scan<CS_POLICY_RIGHTMOST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok, keys, nslots);
     else if (policy == CS_POLICY_FIRST)
-        k_scan<CS_POLICY_FIRST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
-                                                             g_chunk_best, nchunks);
+        k_scan<CS_POLICY_FIRST><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok, keys, nslots);
     else
-        k_scan<CS_POLICY_CONTEXT><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok,
-                                                               g_chunk_best, nchunks);
+        k_scan<CS_POLICY_CONTEXT><<<grid, SCAN_THREADS, 0, s>>>(d_hist, stride, d_len, gamma, vec_ok, keys, nslots);
     cs_prof_end(ps, s);
     CS_TRY(cs_launch_ok("k_scan"));
-    k_gather<<<B, 64, 0, s>>>(d_hist, stride, d_len, gamma, k, policy, g_chunk_best, nchunks, d_room,
+    k_gather<<<B, 64, 0, s>>>(d_hist, stride, d_len, gamma, k, policy, keys, nslots, d_room,
                               d_match_pos, d_src_pos, d_draft, d_draft_len);
     return cs_launch_ok("k_gather");
+}
+
+// Key buffers of the entry point that has no handle to keep one in (cs_find_match_batch_dev): one
+// per (device, stream) it was ever called on, so that scans enqueued on different streams never
+// share scratch and may overlap; calls on one stream are ordered by the stream.  A buffer is
+// allocated on the first call on its stream and replaced (after waiting for that stream only) when
+// a later call needs a larger one; buffers live until the process ends.
+struct scan_keys { int64_t* p; size_t n; };
+static std::mutex g_keys_mu;
+static std::map<std::pair<int, hipStream_t>, scan_keys> g_keys;
+
+int cs_scan_stream_keys(size_t need, hipStream_t s, int64_t** out) {
+    int dev = 0;
+    CS_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_keys_mu);
+    scan_keys& k = g_keys[std::make_pair(dev, s)];
+    if (need > k.n) {
+        size_t n = 4096;
+        while (n < need) n *= 2;
+        if (k.p) {
+            CS_HIP(hipStreamSynchronize(s));
+            (void)hipFree(k.p);
+            k.p = nullptr;
+            k.n = 0;
+        }
+        CS_HIP(hipMalloc(&k.p, n * sizeof(int64_t)));
+        k.n = n;
+    }
+    *out = k.p;
+    return CS_OK;
 }
 
 // draft gather alone, for callers that bring their own per-chunk keys (the gamma-gram index)

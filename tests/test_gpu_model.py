@@ -44,6 +44,17 @@ def tol_for(shape):
     return 1e-4 if shape.dtype == "f32" else 2e-2
 
 
+def _cache_rows_close(got, want, tol):
+    """Cache rows against the oracle's.  Before they are stored the two sides agree to the
+    activation tolerance `tol`; a bf16 cache then rounds each side to its own neighbour, which can
+    add one bf16 step of the value (2^-7 relative at most) when the two fall on different sides of
+    a rounding boundary.  float32 caches get no such allowance."""
+    got = got.float().cpu().numpy().astype(np.float64)
+    step = 2.0 ** -7 * np.abs(want) if tol > 1e-3 else 0.0
+    bad = np.abs(got - want) > tol + step
+    assert not bad.any(), float(np.abs(got - want).max())
+
+
 @pytest.fixture(scope="module")
 def tiny():
     w = synth.model_weights(synth.TINY, synth.seed_for(1), threads=8)
@@ -150,8 +161,8 @@ def test_long_prompt_goes_through_512_row_blocks(shape):
     tol = 2e-2 if shape.dtype == "bf16" else 1e-4
     for layer in range(shape.n_layers):
         k_rows, v_rows = kv.read(layer, 0, 0, 699)
-        assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :699]).max() < tol * 4
-        assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :699]).max() < tol * 4
+        _cache_rows_close(k_rows, okv.k[layer, :, :699], tol)
+        _cache_rows_close(v_rows, okv.v[layer, :, :699], tol)
     kv.destroy()
     model.destroy()
 
@@ -170,8 +181,8 @@ def test_long_prompt_goes_through_large_blocks(shape, block_rows, n):
     tol = 2e-2 if shape.dtype == "bf16" else 1e-4
     for layer in range(shape.n_layers):
         k_rows, v_rows = kv.read(layer, 0, 0, n - 1)
-        assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :n - 1]).max() < tol * 4
-        assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :n - 1]).max() < tol * 4
+        _cache_rows_close(k_rows, okv.k[layer, :, :n - 1], tol)
+        _cache_rows_close(v_rows, okv.v[layer, :, :n - 1], tol)
     kv.destroy()
     model.destroy()
 
@@ -258,13 +269,16 @@ def test_decode_invariance_bf16_models():
         prompt = g["tokens"].tolist()
         kv = cs.KV(model, 1, 400 + 96 + 16)
         greedy = cs.cs_decode_greedy(model, kv, prompt, 96)
+        strict = _follows_oracle(w, prompt, greedy, MARGIN, 400 + 96 + 16)
         for policy in ("rightmost", "first"):
             spec, st = cs.cs_decode(model, kv, prompt, 96, 3, 10, policy)
-            # identical kernels but different block shapes: compare up to the first
-            # position where plain greedy itself was decided by a sub-margin gap
-            n_same = next((i for i in range(96) if spec[i] != greedy[i]), 96)
-            assert len(spec) == 96 and n_same >= 48, (shape.name, policy, n_same)
-            assert st["attempts"] >= 1
+            assert len(spec) == 96 and st["attempts"] >= 1
+            # identical kernels but different block shapes: the two runs may part only where the
+            # oracle's own decision lies inside the margin.  Each run is followed by the oracle on
+            # its own prefix: every token must be the oracle's greedy token wherever the margin is
+            # safe, so a first difference between the runs can only sit at an unsafe position
+            strict += _follows_oracle(w, prompt, spec, MARGIN, 400 + 96 + 16)
+        assert strict >= 3 * 64, (shape.name, strict)       # most of the 3 x 96 decisions were strict
         kv.destroy()
         model.destroy()
 
@@ -373,8 +387,10 @@ def test_merged_decode_bf16_models_and_errors():
     kv, dkv = cs.KV(model, 1, 400 + 96 + 16), cs.KV(dmodel, 1, 400 + 96 + 16)
     greedy = cs.cs_decode_greedy(model, kv, prompt, 96)
     out, st = cs.cs_decode_merged(model, kv, dmodel, dkv, prompt, 96, 3, 10, 4)
-    n_same = next((i for i in range(96) if out[i] != greedy[i]), 96)     # see test_decode_invariance_bf16_models
-    assert len(out) == 96 and n_same >= 48, n_same
+    assert len(out) == 96
+    # both runs follow the oracle under the margin rule (see test_decode_invariance_bf16_models)
+    strict = _follows_oracle(w, prompt, greedy, MARGIN, 400 + 96 + 16) + _follows_oracle(w, prompt, out, MARGIN, 400 + 96 + 16)
+    assert strict >= 2 * 64, strict
     assert st["copy_attempts"] >= 1 and st["spec_attempts"] >= 1 and st["draft_forwards"] > st["spec_drafted"]
     with pytest.raises(cs.CopySpecError):        # the draft model needs handles of its own
         cs.cs_decode_merged(model, kv, model, kv, prompt, 8, 3, 10, 4)
@@ -487,8 +503,8 @@ def test_prefill_batch_and_decode_batch_bf16():
         for layer in range(shape.n_layers):
             if n > 1:
                 k_rows, v_rows = kv.read(layer, b, 0, n - 1)
-                assert np.abs(k_rows.float().cpu().numpy() - okv.k[layer, :, :n - 1]).max() < 8e-2
-                assert np.abs(v_rows.float().cpu().numpy() - okv.v[layer, :, :n - 1]).max() < 8e-2
+                _cache_rows_close(k_rows, okv.k[layer, :, :n - 1], 2e-2)
+                _cache_rows_close(v_rows, okv.v[layer, :, :n - 1], 2e-2)
     toks, stats = cs.cs_decode_batch(model, kv, prompts, new, 3, k)
     strict = 0
     for b in range(B):

@@ -90,8 +90,6 @@ def _gemm_case(host_model, N, K, R):
                                  (128256, 4096)])
 @pytest.mark.parametrize("R", [88, 528, 1])
 def test_gemm_bf16_full_shapes(host_model, N, K, R):
-    if R == 528 and N == 128256:
-        pytest.skip("covered at R=88 and, for the many-row kernel, by the row sweep below")
     _gemm_case(host_model, N, K, R)
 
 
@@ -133,12 +131,22 @@ def test_gemm_f32_plain(host_model):
 # block attention
 # ----------------------------------------------------------------------------------------
 
-def _attention_case(model, shape, lens, rows, sample, seed, poison=False, k_ramp=None):
+def _attention_case(model, shape, lens, rows, sample, seed, poison=False, k_ramp=None, device_fill=False):
+    """device_fill: streams the oracle does not look at get their cache rows from a device-side
+    generator (cheap at long lengths); sampled streams always get the seeded host rows."""
     B = len(lens)
     cap = max(lens) + rows + 5
     kv = cs.KV(model, B, cap)
     ks, vs = {}, {}
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
     for b, L in enumerate(lens):
+        if device_fill and b not in {sb for sb, _ in sample}:
+            shp = (shape.n_kv_heads, L + rows, shape.head_dim)
+            kv.load(0, b, 0, torch.randn(shp, generator=gen, device=DEV).bfloat16(),
+                    torch.randn(shp, generator=gen, device=DEV).bfloat16())
+            kv.set_len(b, L)
+            continue
         kr, vr = synth.random_kv(shape, L + rows, seed, 0, b)
         if k_ramp is not None:
             # keys scaled along the sequence: the scores, and with them the running maximum of
@@ -194,6 +202,23 @@ def test_attention_k32_block(host_model):
     """k = 32: 132 query rows per KV head, three query groups per workgroup column."""
     worst = _attention_case(host_model, HOST, [3000, 2999, 64, 7], 33,
                             [(0, 0), (0, 3), (1, 12), (2, 31), (3, 8)], seed=14)
+    assert worst < 1e-2, worst
+
+
+def test_attention_k32_block_65535_rows_batch16(host_model):
+    """The long multi-turn configuration's launch: 16 streams x 65535 cached rows, 33 block rows
+    (132 query rows per KV head, the wide-block kernel), 128-token V blocks up to index 511.
+    Five (stream, head) pairs are checked element by element against the oracle's attention."""
+    worst = _attention_case(host_model, HOST, [65535] * 16, 33,
+                            [(0, 0), (3, 31), (9, 14), (15, 7), (15, 24)], seed=17, device_fill=True)
+    assert worst < 1e-2, worst
+
+
+def test_attention_k32_block_long_ragged(host_model):
+    """Wide-block kernel with ragged long caches (lengths around the 128-token V blocks and the
+    32-token K blocks) next to an empty one; rows past the block poisoned."""
+    worst = _attention_case(host_model, HOST, [40000, 0, 16383, 16385, 127, 32769], 33,
+                            [(0, 5), (1, 0), (2, 31), (3, 16), (4, 9), (5, 20)], seed=18, poison=True)
     assert worst < 1e-2, worst
 
 

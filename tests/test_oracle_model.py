@@ -150,6 +150,34 @@ def test_round_bf16_vs_torch():
     assert np.array_equal(synth.bf16_bits_to_f32(bits).astype(np.float64), ref)
 
 
+def test_bf16_bit_patterns_and_cache_load_vs_torch():
+    """The oracle reads bf16 data (weights, cache rows) as uint16 bit patterns: every one of the
+    65536 patterns must decode to the value torch's bfloat16 gives it, and KVCache.load must put
+    rows [kv_head][n][hd] of one layer at cache[layer][kv_head][0..n) and nowhere else."""
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    with np.errstate(invalid="ignore"):                     # signalling-NaN patterns
+        got = orc._f64(bits)
+    assert got.dtype == np.float64 and np.array_equal(got, ref, equal_nan=True)
+    assert got[0x3F80] == 1.0 and got[0xC000] == -2.0 and got[0x3DCD] == 0.10009765625   # hand-decoded
+    x = np.array([[1.5, -2.25], [3.0, 0.125]], dtype=np.float32)
+    assert np.array_equal(orc._f64(x), x.astype(np.float64))
+    shape = SMALL_BF16
+    rng = np.random.default_rng(5)
+    kb = rng.integers(0, 0x7F80, (shape.n_kv_heads, 7, shape.head_dim)).astype(np.uint16)   # finite, positive
+    vb = (rng.integers(0, 0x7F80, kb.shape) | 0x8000).astype(np.uint16)                     # finite, negative
+    kv = orc.KVCache(shape, 9)
+    kv.load(1, kb, vb)
+    tk = torch.from_numpy(kb.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    tv = torch.from_numpy(vb.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    assert np.array_equal(kv.k[1, :, :7], tk) and np.array_equal(kv.v[1, :, :7], tv)
+    assert not kv.k[0].any() and not kv.k[1, :, 7:].any() and not kv.v[0].any() and not kv.v[1, :, 7:].any()
+    assert kv.length == 0                                   # loading does not change the length
+    kf = orc.KVCache(shape, 9)
+    kf.load(1, tk.astype(np.float32), tv.astype(np.float32))   # the same values as floats
+    assert np.array_equal(kf.k, kv.k) and np.array_equal(kf.v, kv.v)
+
+
 def test_bf16_cache_rounding_is_the_only_rounding():
     w = synth.model_weights(SMALL_BF16, 77, threads=1)
     toks = np.arange(12) % SMALL_BF16.vocab
