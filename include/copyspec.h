@@ -95,6 +95,24 @@ int cs_find_match_batch_dev(const int32_t* d_hist /*device*/, int64_t stride,
                             int32_t k, int32_t policy, int32_t* d_match_pos, int32_t* d_src_pos,
                             int32_t* d_draft, int32_t* d_draft_len, void* stream);
 
+/* cs_find_match_batch_dev for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels,
+ * same results; it calls no hipMalloc / hipFree or any other allocating routine.  The per-chunk
+ * keys of the scan, which the call above keeps in allocated buffers, live in a fixed array of
+ * CS_NOALLOC_MAX_CHUNKS 64-bit keys (512 KiB) inside the library's device image, held by every GPU
+ * the library runs on until the process ends.  Limit: B * ceil(stride / 4096) <=
+ * CS_NOALLOC_MAX_CHUNKS (e.g. 64 histories of 4 M tokens, or 8192 of 32768), otherwise
+ * CS_E_CAPACITY and nothing is launched.  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (different streams or threads) race; calls on one stream are
+ * ordered by it.  Nothing needs clearing between calls (every key a call reads it has written
+ * itself).  Asynchronous on `stream`. */
+#define CS_NOALLOC_MAX_CHUNKS 65536
+int cs_find_match_batch_dev_noalloc(const int32_t* d_hist /*device*/, int64_t stride,
+                                    const int32_t* d_len /*device [B]*/, int32_t B, int32_t gamma,
+                                    int32_t k, int32_t policy, int32_t* d_match_pos,
+                                    int32_t* d_src_pos, int32_t* d_draft, int32_t* d_draft_len,
+                                    void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Gamma-gram index  (Sec. 3.1: the dictionary that maps every gamma-token subsequence to the
  * places where it occurs and grows with the sequence; App. B.1, dictionary D; App. B.3 steps

@@ -22,7 +22,7 @@ CS_F32, CS_BF16 = 0, 1
 POLICIES = {"rightmost": CS_POLICY_RIGHTMOST, "first": CS_POLICY_FIRST, "context": CS_POLICY_CONTEXT}
 
 EXPORTS = [
-    "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev",
+    "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev", "cs_find_match_batch_dev_noalloc",
     "cs_model_create", "cs_model_destroy", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
     "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_prefill_batch", "cs_decode_batch", "cs_index_create", "cs_index_destroy",
@@ -87,6 +87,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_find_match_ex.argtypes = [vp, i64, i32, i32, i32, C.POINTER(i64), C.POINTER(i64), vp,
                                      C.POINTER(i32)]
     lib.cs_find_match_batch_dev.argtypes = [vp, i64, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.cs_find_match_batch_dev_noalloc.argtypes = [vp, i64, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.cs_index_create.argtypes = [i32, i64, i32, C.POINTER(vp)]
     lib.cs_index_destroy.argtypes = [vp]
     lib.cs_index_destroy.restype = None
@@ -194,6 +195,24 @@ def cs_find_match_batch_dev(d_hist: torch.Tensor, d_len: torch.Tensor, gamma: in
                                                   gamma, k, _policy(policy), mp.data_ptr(),
                                                   sp.data_ptr(), dr.data_ptr(), dl.data_ptr(),
                                                   _stream(stream)))
+    return mp, sp, dr, dl
+
+
+def cs_find_match_batch_dev_noalloc(d_hist: torch.Tensor, d_len: torch.Tensor, gamma: int, k: int,
+                                    policy="rightmost", stream=None, out=None):
+    """Same as cs_find_match_batch_dev through the entry point that allocates nothing; `out` =
+    (match_pos, src_pos, draft, draft_len) lets the caller bring the outputs too."""
+    _dev_i32(d_hist, "d_hist"), _dev_i32(d_len, "d_len")
+    B, stride = d_hist.shape
+    dev = d_hist.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev))
+    mp, sp, dr, dl = out
+    _check(load_library().cs_find_match_batch_dev_noalloc(d_hist.data_ptr(), stride, d_len.data_ptr(), B,
+                                                          gamma, k, _policy(policy), mp.data_ptr(),
+                                                          sp.data_ptr(), dr.data_ptr(), dl.data_ptr(),
+                                                          _stream(stream)))
     return mp, sp, dr, dl
 
 

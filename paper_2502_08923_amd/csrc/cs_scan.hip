@@ -222,3 +222,51 @@ int cs_gather_launch(const int32_t* d_hist, int64_t stride, const int32_t* d_len
     return cs_launch_ok("k_gather");
 }
 
+// -------------------------------------------------------------------------------------
+// cs_find_match_batch_dev for callers that must not allocate: same kernels, the per-chunk keys
+// live in a fixed array in the code object's own device memory instead of a hipMalloc'd buffer.
+// -------------------------------------------------------------------------------------
+#define SCAN_STATIC_KEYS CS_NOALLOC_MAX_CHUNKS
+static __device__ __align__(256) int64_t scratch[SCAN_STATIC_KEYS];
+
+// `scratch` above is only a host-side stand-in for the symbol; the array's device address is
+// asked for once per device (every device holds its own copy at its own address) and only that
+// address is ever handed to a kernel.
+#define SCAN_MAX_DEVICES 64
+static int64_t* g_scratch_ptr[SCAN_MAX_DEVICES];
+static std::mutex g_scratch_mu;
+
+static int scan_static_keys(int64_t** out) {
+    int dev = 0;
+    CS_HIP(hipGetDevice(&dev));
+    CS_REQUIRE(dev >= 0 && dev < SCAN_MAX_DEVICES, CS_E_UNSUPPORTED, "device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        CS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        CS_REQUIRE(p, CS_E_DEVICE, "no device address for the static scan scratch");
+        g_scratch_ptr[dev] = static_cast<int64_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return CS_OK;
+}
+
+extern "C" int cs_find_match_batch_dev_noalloc(const int32_t* d_hist, int64_t stride, const int32_t* d_len,
+                                               int32_t B, int32_t gamma, int32_t k, int32_t policy,
+                                               int32_t* d_match_pos, int32_t* d_src_pos, int32_t* d_draft,
+                                               int32_t* d_draft_len, void* stream) {
+    CS_TRY(cs_check_scan_args(gamma, k, policy));
+    CS_REQUIRE(B >= 0, CS_E_ARG, "B must be >= 0");
+    if (B == 0) return CS_OK;
+    CS_REQUIRE(d_hist && d_len && d_draft_len && (d_draft || k == 0), CS_E_ARG,
+               "cs_find_match_batch_dev_noalloc: NULL pointer");
+    CS_REQUIRE(stride >= 1 && stride <= CS_MAX_STRIDE, CS_E_ARG, "stride out of range");
+    const int nslots = cs_scan_slots(stride);
+    CS_REQUIRE(B <= 65535 && (int64_t)B * nslots <= SCAN_STATIC_KEYS, CS_E_CAPACITY,
+               "cs_find_match_batch_dev_noalloc: B * ceil(stride / %d) = %lld exceeds the static scratch of %d "
+               "chunks (use cs_find_match_batch_dev)", SCAN_CHUNK, (long long)B * nslots, SCAN_STATIC_KEYS);
+    int64_t* keys = nullptr;
+    CS_TRY(scan_static_keys(&keys));
+    return cs_scan_launch(d_hist, stride, d_len, B, gamma, k, policy, keys, nslots, d_match_pos, d_src_pos,
+                          d_draft, d_draft_len, nullptr, (hipStream_t)stream);
+}
