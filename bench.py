@@ -10,12 +10,20 @@ batch 8 streams, each a 2048-token document followed by 16384 tokens of history 
 re-contains document spans (18432 tokens; the last one is pending, 18431 are cached),
 gamma = 3, k = 10.  Weights, KV contents and token histories are seeded synthetic data.
 
+The drafts of the timed step are partly right (accepted lengths 0..k over the streams, planted
+from the model's own greedy continuation), so the accept, history-append and rollback paths run
+inside the timed region.  After the headline timing the same model runs the long multi-turn
+configuration (batch 16, 65535 cached rows, k = 32: 528 block rows) and reports it as `cfg5`,
+the shape at which the projections are bound by the matrix cores.  The CPU oracle is timed on
+one full-depth stream of the headline workload, on the same cache contents the GPU stream had.
+
 Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
 `--prefill N` times prompt ingestion instead (a separate line, not the headline metric).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -33,67 +41,8 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_workload(args):
-    import numpy as np
-    import torch
-    import synth
-    from paper_2502_08923_amd import binding as cs
-
-    shape = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B}[args.shape]
-    if args.layers:
-        shape = shape.with_layers(args.layers)
-    B, k, gamma = args.batch, args.k, args.gamma
-    dev = "cuda:0"
-    t0 = time.time()
-    w = synth.model_weights(shape, synth.seed_for(4), threads=16)
-    log(f"[bench] weights generated in {time.time() - t0:.1f}s")
-    t0 = time.time()
-    model = cs.Model(w, max_batch=B, max_k=k, device=dev)
-    del w
-    log(f"[bench] model uploaded in {time.time() - t0:.1f}s")
-
-    hists = [synth.history_cfg4(b, vocab=shape.vocab, doc=args.doc, hist=args.hist, k=k)["tokens"]
-             for b in range(B)]
-    n = args.doc + args.hist
-    L = n - 1
-    cap = n + 64 * (k + 1) + 64
-    kv = cs.KV(model, B, cap)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(synth.seed_for(4) + 17)
-    t0 = time.time()
-    for layer in range(shape.n_layers):
-        for b in range(B):
-            kr = torch.randn((shape.n_kv_heads, L, shape.head_dim), generator=gen, device=dev,
-                             dtype=torch.float32).to(torch.bfloat16)
-            vr = torch.randn((shape.n_kv_heads, L, shape.head_dim), generator=gen, device=dev,
-                             dtype=torch.float32).to(torch.bfloat16)
-            kv.load(layer, b, 0, kr, vr)
-    log(f"[bench] KV cache filled in {time.time() - t0:.1f}s")
-    stride = ((n + 64 * (k + 1) + 3) // 4) * 4
-    hist = np.zeros((B, stride), dtype=np.int32)
-    for b in range(B):
-        hist[b, :n] = hists[b]
-    st = {
-        "shape": shape, "model": model, "kv": kv, "B": B, "k": k, "gamma": gamma, "n": n, "L": L,
-        "hist": torch.from_numpy(hist).to(dev),
-        "hist_len0": torch.full((B,), n, dtype=torch.int32, device=dev),
-        "kv_len0": torch.full((B,), L, dtype=torch.int32, device=dev),
-        "room0": torch.full((B,), 1 << 20, dtype=torch.int32, device=dev),
-        "hists": hists,
-    }
-    st["hist_len"] = st["hist_len0"].clone()
-    st["room"] = st["room0"].clone()
-    st["out"] = tuple(torch.empty(B, dtype=torch.int32, device=dev) for _ in range(3))
-    return st
-
-
-def one_step(st, cs):
-    """Rewind the state (async, tiny) and run one whole step."""
-    st["hist_len"].copy_(st["hist_len0"])
-    st["room"].copy_(st["room0"])
-    st["kv"].set_len_dev(st["kv_len0"], st["L"])
-    return cs.cs_step(st["model"], st["kv"], st["hist"], st["hist_len"], st["room"], st["gamma"],
-                      st["k"], "rightmost", out=st["out"])
+DTYPE = "bf16 weights and KV cache; fp16 MFMA projections, bf16 MFMA attention, fp32 accumulation"
+TAUS = [0, 2, 5, 10, 7, 3, 10, 5, 1, 8, 4, 6, 9, 0, 10, 2]      # accepted drafts planted per stream
 
 
 def algorithmic_bytes(st):
@@ -168,48 +117,40 @@ def bench_scan(cs, torch, synth, log):
     return res
 
 
-def cpu_baseline(st, args):
-    """The CPU oracle timed on a bounded sample of the same workload: `cpu_streams` of the B
-    streams, `cpu_layers` decoder layers at full width and full context, plus the scan, the
-    lm_head, the argmax and the accept rule; the layer time is scaled to the full depth and
-    the stream time to the full batch."""
+def cpu_baseline(st, args, gpu_acc, gpu_next):
+    """The CPU oracle timed on one whole stream of the same step at full depth: stream 0's match
+    search, the forward pass of its k+1 block rows through every layer against the same cache
+    contents the GPU stream had (synth.random_kv), the lm_head, the argmax and the accept rule.
+    The B streams of a step are independent and equally shaped, so a step costs B stream times;
+    the rate is B*k verified tokens per that."""
+    import numpy as np
     import synth
     from oracle import copyspec_oracle as orc
     sh = st["shape"]
-    nl, ns = min(args.cpu_layers, sh.n_layers), min(args.cpu_streams, st["B"])
-    sub = sh.with_layers(nl)
-    w = synth.model_weights(sub, synth.seed_for(4), threads=8)
-    L, k = st["L"], st["k"]
-    t_scan = t_layers = t_head = 0.0
-    for b in range(ns):
-        okv = orc.KVCache(sub, L + k + 1)
-        for layer in range(nl):
-            kr, vr = synth.random_kv(sub, L, synth.seed_for(4), layer, b)
-            okv.load(layer, kr, vr)
-        okv.truncate(L)
-        h = st["hists"][b]
-        t0 = time.perf_counter()
-        _, _, draft = orc.find_match_np(h, st["gamma"], k)
-        t_scan += time.perf_counter() - t0
-        # layers (return_hidden skips the lm_head) and lm_head timed separately
-        t0 = time.perf_counter()
-        hidden = orc.forward_block(w, okv, [int(h[-1])] + draft, return_hidden=True)
-        t_layers += time.perf_counter() - t0
-        t0 = time.perf_counter()
-        logits = hidden @ orc._f64(w["lm_head"]).T
-        am = [orc.argmax_first(r) for r in logits]
-        orc.accept_prefix(am, draft)
-        t_head += time.perf_counter() - t0
-        del okv
-    t_stream = (t_scan + t_layers / nl * sh.n_layers + t_head) / ns
-    t_step = t_stream * st["B"]
-    return {"value": st["B"] * k / t_step, "unit": "tokens/s",
-            "cores": int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count()),
-            "kind": "oracle",
-            "sample": f"{ns} of {st['B']} streams, {nl} of {sh.n_layers} layers + lm_head + scan at "
-                      f"full width and context (L={L}); measured {t_scan + t_layers + t_head:.1f}s "
-                      f"(scan {t_scan * 1e3:.1f} ms, layers {t_layers:.1f}s, head {t_head:.1f}s), "
-                      f"scaled to {sh.n_layers} layers x {st['B']} streams"}
+    L, k, B = st["L"], st["k"], st["B"]
+    w = synth.model_weights(sh, synth.seed_for(4), threads=16)
+    okv = orc.KVCache(sh, L + k + 1)
+    for layer, (kr, vr) in enumerate(st["host_kv"][0]):
+        okv.load(layer, kr, vr)
+    okv.truncate(L)
+    h = st["hist_host"][0, :st["n"]]
+    t0 = time.perf_counter()
+    _, _, draft = orc.find_match_np(h, st["gamma"], k)
+    t_scan = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    tau, nxt, logits = orc.verify(w, okv, int(h[-1]), draft)
+    t_verify = time.perf_counter() - t0
+    t_stream = t_scan + t_verify
+    margin_ok = all((np.partition(r, -2)[-1] - np.partition(r, -2)[-2]) > 1e-2 for r in logits[:tau + 1])
+    threads = int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count())
+    return {"value": B * k / (B * t_stream), "unit": "tokens/s", "cores": threads,
+            "kind": f"oracle (numpy float64 + BLAS, {threads} threads)",
+            "sample": f"stream 0 of {B} at full depth ({sh.n_layers} layers, {L} cached rows, {k + 1} block rows, "
+                      f"lm_head, argmax, accept) plus its match scan, on the cache contents the GPU stream had: "
+                      f"{t_stream:.1f}s (scan {t_scan * 1e3:.1f} ms); a step is {B} such streams",
+            "stream0": {"oracle_tau": int(tau), "oracle_next": int(nxt), "gpu_tau": int(gpu_acc[0]),
+                        "gpu_next": int(gpu_next[0]), "oracle_margin_safe": bool(margin_ok),
+                        "agree": bool(int(tau) == int(gpu_acc[0]) and int(nxt) == int(gpu_next[0]))}}
 
 
 def bench_prefill(args):
@@ -253,7 +194,7 @@ def bench_prefill(args):
         "metric": f"prompt tokens/sec/GPU ({args.shape.upper()} shape, {n}-token prompt)",
         "value": rows / t, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1),
         "ms_per_step": t * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"llama-{args.shape} shape x{shape.n_layers} layers, one stream, {n}-token prompt "
                                f"ingested by cs_prefill (one whole prompt per step)", "prompt": n},
         "roofline": {"bound": "mfma", "kernel": "k_gemm_dma (all projections of the prompt blocks)",
@@ -269,18 +210,102 @@ def bench_prefill(args):
     print(json.dumps(out), flush=True)
 
 
+def kernel_source_hash() -> str:
+    """Digest of the kernel sources: a counter summary under profiles/ names the digest it was
+    taken at, and its figures are only quoted for the same sources."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2502_08923_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(kernel: str):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE +
-    WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB device copy), or None.
-    bench.py cannot collect hardware counters itself; the summary says how they were taken."""
+    WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB device copy).  bench.py
+    cannot collect hardware counters itself; the summary says how they were taken and for which
+    kernel sources (KERNEL_SOURCES line).  Returns (bytes or None, digest of the summary)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b_b8_k10.txt")
+    val, digest = None, None
     try:
         for line in open(path):
             if line.startswith(f"TRAFFIC {kernel} "):
-                return float(line.split()[2])
+                val = float(line.split()[2])
+            if line.startswith("KERNEL_SOURCES "):
+                digest = line.split()[1]
     except OSError:
         pass
-    return None
+    return (val if digest == kernel_source_hash() else None), digest
+
+
+def timed_steps(st, steps, warmup, torch, cs, wl, classes):
+    """`warmup` untimed steps, `steps` timed ones between two synchronisations, the same steps once
+    more one by one (median, minimum) and once more with HIP-event timing of the kernel classes."""
+    for _ in range(warmup):
+        wl.one_step(st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        wl.one_step(st)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / steps
+    outs = [t.cpu().numpy().copy() for t in st["out"]]
+    per_step = []
+    for _ in range(steps):
+        t1 = time.perf_counter()
+        wl.one_step(st)
+        torch.cuda.synchronize()
+        per_step.append(time.perf_counter() - t1)
+    per_step.sort()
+    cs.cs_profile_enable(classes)
+    cs.cs_profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        wl.one_step(st)
+    torch.cuda.synchronize()
+    t_prof = (time.perf_counter() - t0) / steps
+    prof = {c: cs.cs_profile_read(c) for c in classes}
+    cs.cs_profile_enable([])
+    return t_step, per_step, t_prof, prof, outs
+
+
+def bench_cfg5(model, shape, args, torch, cs, wl, synth):
+    """The long multi-turn configuration on the same model: batch 16, 65535 cached rows, k = 32
+    (528 block rows).  Its projections are bound by the matrix cores, its attention by HBM."""
+    B, k, gamma = 16, 32, 3
+    hists = [synth.history_cfg5(b)["tokens"] for b in range(B)]
+    st = wl.build_state(shape, model, B, k, gamma, hists)
+    taus = wl.plant_acceptance(st, [min(3 * t, k) for t in TAUS[:B]])
+    classes = ["gemm", "attn", "attn_merge", "lm_head"]
+    steps = max(4, args.steps // 2)
+    t_step, per_step, _, prof, outs = timed_steps(st, steps, 2, torch, cs, wl, classes)
+    ab = algorithmic_bytes(st)
+    attn_s = prof["attn"][0] / prof["attn"][1] * 1e-3
+    gemm_s = prof["gemm"][0] / steps * 1e-3
+    lm_s = prof["lm_head"][0] / prof["lm_head"][1] * 1e-3
+    lm_flops = 2.0 * B * (k + 1) * shape.vocab * shape.d_model
+    acc = outs[0]
+    out = {
+        "workload": f"llama-8b shape x{shape.n_layers} layers, batch {B} streams, 65536-token histories "
+                    f"(1024-token answer repeated with 5 % edits), KV length {st['L']} + pending, gamma={gamma}, k={k}",
+        "rows": B * (k + 1), "ms_per_step": t_step * 1e3, "ms_per_step_min": per_step[0] * 1e3,
+        "verified_tokens_per_s": B * k / t_step, "emitted_tokens_per_s": float((acc + 1).sum()) / t_step,
+        "accepted_len": acc.tolist(), "planted_accepted_len": taus.tolist(),
+        "attention": {"kernel": "k_attn_lds", "bound": "hbm", "avg_us": attn_s * 1e6,
+                      "achieved_GBps": ab["attn_launch"] / attn_s / 1e9,
+                      "frac": ab["attn_launch"] / attn_s / 1e9 / HBM_PEAK_GBS},
+        "projections": {"kernel": "k_gemm_dma (all projections of the step, lm_head included)", "bound": "mfma",
+                        "ms_per_step": gemm_s * 1e3, "achieved_TFLOPs": ab["gemm_flops_step"] / gemm_s / 1e12,
+                        "mfma_frac": ab["gemm_flops_step"] / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                        "flops_per_step": ab["gemm_flops_step"]},
+        "lm_head": {"avg_us": lm_s * 1e6, "achieved_TFLOPs": lm_flops / lm_s / 1e12,
+                    "mfma_frac": lm_flops / lm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "attn_merge": {"avg_us": prof["attn_merge"][0] / max(prof["attn_merge"][1], 1) * 1e3},
+    }
+    st["kv"].destroy()
+    return out
 
 
 def main():
@@ -295,9 +320,8 @@ def main():
     ap.add_argument("--gamma", type=int, default=3)
     ap.add_argument("--doc", type=int, default=2048)
     ap.add_argument("--hist", type=int, default=16384)
-    ap.add_argument("--cpu-layers", type=int, default=16)
-    ap.add_argument("--cpu-streams", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-cfg5", action="store_true", help="skip the batch-16 / k=32 block of the default run")
     ap.add_argument("--no-scan", action="store_true")
     ap.add_argument("--prefill", type=int, default=0,
                     help="time the ingestion of an N-token prompt (one stream) instead of the step")
@@ -330,41 +354,22 @@ def main():
         bench_prefill(args)
         return
 
-    st = build_workload(args)
-    B, k = st["B"], st["k"]
-    for _ in range(args.warmup):
-        one_step(st, cs)
-    torch.cuda.synchronize()
+    from paper_2502_08923_amd import workload as wl
+    B, k = args.batch, args.k
+    default_workload = (args.shape, B, k, args.doc, args.hist, args.layers) == ("8b", 8, 10, 2048, 16384, 0)
+    run_cfg5 = default_workload and not args.no_cfg5
+    # one model serves the headline workload and the long multi-turn configuration
+    shape, model = wl.build_model(args.shape, args.layers, max(B, 16) if run_cfg5 else B,
+                                  max(k, 32) if run_cfg5 else k)
+    hists = [synth.history_cfg4(b, vocab=shape.vocab, doc=args.doc, hist=args.hist, k=k)["tokens"]
+             for b in range(B)]
+    st = wl.build_state(shape, model, B, k, args.gamma, hists, host_kv_streams=() if args.no_cpu else (0,))
+    planted = wl.plant_acceptance(st, [min(t, k) for t in (TAUS * ((B + 15) // 16))[:B]]) if k > 0 else None
 
     # timed region: exactly `steps` whole steps, inputs resident in HBM
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(st, cs)
-    torch.cuda.synchronize()
-    t_step = (time.perf_counter() - t0) / args.steps
-    acc = st["out"][0].cpu().numpy()
-    dl = st["out"][2].cpu().numpy()
-
-    # the same steps once more, each bracketed by a synchronize of its own: median and minimum
-    per_step = []
-    for _ in range(args.steps):
-        t1 = time.perf_counter()
-        one_step(st, cs)
-        torch.cuda.synchronize()
-        per_step.append(time.perf_counter() - t1)
-    per_step.sort()
-
-    # third pass of the same steps with HIP-event timing of the kernel classes
     classes = ["scan", "gemm", "attn", "attn_merge", "argmax", "lm_head"]
-    cs.cs_profile_enable(classes)
-    cs.cs_profile_reset()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(st, cs)
-    torch.cuda.synchronize()
-    t_step_prof = (time.perf_counter() - t0) / args.steps
-    prof = {c: cs.cs_profile_read(c) for c in classes}
-    cs.cs_profile_enable([])
+    t_step, per_step, t_step_prof, prof, outs = timed_steps(st, args.steps, args.warmup, torch, cs, wl, classes)
+    acc, nxt, dl = outs
 
     # the step takes the argmax inside the lm_head (no logits in memory, no argmax pass); the
     # stand-alone argmax kernel, which serves callers that ask for the logits, is timed on its own
@@ -415,8 +420,8 @@ def main():
     # more than 48 query rows per KV head go to the LDS-ring attention kernel
     g_rows = (k + 1) * (st["shape"].n_heads // st["shape"].n_kv_heads)
     attn_kernel = "k_attn_mfma" if g_rows <= 48 else "k_attn_lds"
-    # the committed counter summary covers the default workload only
-    default_workload = (args.shape, B, k, args.doc, args.hist, args.layers) == ("8b", 8, 10, 2048, 16384, 0)
+    # the committed counter summary covers the default workload only, at the kernel sources it names
+    traffic, traffic_sources = measured_traffic("k_attn_mfma") if default_workload else (None, None)
     step_bytes = ab["gemm_step"] + ab["attn_step"] + ab["scan_launch"] + (0 if argmax_fused else ab["argmax_launch"])
     out = {
         "metric": f"verified tokens/sec/GPU ({args.shape.upper()} shape, k={k})",
@@ -429,17 +434,21 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": DTYPE,
         "data": "synthetic",
+        "emitted_tokens_per_s": float((acc + 1).sum()) / t_step,
+        "mean_accepted_per_attempt": float(acc.mean()),
         "config": {"workload": f"llama-{args.shape} shape x{st['shape'].n_layers} layers, batch {B} streams, "
                                f"{args.doc}-token document + {args.hist}-token history with planted "
                                f"document spans (KV length {st['L']} + pending), gamma={st['gamma']}, k={k}, "
+                               f"drafts planted so that {acc.tolist()} of {k} are accepted, "
                                f"one whole cs_step per step",
                    "batch": B, "k": k, "gamma": st["gamma"], "kv_len": st["L"], "rows": B * (k + 1)},
         "roofline": {"bound": "hbm", "kernel": f"{attn_kernel} (block attention, one layer, all streams)",
                      "achieved": ab["attn_launch"] / attn_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": ab["attn_launch"] / attn_s / 1e9 / HBM_PEAK_GBS,
-                     "traffic": measured_traffic("k_attn_mfma") if default_workload else None,
+                     "traffic": traffic, "traffic_profile_kernel_sources": traffic_sources,
+                     "kernel_sources": kernel_source_hash(),
                      "algorithmic_bytes_per_launch": ab["attn_launch"], "avg_launch_us": attn_s * 1e6},
         "kernels": kern,
         "step": {"algorithmic_GB": step_bytes / 1e9,
@@ -447,14 +456,22 @@ def main():
                  "ms_per_step_median": per_step[len(per_step) // 2] * 1e3, "ms_per_step_min": per_step[0] * 1e3,
                  "ms_per_step_with_event_timing": t_step_prof * 1e3,
                  "draft_len": dl.tolist(), "accepted_len": acc.tolist(),
+                 "planted_accepted_len": None if planted is None else planted.tolist(),
                  "emitted_tokens_per_s": float((acc + 1).sum()) / t_step},
     }
     if not args.no_scan:
         out["match_scan"] = bench_scan(cs, torch, synth, log)
         out["metric"] += " + match-scan Gtokens/s"
+    st["kv"].destroy()                                   # the long configuration needs the memory
+    if run_cfg5:
+        t0 = time.time()
+        out["cfg5"] = bench_cfg5(model, shape, args, torch, cs, wl, synth)
+        log(f"[bench] cfg5 block took {time.time() - t0:.1f}s")
+    model.destroy()
+    torch.cuda.empty_cache()
     if not args.no_cpu:
         t0 = time.time()
-        out["cpu_baseline"] = cpu_baseline(st, args)
+        out["cpu_baseline"] = cpu_baseline(st, args, acc, nxt)
         log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
     else:
         out["cpu_baseline"] = None

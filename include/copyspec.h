@@ -46,7 +46,9 @@ typedef enum cs_status {
     CS_E_CAPACITY = -3,  /* KV cache or history buffer too small for the request */
     CS_E_DEVICE = -4,    /* a HIP call failed; text in cs_last_error() */
     CS_E_STATE = -5,     /* handle used in a state the call does not allow */
-    CS_E_UNSUPPORTED = -6 /* shape outside what the kernels are built for */
+    CS_E_UNSUPPORTED = -6, /* shape or values outside what the kernels are built for */
+    CS_E_RANGE = -7      /* a synchronous loop finished, but activations left the float16 range of the
+                            projections and were saturated (see cs_model_range_status) */
 } cs_status;
 
 enum { CS_POLICY_RIGHTMOST = 0, CS_POLICY_FIRST = 1, CS_POLICY_CONTEXT = 2 };
@@ -177,6 +179,25 @@ typedef struct cs_weights {
 
 typedef struct cs_model cs_model;
 typedef struct cs_kv cs_kv;
+
+/* Value range of the tuned kernels.  For CS_BF16 models whose shape allows them (head_dim 64 or
+ * 128, d_model, d_ff and n_heads*head_dim multiples of 128, vocab a multiple of 16) the projections
+ * multiply float16 operands on the matrix cores: the library converts its copy of the weights
+ * from bfloat16 (exactly for 2^-17 <= |w| <= 65504; smaller magnitudes are rounded to multiples
+ * of 2^-24) and the kernels round every projection input to float16.  Supported range:
+ *   - weights: finite, |w| <= 65504, otherwise cs_model_create fails with CS_E_UNSUPPORTED;
+ *   - activations that feed a projection (RMSNorm outputs, attention outputs, SwiGLU outputs):
+ *     |x| <= 65504.  A larger magnitude is saturated to +-65504 instead of becoming infinite, and
+ *     the producing kernel raises a bit in a per-model status word on the device:
+ *     CS_RANGE_NORM, CS_RANGE_ATTN, CS_RANGE_FFN.  A NaN raises the bit of its producer too.
+ * cs_model_range_status waits for the device, returns the word in *flags (host) and clears it
+ * if `clear` is non-zero; 0 means every result since the last clear is the exact-range result.
+ * The asynchronous calls (cs_verify, cs_step) never fail for this reason: ask afterwards.  The
+ * synchronous loops (cs_decode*, which clear the word when they start) deliver their tokens and
+ * return CS_E_RANGE if the word is non-zero at the end.  Plain-kernel and CS_F32 models keep
+ * float32 activations and never raise a bit. */
+enum { CS_RANGE_NORM = 1, CS_RANGE_ATTN = 2, CS_RANGE_FFN = 4, CS_RANGE_WEIGHT = 8 };
+int cs_model_range_status(cs_model* m, int32_t* flags /*host*/, int32_t clear);
 
 /* Copies (and re-lays-out) the weights into library-owned device memory; the caller's
  * buffers may be freed afterwards.  Synchronous. */

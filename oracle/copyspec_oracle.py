@@ -274,10 +274,16 @@ class KVCache:
 
 
 def forward_block(w: dict, kv: KVCache, tokens, store_dtype: str | None = None,
-                  return_hidden: bool = False) -> np.ndarray:
+                  return_hidden: bool = False, act_clip: float | None = None) -> np.ndarray:
     """Run the decoder over `tokens` placed at positions kv.length, kv.length+1, ...;
     row i attends to cache rows 0 .. kv.length+i (its own included).  Writes the new K/V
-    rows into the cache (it does not change kv.length) and returns logits [rows][vocab]."""
+    rows into the cache (it does not change kv.length) and returns logits [rows][vocab].
+
+    act_clip (default None: no effect) models an implementation whose linear layers take inputs
+    of limited range: the input of every projection (q/k/v, output, gate/up, down, lm_head) is
+    clipped to [-act_clip, act_clip] before it is multiplied.  This is not part of the model or
+    of the paper; it exists so that a library which documents such a range can be compared on
+    inputs that leave it."""
     sh = w["shape"]
     store = store_dtype or sh.dtype
     H, KVH, hd, d = sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.d_model
@@ -288,9 +294,10 @@ def forward_block(w: dict, kv: KVCache, tokens, store_dtype: str | None = None,
     if L + R > kv.capacity:
         raise ValueError("KV capacity exceeded")
     pos = L + np.arange(R)
+    clip = (lambda t: t) if act_clip is None else (lambda t: np.clip(t, -act_clip, act_clip))
     x = _f64(w["embed"][tokens])                                  # [R][d]
     for l, lw in enumerate(w["layers"]):
-        a = rmsnorm(x, _f64(lw["norm1"]), sh.rms_eps)
+        a = clip(rmsnorm(x, _f64(lw["norm1"]), sh.rms_eps))
         q = (a @ _f64(lw["wq"]).T).reshape(R, H, hd)
         kk = (a @ _f64(lw["wk"]).T).reshape(R, KVH, hd)
         vv = (a @ _f64(lw["wv"]).T).reshape(R, KVH, hd)
@@ -306,12 +313,12 @@ def forward_block(w: dict, kv: KVCache, tokens, store_dtype: str | None = None,
         for hq in range(H):
             g = hq // G                                               # grouped-query mapping
             o[:, hq] = causal_attention(q[:, hq], kv.k[l, g, :L + R], kv.v[l, g, :L + R], pos)
-        x = x + o.reshape(R, H * hd) @ _f64(lw["wo"]).T
-        b = rmsnorm(x, _f64(lw["norm2"]), sh.rms_eps)
+        x = x + clip(o.reshape(R, H * hd)) @ _f64(lw["wo"]).T
+        b = clip(rmsnorm(x, _f64(lw["norm2"]), sh.rms_eps))
         gate = b @ _f64(lw["wg"]).T
         up = b @ _f64(lw["wu"]).T
-        x = x + (silu(gate) * up) @ _f64(lw["wd"]).T
-    hidden = rmsnorm(x, _f64(w["final_norm"]), sh.rms_eps)
+        x = x + clip(silu(gate) * up) @ _f64(lw["wd"]).T
+    hidden = clip(rmsnorm(x, _f64(w["final_norm"]), sh.rms_eps))
     if return_hidden:
         return hidden
     return hidden @ _f64(w["lm_head"]).T

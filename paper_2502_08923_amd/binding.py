@@ -19,11 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libcopyspec.so")
 
 CS_POLICY_RIGHTMOST, CS_POLICY_FIRST, CS_POLICY_CONTEXT = 0, 1, 2
 CS_F32, CS_BF16 = 0, 1
+CS_RANGE_NORM, CS_RANGE_ATTN, CS_RANGE_FFN, CS_RANGE_WEIGHT = 1, 2, 4, 8
+CS_E_RANGE = -7
 POLICIES = {"rightmost": CS_POLICY_RIGHTMOST, "first": CS_POLICY_FIRST, "context": CS_POLICY_CONTEXT}
 
 EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev", "cs_find_match_batch_dev_noalloc",
-    "cs_model_create", "cs_model_destroy", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
+    "cs_model_create", "cs_model_destroy", "cs_model_range_status", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
     "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_prefill_batch", "cs_decode_batch", "cs_index_create", "cs_index_destroy",
     "cs_index_reset", "cs_index_find_match_batch_dev", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
@@ -96,6 +98,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_model_create.argtypes = [C.POINTER(cs_model_cfg), C.POINTER(cs_weights), C.POINTER(vp)]
     lib.cs_model_destroy.argtypes = [vp]
     lib.cs_model_destroy.restype = None
+    lib.cs_model_range_status.argtypes = [vp, C.POINTER(i32), i32]
     lib.cs_kv_create.argtypes = [vp, i32, i64, C.POINTER(vp)]
     lib.cs_kv_destroy.argtypes = [vp]
     lib.cs_kv_destroy.restype = None
@@ -317,6 +320,12 @@ class Model:
         self.handle = h
         self.device = dev
         del keep
+
+    def range_status(self, clear: bool = True) -> int:
+        """CS_RANGE_* bits raised since the last clear (waits for the device)."""
+        f = C.c_int32()
+        _check(load_library().cs_model_range_status(self.handle, C.byref(f), 1 if clear else 0))
+        return int(f.value)
 
     def destroy(self):
         if getattr(self, "handle", None):

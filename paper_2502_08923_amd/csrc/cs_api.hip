@@ -163,7 +163,7 @@ static void model_free(cs_model* m) {
     if (!m) return;
     void* ptrs[] = {m->embed, m->lm_head, m->final_norm, m->x, m->xn, m->q, m->gu, m->act,
                     m->logits, m->part, m->attn_part, m->rope, m->tok, m->am_val_idx,
-                    m->row_argmax, m->draft, m->draft_len, m->match_pos, m->pending};
+                    m->row_argmax, m->draft, m->draft_len, m->match_pos, m->pending, m->range_flags};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (m->layers) {
@@ -187,9 +187,11 @@ static int model_build(cs_model* m, const cs_weights* w) {
     DEV_ALLOC(m->embed, (size_t)V * d * e);
     DEV_ALLOC(m->lm_head, (size_t)V * d * e);
     DEV_ALLOC(m->final_norm, (size_t)d * 4);
+    DEV_ALLOC(m->range_flags, 4);
+    CS_HIP(hipMemset(m->range_flags, 0, 4));
     CS_HIP(hipMemcpy(m->embed, w->embed, (size_t)V * d * e, hipMemcpyDeviceToDevice));
     CS_HIP(hipMemcpy(m->final_norm, w->final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice));
-    if (m->fast) CS_TRY(cs_tile_weights_launch(w->lm_head, nullptr, V, d, 0, V, 0, m->lm_head, nullptr));
+    if (m->fast) CS_TRY(cs_tile_weights_launch(w->lm_head, nullptr, V, d, 0, V, 0, m->lm_head, m->range_flags, nullptr));
     else CS_HIP(hipMemcpy(m->lm_head, w->lm_head, (size_t)V * d * e, hipMemcpyDeviceToDevice));
     for (int l = 0; l < c.n_layers; ++l) {
         const cs_layer_weights& s = w->layers[l];
@@ -207,12 +209,12 @@ static int model_build(cs_model* m, const cs_weights* w) {
         CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
         if (m->fast) {
             // the q, k and v blocks become row ranges of one tiled matrix
-            CS_TRY(cs_tile_weights_launch(s.wq, nullptr, nq, d, 0, nqkv, 0, qkv, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wk, nullptr, nkv, d, 0, nqkv, nq, qkv, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wv, nullptr, nkv, d, 0, nqkv, nq + nkv, qkv, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wo, nullptr, d, nq, 0, d, 0, L.wo, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wg, s.wu, 2 * F, d, 1, 2 * F, 0, L.wgu, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wd, nullptr, d, F, 0, d, 0, L.wd, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wq, nullptr, nq, d, 0, nqkv, 0, qkv, m->range_flags, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wk, nullptr, nkv, d, 0, nqkv, nq, qkv, m->range_flags, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wv, nullptr, nkv, d, 0, nqkv, nq + nkv, qkv, m->range_flags, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wo, nullptr, d, nq, 0, d, 0, L.wo, m->range_flags, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wg, s.wu, 2 * F, d, 1, 2 * F, 0, L.wgu, m->range_flags, nullptr));
+            CS_TRY(cs_tile_weights_launch(s.wd, nullptr, d, F, 0, d, 0, L.wd, m->range_flags, nullptr));
             continue;
         }
         CS_HIP(hipMemcpy(qkv, s.wq, (size_t)nq * d * e, hipMemcpyDeviceToDevice));
@@ -262,6 +264,14 @@ static int model_build(cs_model* m, const cs_weights* w) {
     DEV_ALLOC(m->match_pos, (size_t)c.max_batch * 4);
     DEV_ALLOC(m->pending, (size_t)c.max_batch * 4);
     CS_HIP(hipDeviceSynchronize());
+    if (m->fast) {
+        // the tuned projections multiply in float16: a weight beyond its range cannot be represented
+        int32_t flags = 0;
+        CS_HIP(hipMemcpy(&flags, m->range_flags, 4, hipMemcpyDeviceToHost));
+        CS_REQUIRE(!(flags & CS_RANGE_WEIGHT), CS_E_UNSUPPORTED,
+                   "a projection weight is not finite or exceeds 65504 in magnitude: the float16 matrix "
+                   "cores cannot hold it (cs_set_plain_kernels(1) selects kernels without this limit)");
+    }
     return CS_OK;
 }
 
@@ -306,6 +316,32 @@ extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_
 extern "C" void cs_model_destroy(cs_model* m) {
     if (m) (void)hipDeviceSynchronize();
     model_free(m);
+}
+
+extern "C" int cs_model_range_status(cs_model* m, int32_t* flags, int32_t clear) {
+    CS_REQUIRE(m && flags, CS_E_ARG, "cs_model_range_status: NULL argument");
+    CS_HIP(hipDeviceSynchronize());
+    CS_HIP(hipMemcpy(flags, m->range_flags, 4, hipMemcpyDeviceToHost));
+    if (clear) CS_HIP(hipMemset(m->range_flags, 0, 4));
+    return CS_OK;
+}
+
+static int range_clear(cs_model* m) {
+    CS_HIP(hipDeviceSynchronize());
+    CS_HIP(hipMemset(m->range_flags, 0, 4));
+    return CS_OK;
+}
+
+// the synchronous loops end with this: the tokens are delivered, the status says if they are exact
+static int range_check_after_loop(cs_model* m, const char* who) {
+    if (!m->fast) return CS_OK;
+    int32_t flags = 0;
+    CS_TRY(cs_model_range_status(m, &flags, 1));
+    CS_REQUIRE(flags == 0, CS_E_RANGE,
+               "%s: activations exceeded the float16 range of the projections and were saturated at +-65504 "
+               "(flags 0x%x: 1 = RMSNorm output, 2 = attention output, 4 = SwiGLU output); the tokens were "
+               "computed from the saturated values", who, flags);
+    return CS_OK;
 }
 
 // -------------------------------------------------------------------------------------
@@ -697,6 +733,7 @@ static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t pr
                "cache capacity %lld < prompt_len + max_new + k + 1", (long long)kv->limit);
     cs_stats st = {0, 0, 0, 0};
     *n_out = 0;
+    CS_TRY(range_clear(m));
     CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));
     const int64_t stride = cs_round_up(prompt_len + max_new + k + 2, 4);
     int32_t* d = nullptr;
@@ -744,7 +781,7 @@ static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t pr
     if (rc != CS_OK) return rc;
     *n_out = emitted;
     if (stats) *stats = st;
-    return CS_OK;
+    return range_check_after_loop(m, "cs_decode");
 }
 
 extern "C" int cs_decode(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t prompt_len,
@@ -849,6 +886,7 @@ extern "C" int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, i
     std::vector<int64_t> emitted((size_t)B, 0);
     std::vector<char> active((size_t)B, max_new > 0 ? 1 : 0);
     for (int b = 0; b < B; ++b) n_out[b] = 0;
+    CS_TRY(range_clear(m));
     CS_TRY(cs_prefill_batch(m, kv, prompts, prompt_stride, prompt_len));
     const int64_t stride = cs_round_up(max_len + max_new + k + 2, 4);
     CS_REQUIRE(stride < (int64_t)1 << 31, CS_E_ARG, "history too long");
@@ -916,7 +954,7 @@ extern "C" int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, i
         n_out[b] = emitted[b];
         if (stats) stats[b] = st[b];
     }
-    return CS_OK;
+    return range_check_after_loop(m, "cs_decode_batch");
 }
 
 // -------------------------------------------------------------------------------------
@@ -945,6 +983,8 @@ extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv
                "draft cache capacity %lld < prompt_len + max_new + delta + 1", (long long)dkv->limit);
     cs_merged_stats st = {0, 0, 0, 0, 0, 0, 0, 0};
     *n_out = 0;
+    CS_TRY(range_clear(m));
+    CS_TRY(range_clear(dm));
     CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));
     CS_TRY(cs_kv_set_len(dkv, 0, 0));
     int64_t draft_rows = 0;                       // rows of the accepted sequence in the draft cache
@@ -1040,7 +1080,8 @@ extern "C" int cs_decode_merged(cs_model* m, cs_kv* kv, cs_model* dm, cs_kv* dkv
     if (rc != CS_OK) return rc;
     *n_out = emitted;
     if (stats) *stats = st;
-    return CS_OK;
+    CS_TRY(range_check_after_loop(dm, "cs_decode_merged (draft model)"));
+    return range_check_after_loop(m, "cs_decode_merged");
 }
 
 // -------------------------------------------------------------------------------------
@@ -1060,7 +1101,7 @@ extern "C" int cs_op_gemm(cs_model* m, int32_t dtype, const void* X, const void*
     const size_t x_bytes = cs_xt_bytes(R, K);
     CS_HIP(hipMalloc(&wt, (size_t)N * K * 2 + 2 * x_bytes));
     void* xt = (char*)wt + (size_t)N * K * 2;
-    int rc = cs_tile_weights_launch(W, nullptr, N, K, 0, N, 0, wt, s);
+    int rc = cs_tile_weights_launch(W, nullptr, N, K, 0, N, 0, wt, nullptr, s);
     if (rc == CS_OK) rc = cs_convert_launch(X, CS_T_BF16, xt, CS_T_F16, (int64_t)R * K, s);
     X = xt;
     if (rc == CS_OK && cs_gemm_x_tiled(R, N)) {            // the many-row kernel reads fragment order

@@ -128,6 +128,10 @@ __device__ __forceinline__ float fa_row4_max(float x) {
 #define FA_RESCALE_LOG2 8.0f
 #define FA_OPAD 4          // LDS row padding (floats) of the in-workgroup merge buffers
 
+// attention output element: float16 outputs feed the output projection and are saturated
+__device__ __forceinline__ void fa_store_out(f16_t* p, int64_t i, float v, bool& hit) { p[i] = cs_f16_sat(v, hit); }
+__device__ __forceinline__ void fa_store_out(float* p, int64_t i, float v, bool&) { p[i] = v; }
+
 template <int HD>
 struct fa_kbuf { bf16x8 k[2][HD / 32]; };
 template <int HD>
@@ -934,7 +938,8 @@ __global__ __launch_bounds__(PF_THREADS) void k_attn_prefill(const bf16_t* __res
                                                              const int32_t* __restrict__ kv_len,
                                                              int rows, int H, int KVH, int64_t cap,
                                                              int nqt, int ranges, int g_shift,
-                                                             OT* __restrict__ out, int tiled) {
+                                                             OT* __restrict__ out, int tiled,
+                                                             int32_t* __restrict__ flags) {
     constexpr int KS = HD / 32, MT = HD / 16;
     constexpr int WQROWS = 16 * NT;                     // query rows per wave
     constexpr int PF_QROWS = PF_WAVES * WQROWS;         // ... per workgroup
@@ -1187,6 +1192,8 @@ __global__ __launch_bounds__(PF_THREADS) void k_attn_prefill(const bf16_t* __res
 #undef PF_SYNC
 
     // out[r][head*HD + d] = O[d] / l: acc[mt][nt][j] holds O of query row nt*16 + c, feature mt*16 + 4g + j
+    // (the float16 input of the output projection: saturated at +-65504, reported if it was)
+    bool hit = false;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int n = n0 + nt * 16;
@@ -1199,9 +1206,10 @@ __global__ __launch_bounds__(PF_THREADS) void k_attn_prefill(const bf16_t* __res
             const int col = col0 + mt * 16;
             const int64_t off = tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) cs_st(out, off + j, oacc[mt][nt][j] * inv);
+            for (int j = 0; j < 4; ++j) fa_store_out(out, off + j, oacc[mt][nt][j] * inv, hit);
         }
     }
+    cs_range_report(flags, hit, CS_RANGE_ATTN);
 }
 
 // out[r][h*HD + d] = sum_s 2^(m_s - M) O_s[d] / sum_s 2^(m_s - M) l_s  over the splits
@@ -1216,7 +1224,8 @@ __global__ __launch_bounds__(FA_MERGE_THREADS) void k_attn_merge(const float* __
                                                                  const float* __restrict__ pml,
                                                                  int rows, int H, int KVH, int HD,
                                                                  int nqg, int nsplit,
-                                                                 OT* __restrict__ out, int tiled) {
+                                                                 OT* __restrict__ out, int tiled,
+                                                                 int32_t* __restrict__ flags) {
     const int lpr = HD >> 2;                  // lanes per query row
     const int n = blockIdx.x * (FA_MERGE_THREADS / lpr) + (int)threadIdx.x / lpr;   // row within the KV head: i*G + gq
     const int d = ((int)threadIdx.x % lpr) * 4;
@@ -1262,8 +1271,10 @@ __global__ __launch_bounds__(FA_MERGE_THREADS) void k_attn_merge(const float* __
     // tiled: the output projection runs the many-row GEMM, which reads fragment order
     const int col = (kvh * G + gq) * HD + d;
     const int64_t off = tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col;
+    bool hit = false;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) cs_st(out, off + j, num[j] * inv);
+    for (int j = 0; j < 4; ++j) fa_store_out(out, off + j, num[j] * inv, hit);
+    cs_range_report(flags, hit, CS_RANGE_ATTN);
 }
 
 bool cs_attention_fuses_rope(const cs_model* m, int rows) {
@@ -1313,10 +1324,10 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
         const int pa = cs_prof_begin(CS_PROF_ATTN, s);
         if (hd == 128)
             k_attn_prefill<128, PF_NT, f16_t><<<grid, PF_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
-                                                                  kv->cap, nqt, ranges, g_shift, (f16_t*)m->xn, tiled);
+                                                                  kv->cap, nqt, ranges, g_shift, (f16_t*)m->xn, tiled, m->range_flags);
         else
             k_attn_prefill<64, PF_NT, f16_t><<<grid, PF_THREADS, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,
-                                                                 kv->cap, nqt, ranges, g_shift, (f16_t*)m->xn, tiled);
+                                                                 kv->cap, nqt, ranges, g_shift, (f16_t*)m->xn, tiled, m->range_flags);
         cs_prof_end(pa, s);
         return cs_launch_ok("k_attn_prefill");
     }
@@ -1350,7 +1361,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
         dim3 mgrid((unsigned)cs_ceil_div(QR, FA_MERGE_THREADS / (hd / 4)), KVH, B);
         const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
         k_attn_merge<f16_t><<<mgrid, FA_MERGE_THREADS, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
-                                                              (f16_t*)m->xn, tiled);
+                                                              (f16_t*)m->xn, tiled, m->range_flags);
         cs_prof_end(pm, s);
         return cs_launch_ok("k_attn_merge");
     }
@@ -1391,7 +1402,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     dim3 mgrid((unsigned)cs_ceil_div(QR, FA_MERGE_THREADS / (hd / 4)), KVH, B);
     const int pm = cs_prof_begin(CS_PROF_ATTN_MERGE, s);
     k_attn_merge<f16_t><<<mgrid, FA_MERGE_THREADS, 0, s>>>(po, pml, rows, H, KVH, hd, nqg, nsplit,
-                                                          (f16_t*)m->xn, tiled);
+                                                          (f16_t*)m->xn, tiled, m->range_flags);
     cs_prof_end(pm, s);
     return cs_launch_ok("k_attn_merge");
 }

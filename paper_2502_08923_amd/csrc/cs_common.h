@@ -105,6 +105,7 @@ struct cs_model {
     int32_t* draft_len; // [B]
     int32_t* match_pos; // [B]
     int32_t* pending;   // [B]
+    int32_t* range_flags; // device word: CS_RANGE_* bits raised by producers of float16 GEMM inputs
     int am_chunks;
 };
 
@@ -196,8 +197,9 @@ __host__ __device__ __forceinline__ int64_t cs_v_index(int64_t t, int d, int hd)
 }
 
 // bf16 weights of the tuned GEMM live in MFMA fragment order (see cs_gemm.hip)
+// (flags: device word in which CS_RANGE_WEIGHT is raised if a weight does not fit float16; may be NULL)
 int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int rowmap, int N_total,
-                           int n_off, void* dst, hipStream_t s);
+                           int n_off, void* dst, int32_t* flags, hipStream_t s);
 
 // attention: reads m->q, writes m->xn (GEMM-input type) as [R][H*hd], or, if for_o_proj, in
 // the layout the output projection's GEMM reads
@@ -233,6 +235,21 @@ __device__ __forceinline__ void cs_st(float* p, int64_t i, float v) { p[i] = v; 
 __device__ __forceinline__ void cs_st(bf16_t* p, int64_t i, float v) { p[i] = (bf16_t)v; }
 __device__ __forceinline__ float cs_ld(const f16_t* p, int64_t i) { return (float)p[i]; }
 __device__ __forceinline__ void cs_st(f16_t* p, int64_t i, float v) { p[i] = (f16_t)v; }
+
+// float32 -> float16 for the inputs of the tuned projections, saturating: a magnitude beyond the
+// largest finite float16 (65504) is stored as +-65504 instead of +-inf, and `hit` is raised (also
+// for a NaN, which is stored as it is).  In-range values convert exactly as a plain cast does.
+#define CS_F16_MAX 65504.0f
+__device__ __forceinline__ f16_t cs_f16_sat(float v, bool& hit) {
+    const float c = fminf(fmaxf(v, -CS_F16_MAX), CS_F16_MAX);
+    hit |= !(fabsf(v) <= CS_F16_MAX);
+    return (f16_t)(v != v ? v : c);
+}
+// a producer that saturated something reports it in the model's range flags (one atomic per lane
+// that hit: rare by construction)
+__device__ __forceinline__ void cs_range_report(int32_t* flags, bool hit, int bit) {
+    if (hit && flags) atomicOr(flags, bit);
+}
 
 // running (largest value, lowest index) pair of an argmax
 __device__ __forceinline__ void cs_am_take(float& bv, int& bi, float v, int i) {

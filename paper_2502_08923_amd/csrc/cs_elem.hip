@@ -59,7 +59,8 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
                                                           const float* __restrict__ part,
                                                           int nparts, int64_t part_stride, int d,
                                                           float eps, const float* __restrict__ gain,
-                                                          OutT* __restrict__ xn, int tiled) {
+                                                          OutT* __restrict__ xn, int tiled,
+                                                          int32_t* __restrict__ flags) {
     const int r = blockIdx.x;
     const int nvec = d >> 2;                 // d is a multiple of 4 (checked on the host)
     float4 v[NORM_MAXV];
@@ -91,6 +92,7 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
 #pragma unroll
     for (int w = 0; w < NORM_THREADS / CS_WAVE; ++w) tot += wsum[w];
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+    bool hit = false;
 #pragma unroll
     for (int u = 0; u < NORM_MAXV; ++u) {
         const int c = threadIdx.x + u * NORM_THREADS;
@@ -99,8 +101,9 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
             // tiled: the reader is the many-row GEMM, which wants fragment order
             const int64_t off = tiled ? cs_xt_index(r, 4 * c, d) : (int64_t)r * d + 4 * c;
             if constexpr (std::is_same<OutT, f16_t>::value) {   // one 8-byte store
-                const f16x4 o = (f16x4){(f16_t)(v[u].x * scale * gn.x), (f16_t)(v[u].y * scale * gn.y),
-                                        (f16_t)(v[u].z * scale * gn.z), (f16_t)(v[u].w * scale * gn.w)};
+                // the float16 input of the next projection: saturated, and reported if it was
+                const f16x4 o = (f16x4){cs_f16_sat(v[u].x * scale * gn.x, hit), cs_f16_sat(v[u].y * scale * gn.y, hit),
+                                        cs_f16_sat(v[u].z * scale * gn.z, hit), cs_f16_sat(v[u].w * scale * gn.w, hit)};
                 *reinterpret_cast<f16x4*>(xn + off) = o;
             } else {
                 cs_st(xn, off + 0, v[u].x * scale * gn.x);
@@ -110,6 +113,7 @@ __global__ __launch_bounds__(NORM_THREADS) void k_addnorm(float* __restrict__ x,
             }
         }
     }
+    cs_range_report(flags, hit, CS_RANGE_NORM);
 }
 
 // -------------------------------------------------------------------------------------
@@ -431,10 +435,11 @@ int cs_addnorm_launch(const cs_model* m, const float* part, int nparts,
     const int64_t ps = (int64_t)R * d;
     if (xn_out && m->fast) {
         k_addnorm<f16_t><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
-                                                    (f16_t*)xn_out, cs_gemm_x_tiled(R, next_N) ? 1 : 0);
+                                                    (f16_t*)xn_out, cs_gemm_x_tiled(R, next_N) ? 1 : 0,
+                                                    m->range_flags);
     } else
         k_addnorm<float><<<R, NORM_THREADS, 0, s>>>(m->x, part, nparts, ps, d, m->cfg.rms_eps, gain,
-                                                    (float*)xn_out, 0);
+                                                    (float*)xn_out, 0, nullptr);
     return cs_launch_ok("k_addnorm");
 }
 

@@ -262,8 +262,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
             am[o + 1] = bi;
         }
     } else {
-        // W rows alternate 16 gate rows / 16 up rows of the same 16 FFN channels
+        // W rows alternate 16 gate rows / 16 up rows of the same 16 FFN channels.  The result is
+        // the float16 input of the down projection: saturated at +-65504, and reported through the
+        // range flags (Y carries their address in this mode)
         const int F = N / 2;
+        bool hit = false;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int r = r_base + nt * 16 + lrow;
@@ -277,12 +280,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
-                    o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
+                    o[j] = cs_f16_sat(gt / (1.0f + __expf(-gt)) * up, hit);
                 }
                 // act_tiled: the down projection runs the many-row GEMM (fragment order)
                 *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
             }
         }
+        cs_range_report(reinterpret_cast<int32_t*>(Y), hit, CS_RANGE_FFN);
     }
 }
 
@@ -504,6 +508,7 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
         }
     } else {
         const int F = N / 2;
+        bool hit = false;                                   // as in k_gemm_mfma
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int r = r_base + (wm * NT + nt) * 16 + lrow;
@@ -517,11 +522,12 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
-                    o[j] = (f16_t)(gt / (1.0f + __expf(-gt)) * up);
+                    o[j] = cs_f16_sat(gt / (1.0f + __expf(-gt)) * up, hit);
                 }
                 *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
             }
         }
+        cs_range_report(reinterpret_cast<int32_t*>(Y), hit, CS_RANGE_FFN);
     }
 }
 
@@ -566,7 +572,7 @@ static bool mfma_shape_ok(int N, int K) { return K % GEMM_KC == 0 && N % 16 == 0
 // matrix (the fused q,k,v projection).  rowmap 0: source row = n.  rowmap 1: rows alternate
 // 16 gate rows (src) / 16 up rows (src2).
 __global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restrict__ src2, int N, int K,
-                         int rowmap, int N_total, int n_off, f16_t* __restrict__ dst) {
+                         int rowmap, int N_total, int n_off, f16_t* __restrict__ dst, int32_t* flags) {
     const int64_t nvec = (int64_t)N * K / 8;
     const int n_tiles = N >> 4, nt_total = N_total >> 4;
     for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec;
@@ -588,20 +594,25 @@ __global__ void k_tile_w(const bf16_t* __restrict__ src, const bf16_t* __restric
         // 11-bit significand, subnormals included); smaller magnitudes round to 2^-24 steps
         const bf16x8 wv = *reinterpret_cast<const bf16x8*>(sp + k);
         f16x8 hv;
+        bool bad = false;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) hv[j] = (f16_t)(float)wv[j];
+        for (int j = 0; j < 8; ++j) {
+            hv[j] = (f16_t)(float)wv[j];
+            bad |= !(fabsf((float)wv[j]) <= CS_F16_MAX);      // would become inf (or is a NaN)
+        }
         *reinterpret_cast<f16x8*>(dst + o) = hv;
+        if (bad && flags) atomicOr(flags, CS_RANGE_WEIGHT);
     }
 }
 
 int cs_tile_weights_launch(const void* src, const void* src2, int N, int K, int rowmap, int N_total,
-                           int n_off, void* dst, hipStream_t s) {
+                           int n_off, void* dst, int32_t* flags, hipStream_t s) {
     CS_REQUIRE(mfma_shape_ok(N, K) && N_total % 16 == 0 && n_off % 16 == 0, CS_E_UNSUPPORTED,
                "cannot tile a %d x %d matrix", N, K);
     const int64_t nvec = (int64_t)N * K / 8;
     const int blocks = (int)(cs_ceil_div(nvec, 256) < 8192 ? cs_ceil_div(nvec, 256) : 8192);
     k_tile_w<<<blocks, 256, 0, s>>>((const bf16_t*)src, (const bf16_t*)src2, N, K, rowmap, N_total, n_off,
-                                    (f16_t*)dst);
+                                    (f16_t*)dst, flags);
     return cs_launch_ok("k_tile_w");
 }
 
@@ -663,6 +674,7 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
         act_tiled = (int)cs_ceil_div(N, tile ? TG_WROWS : 128);
         Y = reinterpret_cast<float*>(m->am_val_idx);
     }
+    if (mode == CS_GEMM_SWIGLU) Y = reinterpret_cast<float*>(m->range_flags);   // see the epilogue
     const int rt_total = (int)cs_ceil_div(R, 16);
     const int r_blocks = tile ? (int)cs_ceil_div(rt_total, 18) : (int)cs_ceil_div(rt_total, 6);
     int ksplit = 1;

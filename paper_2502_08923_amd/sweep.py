@@ -172,26 +172,25 @@ def main():
     import torch
     import synth
     from paper_2502_08923_amd import binding as cs
-    import bench
+    from paper_2502_08923_amd import workload as wl
 
     cs.load_library()
     ks = [int(x) for x in args.ks.split(",")]
     kmax = max(ks)
-
-    class A:  # the benchmark's workload builder, with room for the largest block
-        shape, layers, batch, k, gamma, doc, hist = "8b", args.layers, 8, kmax, 3, 2048, 16384
-    st = bench.build_workload(A)
+    # the benchmark's workload, with room for the largest block
+    shape, model = wl.build_model("8b", args.layers, 8, kmax)
+    hists = [synth.history_cfg4(b, vocab=shape.vocab, k=kmax)["tokens"] for b in range(8)]
+    st = wl.build_state(shape, model, 8, kmax, 3, hists)
     B = st["B"]
 
     rows = []
     for k in ks:
-        st["k"] = k
         for _ in range(2):
-            bench.one_step(st, cs)
+            wl.one_step(st, k=k)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            bench.one_step(st, cs)
+            wl.one_step(st, k=k)
         torch.cuda.synchronize()
         t = (time.perf_counter() - t0) / args.steps
         rows.append({"k": k, "ms_per_step": t * 1e3})

@@ -404,6 +404,69 @@ def test_merged_decode_bf16_models_and_errors():
         h.destroy()
 
 
+def test_float16_range_is_saturated_and_reported():
+    """The tuned projections take float16 inputs.  Activations beyond +-65504 are saturated, not
+    turned into infinities, the producer raises its bit in the model's status word, and the logits
+    are those of the oracle with the same clip on every projection input.  Weights beyond the
+    range are refused when the model is created."""
+    shape = MINI64
+    CLIP = 65504.0
+    rng = np.random.default_rng(77)
+    prompt = rng.integers(0, shape.vocab, 7).tolist()
+    draft = rng.integers(0, shape.vocab, 10).tolist()
+
+    def scaled_bits(bits, f):
+        return synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(bits) * np.float32(f))
+
+    def make(case):
+        w = synth.model_weights(shape, 909, threads=4)
+        if case == "ffn":        # gate and up ~ 300: their SwiGLU product passes 65504
+            w["layers"][0]["norm2"] = (w["layers"][0]["norm2"] * 300.0).astype(np.float32)
+        elif case == "norm":     # the final norm's output itself passes 65504
+            w["final_norm"] = (w["final_norm"] * 3.0e4).astype(np.float32)
+        elif case == "attn":     # values ~ 1e5: attention outputs pass 65504
+            w["layers"][1]["wv"] = scaled_bits(w["layers"][1]["wv"], 2.0 ** 17)
+        return w
+
+    for case, bit in (("none", 0), ("ffn", cs.CS_RANGE_FFN), ("norm", cs.CS_RANGE_NORM), ("attn", cs.CS_RANGE_ATTN)):
+        w = make(case)
+        model = cs.Model(w, max_batch=1, max_k=10)
+        kv = cs.KV(model, 1, 64)
+        cs.cs_prefill(model, kv, 0, prompt)
+        model.range_status(clear=True)
+        acc, nx, logits = cs.cs_verify(model, kv, t32([prompt[-1]]), t32([draft]), t32([10]), 10, want_logits=True)
+        flags = model.range_status(clear=True)
+        got = logits[0].cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all(), case
+        okv = orc.KVCache(shape, 64)
+        orc.forward_block(w, okv, prompt[:-1], return_hidden=True, act_clip=CLIP)
+        okv.truncate(len(prompt) - 1)
+        okv2 = orc.KVCache(shape, 64)
+        okv2.k[:], okv2.v[:] = okv.k, okv.v
+        okv2.truncate(okv.length)
+        clipped = orc.forward_block(w, okv, [prompt[-1]] + draft, act_clip=CLIP)
+        plain = orc.forward_block(w, okv2, [prompt[-1]] + draft)
+        tol = 2e-2 * max(1.0, float(np.abs(clipped).max()))
+        assert np.abs(got - clipped).max() <= tol, (case, np.abs(got - clipped).max(), tol)
+        if bit:
+            assert flags & bit, (case, flags)
+            assert np.abs(plain - clipped).max() > 4 * tol, case        # the clip decided the result
+            with pytest.raises(cs.CopySpecError) as e:                  # a synchronous loop says so
+                cs.cs_decode(model, kv, prompt, 4, 3, 10)
+            assert e.value.code == cs.CS_E_RANGE
+        else:
+            assert flags == 0 and np.array_equal(plain, clipped)
+            cs.cs_decode(model, kv, prompt, 4, 3, 10)
+        kv.destroy()
+        model.destroy()
+    w = make("none")
+    w["layers"][1]["wo"][3, 5] = synth.f32_to_bf16_bits(np.array([1.0e5], dtype=np.float32))[0]
+    with pytest.raises(cs.CopySpecError) as e:
+        cs.Model(w, max_batch=1, max_k=10)
+    assert e.value.code == -6
+    cs.Model(w, max_batch=1, max_k=10, plain=True).destroy()          # the plain kernels have no such limit
+
+
 def test_capacity_and_argument_errors(tiny):
     w, model = tiny
     kv = cs.KV(model, 1, 64)

@@ -74,6 +74,45 @@ def test_forward_matches_library_llama(small_w):
     assert np.abs(tail - got[20:]).max() < 1e-11
 
 
+def test_act_clip_matches_library_llama_with_clamped_linear_inputs():
+    """The optional input range of the projections (act_clip): the same weights in the library
+    implementation, with a hook on every linear layer that clamps its input, give the same
+    logits.  Gains are scaled so that every kind of projection input leaves the range; a clip
+    that nothing reaches, and no clip, are the unclipped model."""
+    w = synth.model_weights(SMALL, 4321, threads=1)
+    w["layers"][0]["norm2"] = (w["layers"][0]["norm2"] * 3.0).astype(np.float32)    # gate/up input, SwiGLU output
+    w["layers"][1]["norm1"] = (w["layers"][1]["norm1"] * 2.5).astype(np.float32)    # q/k/v input, attention output
+    w["final_norm"] = (w["final_norm"] * 2.0).astype(np.float32)                    # lm_head input
+    m = _hf_model(w)
+    clip = 1.5
+    seen = {}
+
+    def clamp_input(name):
+        def hook(mod, args):
+            seen[name] = max(seen.get(name, 0.0), float(args[0].abs().max()))
+            return (args[0].clamp(-clip, clip),)
+        return hook
+
+    hooks = [mod.register_forward_pre_hook(clamp_input(name.split(".")[-1]))
+             for name, mod in m.named_modules() if isinstance(mod, torch.nn.Linear)]
+    assert len(hooks) == 7 * SMALL.n_layers + 1
+    rng = np.random.default_rng(6)
+    toks = rng.integers(0, SMALL.vocab, 29)
+    with torch.no_grad():
+        ref = m(torch.from_numpy(toks)[None]).logits[0].numpy()
+    for h in hooks:
+        h.remove()
+    # the clip bites at every kind of projection input
+    for name in ("q_proj", "o_proj", "gate_proj", "down_proj", "lm_head"):
+        assert seen[name] > clip, (name, seen[name])
+    got = orc.forward_block(w, orc.KVCache(SMALL, 32), toks, store_dtype="f64", act_clip=clip)
+    assert np.abs(got - ref).max() < 5e-6
+    plain = orc.forward_block(w, orc.KVCache(SMALL, 32), toks, store_dtype="f64")
+    assert np.abs(plain - got).max() > 1e-2                       # ... and changes the result
+    loose = orc.forward_block(w, orc.KVCache(SMALL, 32), toks, store_dtype="f64", act_clip=1e30)
+    assert np.array_equal(loose, plain)
+
+
 def test_block_equals_sequential_rows(small_w):
     """Causality: an (m+1)-row block gives the logits of m+1 single-row steps."""
     rng = np.random.default_rng(4)
