@@ -319,13 +319,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 #define TG_WROWS 256
 
 
-template <int NT, int MODE>
+// XT: 16-row X tiles per workgroup (8..18).  The two wave rows split them as evenly as whole tiles
+// allow: wave row 0 takes the first NT0 = ceil(XT/2), wave row 1 the other NT1 = floor(XT/2); with
+// XT odd (528 rows in two blocks: 17 tiles) the two waves of a SIMD, one of each row, then multiply
+// 4*17 tile pairs per chunk where an even split rounded up would make it 4*18.
+template <int XT, int MODE>
 __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict__ X,
                                                          const f16_t* __restrict__ W,
                                                          float* __restrict__ Y,
                                                          f16_t* __restrict__ act, int R, int N, int K,
                                                          int Ks, int RB, int act_tiled) {
-    constexpr int XT = 2 * NT;                        // X row tiles per workgroup
+    constexpr int NT0 = (XT + 1) / 2, NT1 = XT / 2;   // X tiles of a wave in wave row 0 / 1
     constexpr int NBLK = 16 + XT;                     // 1 KB blocks per stage: 16 W tiles, then X tiles
     constexpr int XLD = (XT + 7) / 8;                 // X loads per wave per stage (the last may be partial)
     constexpr int LDMIN = 2 + XT / 8;                 // loads every wave issues per stage
@@ -341,7 +345,7 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
     const int grp = blockIdx.x / (8 * RB), rem = blockIdx.x % (8 * RB);
     const int w_tile = grp * 8 + (rem & 7);
     if (w_tile * TG_WROWS >= N) return;
-    const int r_base = (rem >> 3) * 32 * NT;
+    const int r_base = (rem >> 3) * 16 * XT;
     const int n_tiles = N >> 4;
     const int64_t chunk_stride = (int64_t)n_tiles * 4 * 512;
 
@@ -387,161 +391,175 @@ __global__ __launch_bounds__(TG_THREADS) void k_gemm_dma(const f16_t* __restrict
         for (int idx = 0; idx < NL; ++idx) issue_one(sb, c, idx);
     };
     const unsigned char* a_base = lds + wn * 4 * 1024 + lane * 16;
-    const unsigned char* b_base = lds + (16 + wm * NT) * 1024 + lane * 16;
+    const unsigned char* b_base = lds + (16 + wm * NT0) * 1024 + lane * 16;
     auto a_frag = [&](int sb, int mt) { return *reinterpret_cast<const f16x8*>(a_base + sb * STAGE + mt * 1024); };
     auto b_frag = [&](int sb, int nt) { return *reinterpret_cast<const f16x8*>(b_base + sb * STAGE + nt * 1024); };
-
-    f32x4 acc[4][NT];
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    f16x8 a[4], bq[4];
+    const int n_wave = w_tile * TG_WROWS + wn * 64;
 
     // wait until at most `n` of this wave's loads are outstanding, then meet the other waves.
     // (A plain s_barrier: the workgroup fence of __syncthreads would drain every load in flight.)
 #define TD_SYNC(n) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(n) : "memory")
-    issue(0, 0);
-    issue(1, 1);
-    issue(2, 2);
-    TD_SYNC(2 * LDMIN);                                        // chunk 0 has landed everywhere
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) a[mt] = a_frag(0, mt);
-    bq[0] = b_frag(0, 0);
-    bq[1] = b_frag(0, 1);
-    bq[2] = b_frag(0, 2);
 
-    // four chunks, one per stage.  TAIL marks the last trip, where nothing more is requested.
-    auto trip = [&](int c0, auto tailc) {
-        constexpr bool TAIL = decltype(tailc)::value;
+    // Everything a wave does with its NT X tiles: the multiply loop and the epilogue.  Both wave rows
+    // run it with their own NT; the requests, the waits and the barriers are the same in both, so
+    // the two instantiations stay in step.
+    auto body = [&](auto nt_tag) {
+        constexpr int NT = decltype(nt_tag)::value;
+        const int xt0 = wm * NT0;                        // first X tile of this wave within the block
+        f32x4 acc[4][NT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            // chunk c+1 (requested two iterations ago) must be in LDS before its first fragments
-            // are read at the end of this iteration; only chunk c+2 may still be in flight
-            if (TAIL && u >= 2) TD_SYNC(0);
-            else TD_SYNC(LDMIN);
-            // chunk c+3 goes to the stage of chunk c-1, free since the barrier.  Its requests are
-            // spread over the iteration, one after every few MFMA groups: a wave issues in order,
-            // so a burst of requests that the memory pipeline takes one at a time would hold
-            // back the MFMAs behind it, in all eight waves at once right after the barrier.
-            const bool req = !TAIL || u == 0;
-            const bool more = !TAIL || u < 3;
-            int next_req = 0;
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        f16x8 a[4], bq[4];
+
+        issue(0, 0);
+        issue(1, 1);
+        issue(2, 2);
+        TD_SYNC(2 * LDMIN);                                        // chunk 0 has landed everywhere
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) a[mt] = a_frag(0, mt);
+        bq[0] = b_frag(0, 0);
+        bq[1] = b_frag(0, 1);
+        bq[2] = b_frag(0, 2);
+
+        // four chunks, one per stage.  TAIL marks the last trip, where nothing more is requested.
+        auto trip = [&](int c0, auto tailc) {
+            constexpr bool TAIL = decltype(tailc)::value;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                // chunk c+1 (requested two iterations ago) must be in LDS before its first fragments
+                // are read at the end of this iteration; only chunk c+2 may still be in flight
+                if (TAIL && u >= 2) TD_SYNC(0);
+                else TD_SYNC(LDMIN);
+                // chunk c+3 goes to the stage of chunk c-1, free since the barrier.  Its requests are
+                // spread over the iteration, one after every few MFMA groups: a wave issues in order,
+                // so a burst of requests that the memory pipeline takes one at a time would hold
+                // back the MFMAs behind it, in all eight waves at once right after the barrier.
+                const bool req = !TAIL || u == 0;
+                const bool more = !TAIL || u < 3;
+                int next_req = 0;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    if (req && next_req < NL && nt == (next_req * NT) / NL) {
+                        issue_one((u + 3) & 3, c0 + u + 3, next_req);
+                        ++next_req;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    const int q = u * NT + nt;                        // position in the B fragment stream
+                    if (nt + 3 < NT) bq[(q + 3) & 3] = b_frag(u, nt + 3);              // three tiles ahead
+                    else if (more) bq[(q + 3) & 3] = b_frag((u + 1) & 3, nt + 3 - NT);
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) {
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bq[q & 3], acc[mt][nt], 0, 0, 0);
+                        // an A fragment is replaced by the next chunk's right after its last use
+                        if (nt == NT - 1 && more) a[mt] = a_frag((u + 1) & 3, mt);
+                    }
+                }
+            }
+        };
+        int c0 = 0;
+        for (; c0 + 4 < nchunks; c0 += 4) trip(c0, std::false_type{});
+        trip(c0, std::true_type{});
+
+        // epilogue: acc[mt][nt][j] = Y[r_base + (xt0 + nt)*16 + lrow][n_wave + mt*16 + 4g + j]
+        if (MODE == CS_GEMM_STORE) {
+            float* __restrict__ y = Y + (int64_t)blockIdx.y * R * N;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                if (req && next_req < NL && nt == (next_req * NT) / NL) {
-                    issue_one((u + 3) & 3, c0 + u + 3, next_req);
-                    ++next_req;
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                const int q = u * NT + nt;                        // position in the B fragment stream
-                if (nt + 3 < NT) bq[(q + 3) & 3] = b_frag(u, nt + 3);              // three tiles ahead
-                else if (more) bq[(q + 3) & 3] = b_frag((u + 1) & 3, nt + 3 - NT);
+                const int r = r_base + (xt0 + nt) * 16 + lrow;
+                if (r >= R) continue;
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt) {
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], bq[q & 3], acc[mt][nt], 0, 0, 0);
-                    // an A fragment is replaced by the next chunk's right after its last use
-                    if (nt == NT - 1 && more) a[mt] = a_frag((u + 1) & 3, mt);
+                    const int n = n_wave + mt * 16 + 4 * g;
+                    if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
                 }
             }
+        } else if (MODE == CS_GEMM_ARGMAX) {
+            // as in k_gemm_mfma: the largest of the workgroup's 256 columns per row, lowest column on ties
+            int32_t* __restrict__ am = reinterpret_cast<int32_t*>(Y);
+            const int nch = act_tiled;
+            float* rv = reinterpret_cast<float*>(lds);                        // [4 column waves][16*XT rows]
+            int* ri = reinterpret_cast<int*>(lds) + 4 * 16 * XT;
+            __syncthreads();                                    // every wave is past its last fragment
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float bv = -INFINITY;
+                int bi = 0x7fffffff;
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) {
+                    if (n_wave + mt * 16 >= N) continue;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float v = acc[mt][nt][j];
+                        if (v > bv) { bv = v; bi = n_wave + mt * 16 + 4 * g + j; }
+                    }
+                }
+#pragma unroll
+                for (int o = 16; o <= 32; o <<= 1) {
+                    const float ov = __shfl_xor(bv, o, 64);
+                    const int oi = __shfl_xor(bi, o, 64);
+                    cs_am_take(bv, bi, ov, oi);
+                }
+                if (g == 0) {
+                    rv[wn * 16 * XT + (xt0 + nt) * 16 + lrow] = bv;
+                    ri[wn * 16 * XT + (xt0 + nt) * 16 + lrow] = bi;
+                }
+            }
+            __syncthreads();
+            if (tid < 16 * XT && r_base + tid < R) {
+                float bv = rv[tid];
+                int bi = ri[tid];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) cs_am_take(bv, bi, rv[w * 16 * XT + tid], ri[w * 16 * XT + tid]);
+                const int64_t o = ((int64_t)(r_base + tid) * nch + w_tile) * 2;
+                am[o] = __float_as_int(bv);
+                am[o + 1] = bi;
+            }
+        } else {
+            const int F = N / 2;
+            bool hit = false;                                   // as in k_gemm_mfma
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int r = r_base + (xt0 + nt) * 16 + lrow;
+                if (r >= R) continue;
+#pragma unroll
+                for (int mp = 0; mp < 2; ++mp) {
+                    const int n = n_wave + mp * 32;
+                    if (n >= N) continue;
+                    const int f = n / 2 + 4 * g;
+                    f16x4 o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
+                        o[j] = cs_f16_sat(gt / (1.0f + __expf(-gt)) * up, hit);
+                    }
+                    *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
+                }
+            }
+            cs_range_report(reinterpret_cast<int32_t*>(Y), hit, CS_RANGE_FFN);
         }
     };
-    int c0 = 0;
-    for (; c0 + 4 < nchunks; c0 += 4) trip(c0, std::false_type{});
-    trip(c0, std::true_type{});
-#undef TD_SYNC
-
-    // epilogue: acc[mt][nt][j] = Y[r_base + (wm*NT + nt)*16 + lrow][n_wave + mt*16 + 4g + j]
-    const int n_wave = w_tile * TG_WROWS + wn * 64;
-    if (MODE == CS_GEMM_STORE) {
-        float* __restrict__ y = Y + (int64_t)blockIdx.y * R * N;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int r = r_base + (wm * NT + nt) * 16 + lrow;
-            if (r >= R) continue;
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const int n = n_wave + mt * 16 + 4 * g;
-                if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
-            }
-        }
-    } else if (MODE == CS_GEMM_ARGMAX) {
-        // as in k_gemm_mfma: the largest of the workgroup's 256 columns per row, lowest column on ties
-        int32_t* __restrict__ am = reinterpret_cast<int32_t*>(Y);
-        const int nch = act_tiled;
-        float* rv = reinterpret_cast<float*>(lds);                        // [4 column waves][32*NT rows]
-        int* ri = reinterpret_cast<int*>(lds) + 4 * 32 * NT;
-        __syncthreads();                                    // every wave is past its last fragment
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            float bv = -INFINITY;
-            int bi = 0x7fffffff;
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                if (n_wave + mt * 16 >= N) continue;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float v = acc[mt][nt][j];
-                    if (v > bv) { bv = v; bi = n_wave + mt * 16 + 4 * g + j; }
-                }
-            }
-#pragma unroll
-            for (int o = 16; o <= 32; o <<= 1) {
-                const float ov = __shfl_xor(bv, o, 64);
-                const int oi = __shfl_xor(bi, o, 64);
-                cs_am_take(bv, bi, ov, oi);
-            }
-            if (g == 0) {
-                rv[wn * 32 * NT + (wm * NT + nt) * 16 + lrow] = bv;
-                ri[wn * 32 * NT + (wm * NT + nt) * 16 + lrow] = bi;
-            }
-        }
-        __syncthreads();
-        if (tid < 32 * NT && r_base + tid < R) {
-            float bv = rv[tid];
-            int bi = ri[tid];
-#pragma unroll
-            for (int w = 1; w < 4; ++w) cs_am_take(bv, bi, rv[w * 32 * NT + tid], ri[w * 32 * NT + tid]);
-            const int64_t o = ((int64_t)(r_base + tid) * nch + w_tile) * 2;
-            am[o] = __float_as_int(bv);
-            am[o + 1] = bi;
-        }
+    if constexpr (NT0 == NT1) {
+        body(std::integral_constant<int, NT0>{});
     } else {
-        const int F = N / 2;
-        bool hit = false;                                   // as in k_gemm_mfma
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int r = r_base + (wm * NT + nt) * 16 + lrow;
-            if (r >= R) continue;
-#pragma unroll
-            for (int mp = 0; mp < 2; ++mp) {
-                const int n = n_wave + mp * 32;
-                if (n >= N) continue;
-                const int f = n / 2 + 4 * g;
-                f16x4 o;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float gt = acc[2 * mp][nt][j], up = acc[2 * mp + 1][nt][j];
-                    o[j] = cs_f16_sat(gt / (1.0f + __expf(-gt)) * up, hit);
-                }
-                *reinterpret_cast<f16x4*>(act + (act_tiled ? cs_xt_index(r, f, F) : (int64_t)r * F + f)) = o;
-            }
-        }
-        cs_range_report(reinterpret_cast<int32_t*>(Y), hit, CS_RANGE_FFN);
+        if (wm == 0) body(std::integral_constant<int, NT0>{});
+        else body(std::integral_constant<int, NT1>{});
     }
+#undef TD_SYNC
 }
 
-template <int NT>
+template <int XT>
 static int launch_tile(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int R, int N, int K, int mode,
                        int ksplit, int act_tiled, hipStream_t s) {
     CS_REQUIRE(((int64_t)R + 15) * K < ((int64_t)1 << 31), CS_E_UNSUPPORTED, "R*K too large for the many-row GEMM");
     const int Ks = (int)cs_round_up(cs_ceil_div(K, ksplit), GEMM_KC);
-    const int RB = (int)cs_ceil_div(R, 32 * NT);
+    const int RB = (int)cs_ceil_div(R, 16 * XT);
     dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, TG_WROWS), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
-    if (mode == CS_GEMM_STORE) k_gemm_dma<NT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
-    else if (mode == CS_GEMM_ARGMAX) k_gemm_dma<NT, CS_GEMM_ARGMAX><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
-    else k_gemm_dma<NT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+    if (mode == CS_GEMM_STORE) k_gemm_dma<XT, CS_GEMM_STORE><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+    else if (mode == CS_GEMM_ARGMAX) k_gemm_dma<XT, CS_GEMM_ARGMAX><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+    else k_gemm_dma<XT, CS_GEMM_SWIGLU><<<grid, TG_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     cs_prof_end(pg, s);
     return cs_launch_ok("k_gemm_dma");
 }
@@ -694,13 +712,18 @@ int cs_gemm_launch(const cs_model* m, const void* X, const void* W, float* Y, in
     const f16_t* w = (const f16_t*)W;
     f16_t* act = (f16_t*)m->act;
     if (tile) {
-        switch ((int)cs_ceil_div(rt, 2)) {           // 16-row X tiles per wave
-            case 1: case 2: case 3: case 4: return launch_tile<4>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
-            case 5: return launch_tile<5>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
-            case 6: return launch_tile<6>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
-            case 7: return launch_tile<7>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
-            case 8: return launch_tile<8>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
-            default: return launch_tile<9>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+        switch (rt) {                                // 16-row X tiles per workgroup
+            case 9: return launch_tile<9>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 10: return launch_tile<10>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 11: return launch_tile<11>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 12: return launch_tile<12>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 13: return launch_tile<13>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 14: return launch_tile<14>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 15: return launch_tile<15>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 16: return launch_tile<16>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 17: return launch_tile<17>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            case 18: return launch_tile<18>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);
+            default: return launch_tile<8>(x, w, Y, act, R, N, K, mode, nparts, act_tiled, s);   // up to 128 rows
         }
     }
     switch (rt) {
