@@ -322,6 +322,9 @@ def main():
     ap.add_argument("--hist", type=int, default=16384)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the batch-16 / k=32 block of the default run")
+    ap.add_argument("--no-plant", action="store_true",
+                    help="leave the drafts as the histories give them (nothing accepted); for counter runs, "
+                         "which then see the timed step's launches only")
     ap.add_argument("--no-scan", action="store_true")
     ap.add_argument("--prefill", type=int, default=0,
                     help="time the ingestion of an N-token prompt (one stream) instead of the step")
@@ -364,7 +367,9 @@ def main():
     hists = [synth.history_cfg4(b, vocab=shape.vocab, doc=args.doc, hist=args.hist, k=k)["tokens"]
              for b in range(B)]
     st = wl.build_state(shape, model, B, k, args.gamma, hists, host_kv_streams=() if args.no_cpu else (0,))
-    planted = wl.plant_acceptance(st, [min(t, k) for t in (TAUS * ((B + 15) // 16))[:B]]) if k > 0 else None
+    planted = None
+    if k > 0 and not args.no_plant:
+        planted = wl.plant_acceptance(st, [min(t, k) for t in (TAUS * ((B + 15) // 16))[:B]])
 
     # timed region: exactly `steps` whole steps, inputs resident in HBM
     classes = ["scan", "gemm", "attn", "attn_merge", "argmax", "lm_head"]

@@ -45,28 +45,23 @@ __device__ __forceinline__ bool rest_matches(const int32_t* __restrict__ h, int 
     return true;
 }
 
-// chunk_best[b][s] = best key among the chunks s, s + gridDim.x, ... of stream b, -1 if none.
-// A workgroup walks its chunks with a stride of the grid width, so every candidate position is
-// visited whatever the number of slots the launch was given.
-template <int POLICY>
-__global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict__ hist,
-                                                       int64_t stride,
-                                                       const int32_t* __restrict__ len, int gamma,
-                                                       int vec_ok, int64_t* __restrict__ chunk_best,
-                                                       int nslots) {
-    const int b = blockIdx.y;
-    const int n = len[b];
-    const int32_t* __restrict__ h = hist + (int64_t)b * stride;
+// The candidates begin, begin + 1, ... of history h[0..n) in strides of THREADS*16 positions
+// (`first` and `step` count such strides): a thread loads 16 bytes (4 tokens) per step, compares
+// them with the first token of the suffix and only on a hit checks the other gamma - 1.  Returns
+// the thread's best key.  Every lane runs every iteration (positions past the end never hit), so
+// the wave stays converged for the cooperative context measurement.
+template <int POLICY, int THREADS>
+__device__ __forceinline__ int64_t scan_strides(const int32_t* __restrict__ h, int n, int gamma, int vec_ok,
+                                                int first, int step) {
+    constexpr int STRIDE = THREADS * 16;
     const int cnt = n - 2 * gamma + 1;            // candidate starts are 0 .. cnt-1
     int64_t best = -1;
     const int s0 = cnt > 0 ? h[n - gamma] : 0;
-    for (int64_t begin64 = (int64_t)blockIdx.x * SCAN_CHUNK; begin64 < cnt; begin64 += (int64_t)nslots * SCAN_CHUNK) {
+    for (int64_t begin64 = (int64_t)first * STRIDE; begin64 < cnt; begin64 += (int64_t)step * STRIDE) {
         const int begin = (int)begin64;
-        const int end = (int)min((int64_t)cnt, begin64 + SCAN_CHUNK);
-        // every lane runs every iteration (positions past the end just never hit), so the wave
-        // stays converged for the cooperative context measurement
-        for (int it = 0; it < SCAN_CHUNK / (SCAN_THREADS * 4); ++it) {
-            const int p = begin + (it * SCAN_THREADS + (int)threadIdx.x) * 4;
+        const int end = (int)min((int64_t)cnt, begin64 + STRIDE);
+        for (int it = 0; it < 4; ++it) {
+            const int p = begin + (it * THREADS + (int)threadIdx.x) * 4;
             int t[4];
             if (vec_ok && p + 3 < n) {
                 const int4 v = *reinterpret_cast<const int4*>(h + p);
@@ -102,24 +97,63 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict
             }
         }
     }
-    // workgroup reduction: wave shuffle, then LDS across the 4 waves
+    return best;
+}
+
+// best key of the workgroup (valid in every thread): wave shuffle, then LDS across the waves
+template <int POLICY, int THREADS>
+__device__ __forceinline__ int64_t scan_block_best(int64_t best) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         const int64_t other = __shfl_xor(best, o, 64);
         best = key_better<POLICY>(best, other);
     }
-    __shared__ int64_t wave_best[SCAN_THREADS / CS_WAVE];
+    __shared__ int64_t wave_best[THREADS / CS_WAVE];
     if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int64_t r = wave_best[0];
+    int64_t r = wave_best[0];
 #pragma unroll
-        for (int w = 1; w < SCAN_THREADS / CS_WAVE; ++w) r = key_better<POLICY>(r, wave_best[w]);
-        chunk_best[(int64_t)b * nslots + blockIdx.x] = r;
-    }
+    for (int w = 1; w < THREADS / CS_WAVE; ++w) r = key_better<POLICY>(r, wave_best[w]);
+    return r;
 }
 
-// One wave per stream: reduce the chunk results, then copy the draft (App. B.1, the chunk that follows the match).
+// chunk_best[b][s] = best key among the chunks s, s + gridDim.x, ... of stream b, -1 if none
+// (SCAN_CHUNK = SCAN_THREADS * 16 positions per chunk).  A workgroup walks its chunks with a stride
+// of the grid width, so every candidate position is visited whatever the number of slots the
+// launch was given.
+template <int POLICY>
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan(const int32_t* __restrict__ hist,
+                                                       int64_t stride,
+                                                       const int32_t* __restrict__ len, int gamma,
+                                                       int vec_ok, int64_t* __restrict__ chunk_best,
+                                                       int nslots) {
+    static_assert(SCAN_CHUNK == SCAN_THREADS * 16, "chunk size and stride of scan_strides agree");
+    const int b = blockIdx.y;
+    const int64_t best = scan_strides<POLICY, SCAN_THREADS>(hist + (int64_t)b * stride, len[b], gamma, vec_ok,
+                                                            blockIdx.x, nslots);
+    const int64_t r = scan_block_best<POLICY, SCAN_THREADS>(best);
+    if (threadIdx.x == 0) chunk_best[(int64_t)b * nslots + blockIdx.x] = r;
+}
+
+// what follows the search: positions from the key, the draft copied from the history (App. B.1,
+// the chunk that follows the match), unused slots -1.  Called by every thread of the workgroup.
+__device__ __forceinline__ void gather_draft(const int32_t* __restrict__ h, int n, int gamma, int k, int64_t key,
+                                             int b, const int32_t* __restrict__ room,
+                                             int32_t* __restrict__ match_pos, int32_t* __restrict__ src_pos,
+                                             int32_t* __restrict__ draft, int32_t* __restrict__ draft_len) {
+    const int best = key < 0 ? -1 : (int)(key & 0x7fffffff);      // low word: the position
+    const int src = best < 0 ? -1 : best + gamma;
+    int dl = best < 0 ? 0 : min(k, n - src);
+    if (room) dl = min(dl, max(room[b] - 1, 0));   // never draft past the emission budget
+    if (threadIdx.x == 0) {
+        if (match_pos) match_pos[b] = best;
+        if (src_pos) src_pos[b] = src;
+        draft_len[b] = dl;
+    }
+    for (int i = threadIdx.x; i < k; i += blockDim.x) draft[(int64_t)b * k + i] = i < dl ? h[src + i] : -1;
+}
+
+// One wave per stream: reduce the chunk results, then copy the draft.
 __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist, int64_t stride,
                                                const int32_t* __restrict__ len, int gamma, int k,
                                                int policy, const int64_t* __restrict__ chunk_best,
@@ -129,8 +163,6 @@ __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist,
                                                int32_t* __restrict__ draft,
                                                int32_t* __restrict__ draft_len) {
     const int b = blockIdx.x;
-    const int n = len[b];
-    const int32_t* __restrict__ h = hist + (int64_t)b * stride;
     int64_t key = -1;
     for (int c = threadIdx.x; c < nchunks; c += 64) {
         const int64_t v = chunk_best[(int64_t)b * nchunks + c];
@@ -141,16 +173,7 @@ __global__ __launch_bounds__(64) void k_gather(const int32_t* __restrict__ hist,
         const int64_t other = __shfl_xor(key, o, 64);
         key = policy == CS_POLICY_FIRST ? key_better<CS_POLICY_FIRST>(key, other) : key_better<CS_POLICY_RIGHTMOST>(key, other);
     }
-    const int best = key < 0 ? -1 : (int)(key & 0x7fffffff);      // low word: the position
-    const int src = best < 0 ? -1 : best + gamma;
-    int dl = best < 0 ? 0 : min(k, n - src);
-    if (room) dl = min(dl, max(room[b] - 1, 0));   // never draft past the emission budget
-    if (threadIdx.x == 0) {
-        if (match_pos) match_pos[b] = best;
-        if (src_pos) src_pos[b] = src;
-        draft_len[b] = dl;
-    }
-    for (int i = threadIdx.x; i < k; i += 64) draft[(int64_t)b * k + i] = i < dl ? h[src + i] : -1;
+    gather_draft(hist + (int64_t)b * stride, len[b], gamma, k, key, b, room, match_pos, src_pos, draft, draft_len);
 }
 
 // Number of key slots per stream a scan over histories of up to max_len tokens wants (one per

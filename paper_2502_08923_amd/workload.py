@@ -48,9 +48,12 @@ def build_state(shape, model, B: int, k: int, gamma: int, hists, host_kv_streams
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.seed_for(4) + 17)
     host_kv = {b: [] for b in host_kv_streams}
-    t0 = time.time()
+    t0 = t_log = time.time()
     shp = (shape.n_kv_heads, L, shape.head_dim)
     for layer in range(shape.n_layers):
+        if time.time() - t_log > 20.0:                     # slow under a profiler: show that it moves
+            log(f"[workload] filling the KV cache: layer {layer} of {shape.n_layers}")
+            t_log = time.time()
         for b in range(B):
             if b in host_kv:
                 kr, vr = synth.random_kv(shape, L, synth.seed_for(4), layer, b)
