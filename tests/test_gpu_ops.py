@@ -246,6 +246,19 @@ def test_attention_prompt_block(k_ramp):
     assert worst < 1e-2, worst
 
 
+@pytest.mark.parametrize("rows", [6, 21, 51, 101])
+def test_attention_block_size_sweep(rows):
+    """Block sizes of the paper's sweep (Sec. 5.3, Table 4: 5, 10, 50, 100 draft tokens; 20 added):
+    6 rows fit one 48-row query group, 21 rows fill two groups of a three-group workgroup column
+    partly, 51 and 101 rows need two and three columns with a ragged last one."""
+    w = synth.model_weights(HOST, 99, threads=16)
+    m = cs.Model(w, max_batch=5, max_k=100)
+    sample = [(0, 0), (0, 31), (1, 13), (2, 5), (3, 22), (4, 9)]
+    worst = _attention_case(m, HOST, [2500, 777, 40, 0, 4100], rows, sample, seed=30 + rows, poison=True)
+    m.destroy()
+    assert worst < 1e-2, worst
+
+
 def test_attention_hd64():
     shape = ModelShape("w-hd64", 1, 2048, 32, 8, 64, 8192, 1024, 10000.0, 1e-5, "bf16")
     w = synth.model_weights(shape, 5, threads=16)
@@ -338,4 +351,15 @@ def test_verify_llama8b_width_batch8():
     4 of the 32 layers; the oracle checks two sampled streams."""
     shape = synth.LLAMA_8B.with_layers(4)
     worst = _deep_verify(shape, 8, 18431, 10, [0, 5], seed=synth.seed_for(4))
+    assert worst <= 2e-2, worst
+
+
+@pytest.mark.parametrize("B,k", [(1, 50), (1, 100), (8, 100), (8, 20), (8, 5)])
+def test_verify_llama8b_width_block_size_sweep(B, k):
+    """Block sizes of the paper's sweep (Sec. 5.3, Table 4) at the 8B width, one layer, short cache:
+    51 and 101 rows of a single stream (the paper's batch size) go through the weight-streaming
+    projections with one and two row blocks and the wide-block attention; 808 rows (batch 8,
+    k = 100) take three row blocks of the many-row projections; 168 and 48 rows sit between."""
+    shape = synth.LLAMA_8B.with_layers(1)
+    worst = _deep_verify(shape, B, 300, k, [B - 1], seed=synth.seed_for(5) + 10 * k + B)
     assert worst <= 2e-2, worst
