@@ -281,6 +281,10 @@ typedef struct cs_stats {
  * Requires kv batch == 1 and capacity >= prompt_len + max_new + k + 1.
  * cs_decode_greedy is plain greedy decoding through the same kernels (draft length 0);
  * by the paper's construction both emit the same tokens.  Synchronous.
+ * Lengths, budgets and step outcomes live on the device; the loops enqueue up to four steps
+ * (never more than the remaining budget needs at full acceptance) before the host reads their
+ * outcome in one copy, so only a stop token can leave steps of a burst unused.  On return the
+ * cache of a stream holds prompt_len + n_out - 1 rows (every token but the last one emitted).
  * ---------------------------------------------------------------------------------- */
 int cs_decode(cs_model* m, cs_kv* kv, const int32_t* prompt /*host*/, int64_t prompt_len,
               int64_t max_new, int32_t gamma, int32_t k, int32_t policy, int32_t eos_id,

@@ -721,6 +721,104 @@ extern "C" int cs_prefill(cs_model* m, cs_kv* kv, int32_t stream_idx, const int3
     return CS_OK;
 }
 
+// Steps the decode loops enqueue between two host reads.  A step whose streams have used up
+// their budgets still costs a forward pass, so a burst never holds more steps than the stream
+// with the most tokens left needs at full acceptance; only a stop token can make the tail of
+// a burst idle.
+static const int DECODE_BURST = 4;
+
+// room for the histories of a decode loop: every step of a burst is checked against the host's
+// upper bound of the lengths, which grows by k+1 per step until the next read
+static int64_t decode_stride(int64_t max_len, int64_t max_new, int k) {
+    return cs_round_up(max_len + max_new + (int64_t)DECODE_BURST * (k + 1) + 2, 4);
+}
+
+// The loop of cs_decode and cs_decode_batch (Sec. 3.2; App. B.3 step 4): cs_step on all streams
+// of a prefilled cache until every stream has emitted max_new tokens or eos_id.  d_hist holds
+// the prompts ([B][stride], device); lengths, budgets and the outcome of every step stay on
+// the device, and the host reads the log of a whole burst of steps in one copy.
+static int decode_loop(cs_model* m, cs_kv* kv, int32_t* d_hist, int64_t stride,
+                       const int64_t* prompt_len, int64_t max_new, int gamma, int k, int policy,
+                       int eos_id, int32_t* out_tokens, int64_t* emitted, cs_stats* st) {
+    const int B = kv->B;
+    // device state: [hist_len | room] (B each), then per step of a burst
+    // [accepted | next | draft_len] (B each) and the tokens the step appended [B][k+1]
+    const size_t n_slice = (size_t)3 * B + (size_t)B * (k + 1);
+    const size_t n_state = (size_t)2 * B + (size_t)DECODE_BURST * n_slice;
+    int32_t* d_state = nullptr;
+    CS_HIP(hipMalloc(&d_state, n_state * 4));
+    std::vector<int32_t> h(n_state, 0);
+    std::vector<char> active((size_t)B, max_new > 0 ? 1 : 0);
+    for (int b = 0; b < B; ++b) {
+        h[b] = (int32_t)prompt_len[b];
+        h[B + b] = (int32_t)max_new;
+        emitted[b] = 0;
+        st[b] = cs_stats{0, 0, 0, 0};
+    }
+    int rc = CS_OK;
+    if (hipMemcpy(d_state, h.data(), (size_t)2 * B * 4, hipMemcpyHostToDevice) != hipSuccess) {
+        cs_set_error("decode loop: copy to device failed");
+        rc = CS_E_DEVICE;
+    }
+    while (rc == CS_OK) {
+        int64_t most = 0;
+        for (int b = 0; b < B; ++b)
+            if (active[b] && max_new - emitted[b] > most) most = max_new - emitted[b];
+        if (most == 0) break;
+        const int64_t need = cs_ceil_div(most, (int64_t)k + 1);
+        const int burst = (int)(need < DECODE_BURST ? need : DECODE_BURST);
+        for (int j = 0; j < burst && rc == CS_OK; ++j) {
+            int32_t* sl = d_state + 2 * B + (size_t)j * n_slice;
+            rc = cs_step(m, kv, d_hist, stride, d_state, d_state + B, gamma, k, policy, sl, sl + B,
+                         sl + 2 * B, nullptr);
+            if (rc != CS_OK) break;
+            k_emitted<<<B, 64, 0, nullptr>>>(d_hist, stride, d_state, sl, k, sl + 3 * B);
+            rc = cs_launch_ok("k_emitted");
+        }
+        if (rc != CS_OK) break;
+        if (hipMemcpy(h.data(), d_state, ((size_t)2 * B + (size_t)burst * n_slice) * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess) {
+            cs_set_error("decode loop: copy from device failed");
+            rc = CS_E_DEVICE;
+            break;
+        }
+        for (int b = 0; b < B; ++b) kv->h_len_ub[b] = h[b] - 1;   // everything but the pending token
+        for (int j = 0; j < burst; ++j) {
+            const int32_t* sl = h.data() + 2 * B + (size_t)j * n_slice;
+            for (int b = 0; b < B; ++b) {
+                if (!active[b]) continue;
+                const int tau = sl[b], got = tau + 1, dl = sl[2 * B + b];
+                const int32_t* fresh = sl + 3 * B + (size_t)b * (k + 1);
+                st[b].steps += 1;
+                if (dl > 0) { st[b].attempts += 1; st[b].drafted += dl; st[b].accepted += tau; }
+                int take = got;
+                bool stopped = false;
+                for (int i = 0; i < got; ++i)
+                    if (eos_id >= 0 && fresh[i] == eos_id) { take = i + 1; stopped = true; break; }
+                for (int i = 0; i < take; ++i) out_tokens[(int64_t)b * max_new + emitted[b] + i] = fresh[i];
+                emitted[b] += take;
+                if (stopped || emitted[b] >= max_new) active[b] = 0;
+                if (stopped) {
+                    // the steps after the stop token are not part of the output: the stream's budget
+                    // goes to 0 and its cache back to the tokens before the stop token
+                    const int32_t zero = 0;
+                    const int64_t keep = prompt_len[b] + emitted[b] - 1;
+                    if (hipMemcpy(d_state + B + b, &zero, 4, hipMemcpyHostToDevice) != hipSuccess) {
+                        cs_set_error("decode loop: copy to device failed");
+                        rc = CS_E_DEVICE;
+                    } else {
+                        rc = cs_kv_set_len(kv, b, keep);
+                    }
+                    if (rc != CS_OK) break;
+                }
+            }
+            if (rc != CS_OK) break;
+        }
+    }
+    (void)hipFree(d_state);
+    return rc;
+}
+
 static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t prompt_len,
                        int64_t max_new, int gamma, int k, int policy, int eos_id, int32_t* out_tokens,
                        int64_t* n_out, cs_stats* stats) {
@@ -731,52 +829,23 @@ static int decode_impl(cs_model* m, cs_kv* kv, const int32_t* prompt, int64_t pr
     CS_REQUIRE(prompt && prompt_len >= 1, CS_E_ARG, "prompt must hold at least one token");
     CS_REQUIRE(prompt_len + max_new + k + 1 <= kv->limit, CS_E_CAPACITY,
                "cache capacity %lld < prompt_len + max_new + k + 1", (long long)kv->limit);
-    cs_stats st = {0, 0, 0, 0};
     *n_out = 0;
     CS_TRY(range_clear(m));
     CS_TRY(cs_prefill(m, kv, 0, prompt, prompt_len));
-    const int64_t stride = cs_round_up(prompt_len + max_new + k + 2, 4);
+    const int64_t stride = decode_stride(prompt_len, max_new, k);
+    CS_REQUIRE(stride <= CS_MAX_STRIDE, CS_E_ARG, "history too long");
     int32_t* d = nullptr;
-    CS_HIP(hipMalloc(&d, (size_t)(stride + 8) * 4));
-    int32_t* d_len = d + stride;          // [0] hist_len, [1] room, [2] accepted, [3] next, [4] draft_len
-    int32_t init[5] = {(int32_t)prompt_len, (int32_t)max_new, 0, 0, 0};
+    CS_HIP(hipMalloc(&d, (size_t)stride * 4));
     int rc = CS_OK;
-    if (hipMemcpy(d, prompt, (size_t)prompt_len * 4, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(d_len, init, sizeof(init), hipMemcpyHostToDevice) != hipSuccess) {
+    if (hipMemcpy(d, prompt, (size_t)prompt_len * 4, hipMemcpyHostToDevice) != hipSuccess) {
         cs_set_error("cs_decode: copy to device failed");
         rc = CS_E_DEVICE;
     }
     int64_t emitted = 0;
-    bool stop = false;
-    while (rc == CS_OK && emitted < max_new && !stop) {
-        rc = cs_step(m, kv, d, stride, d_len, d_len + 1, gamma, k, policy, d_len + 2, d_len + 3,
-                     d_len + 4, nullptr);
-        if (rc != CS_OK) break;
-        int32_t h[5];
-        if (hipMemcpy(h, d_len, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) {
-            cs_set_error("cs_decode: copy from device failed");
-            rc = CS_E_DEVICE;
-            break;
-        }
-        const int tau = h[2], got = tau + 1;
-        kv->h_len_ub[0] = h[0] - 1;       // true length: everything but the pending token
-        if (hipMemcpy(out_tokens + emitted, d + (h[0] - got), (size_t)got * 4,
-                      hipMemcpyDeviceToHost) != hipSuccess) {
-            cs_set_error("cs_decode: copy from device failed");
-            rc = CS_E_DEVICE;
-            break;
-        }
-        st.steps += 1;
-        if (h[4] > 0) { st.attempts += 1; st.drafted += h[4]; st.accepted += tau; }
-        for (int i = 0; i < got; ++i) {
-            if (eos_id >= 0 && out_tokens[emitted + i] == eos_id) {
-                emitted += i + 1;
-                stop = true;
-                break;
-            }
-        }
-        if (!stop) emitted += got;
-    }
+    cs_stats st = {0, 0, 0, 0};
+    if (rc == CS_OK)
+        rc = decode_loop(m, kv, d, stride, &prompt_len, max_new, gamma, k, policy, eos_id, out_tokens,
+                         &emitted, &st);
     (void)hipFree(d);
     if (rc != CS_OK) return rc;
     *n_out = emitted;
@@ -884,70 +953,22 @@ extern "C" int cs_decode_batch(cs_model* m, cs_kv* kv, const int32_t* prompts, i
                "cache capacity %lld < longest prompt + max_new + k + 1", (long long)kv->limit);
     std::vector<cs_stats> st((size_t)B, cs_stats{0, 0, 0, 0});
     std::vector<int64_t> emitted((size_t)B, 0);
-    std::vector<char> active((size_t)B, max_new > 0 ? 1 : 0);
     for (int b = 0; b < B; ++b) n_out[b] = 0;
     CS_TRY(range_clear(m));
     CS_TRY(cs_prefill_batch(m, kv, prompts, prompt_stride, prompt_len));
-    const int64_t stride = cs_round_up(max_len + max_new + k + 2, 4);
-    CS_REQUIRE(stride < (int64_t)1 << 31, CS_E_ARG, "history too long");
-    // device state: histories, then [hist_len | room | accepted | next | draft_len] (B each),
-    // then the tokens of the last step [B][k+1]
-    const size_t n_state = (size_t)5 * B + (size_t)B * (k + 1);
+    const int64_t stride = decode_stride(max_len, max_new, k);
+    CS_REQUIRE(stride <= CS_MAX_STRIDE, CS_E_ARG, "history too long");
     int32_t* d = nullptr;
-    CS_HIP(hipMalloc(&d, ((size_t)B * stride + n_state) * 4));
-    int32_t* d_state = d + (size_t)B * stride;
-    int32_t* d_new = d_state + 5 * B;
-    std::vector<int32_t> h((size_t)n_state, 0);
-    for (int b = 0; b < B; ++b) {
-        h[b] = (int32_t)prompt_len[b];
-        h[B + b] = (int32_t)max_new;
-    }
+    CS_HIP(hipMalloc(&d, (size_t)B * stride * 4));
     int rc = CS_OK;
     if (hipMemcpy2D(d, (size_t)stride * 4, prompts, (size_t)prompt_stride * 4, (size_t)max_len * 4, B,
-                    hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(d_state, h.data(), n_state * 4, hipMemcpyHostToDevice) != hipSuccess) {
+                    hipMemcpyHostToDevice) != hipSuccess) {
         cs_set_error("cs_decode_batch: copy to device failed");
         rc = CS_E_DEVICE;
     }
-    auto any_active = [&]() {
-        for (int b = 0; b < B; ++b)
-            if (active[b]) return true;
-        return false;
-    };
-    while (rc == CS_OK && any_active()) {
-        rc = cs_step(m, kv, d, stride, d_state, d_state + B, gamma, k, policy, d_state + 2 * B,
-                     d_state + 3 * B, d_state + 4 * B, nullptr);
-        if (rc != CS_OK) break;
-        k_emitted<<<B, 64, 0, nullptr>>>(d, stride, d_state, d_state + 2 * B, k, d_new);
-        rc = cs_launch_ok("k_emitted");
-        if (rc != CS_OK) break;
-        if (hipMemcpy(h.data(), d_state, n_state * 4, hipMemcpyDeviceToHost) != hipSuccess) {
-            cs_set_error("cs_decode_batch: copy from device failed");
-            rc = CS_E_DEVICE;
-            break;
-        }
-        for (int b = 0; b < B && rc == CS_OK; ++b) {
-            kv->h_len_ub[b] = h[b] - 1;           // true length: everything but the pending token
-            if (!active[b]) continue;
-            const int tau = h[2 * B + b], got = tau + 1, dl = h[4 * B + b];
-            const int32_t* fresh = h.data() + 5 * B + (size_t)b * (k + 1);
-            st[b].steps += 1;
-            if (dl > 0) { st[b].attempts += 1; st[b].drafted += dl; st[b].accepted += tau; }
-            int take = got;
-            for (int i = 0; i < got; ++i)
-                if (eos_id >= 0 && fresh[i] == eos_id) { take = i + 1; active[b] = 0; break; }
-            for (int i = 0; i < take; ++i) out_tokens[(int64_t)b * max_new + emitted[b] + i] = fresh[i];
-            emitted[b] += take;
-            if (emitted[b] >= max_new) active[b] = 0;
-            if (!active[b] && h[B + b] > 0) {     // stopped by eos: take its remaining budget away
-                const int32_t zero = 0;
-                if (hipMemcpy(d_state + B + b, &zero, 4, hipMemcpyHostToDevice) != hipSuccess) {
-                    cs_set_error("cs_decode_batch: copy to device failed");
-                    rc = CS_E_DEVICE;
-                }
-            }
-        }
-    }
+    if (rc == CS_OK)
+        rc = decode_loop(m, kv, d, stride, prompt_len, max_new, gamma, k, policy, eos_id, out_tokens,
+                         emitted.data(), st.data());
     (void)hipFree(d);
     if (rc != CS_OK) return rc;
     for (int b = 0; b < B; ++b) {

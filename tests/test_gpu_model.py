@@ -513,6 +513,27 @@ def _ragged_prompts(vocab, lens, seed):
             for b, n in enumerate(lens)]
 
 
+def _replay_stats(prompt, toks, gamma, k, budget, stop_after):
+    """Counters of the copy-and-verify loop that emits the greedy tokens `toks`: the oracle's
+    match search drafts (clamped to the budget as in App. B.3 step 4), a draft token is accepted
+    iff it is the next token, and the loop ends with the step that emits token `stop_after`."""
+    seq, done = list(prompt), 0
+    st = {"steps": 0, "attempts": 0, "drafted": 0, "accepted": 0}
+    while done < stop_after:
+        draft = list(orc.find_match(seq, gamma, k, "rightmost")[2])[:budget - done - 1]
+        tau = 0
+        while tau < len(draft) and draft[tau] == toks[done + tau]:
+            tau += 1
+        st["steps"] += 1
+        if draft:
+            st["attempts"] += 1
+            st["drafted"] += len(draft)
+            st["accepted"] += tau
+        seq += toks[done:done + tau + 1]
+        done += tau + 1
+    return st
+
+
 def test_decode_batch_equals_single_stream_decodes_and_oracle():
     """Three prompts of different lengths through one cache: every stream's output is what the
     single-stream loop gives for it, follows the oracle, and stops on its own at eos."""
@@ -533,10 +554,15 @@ def test_decode_batch_equals_single_stream_decodes_and_oracle():
     assert stats[0]["attempts"] >= 1
     # eos: a token that stream 1 emits in the middle; every stream is cut after its first one
     eos = toks[1][new // 2]
-    cut, _ = cs.cs_decode_batch(model, kvb, prompts, new, 3, k, eos_id=eos)
+    cut, cut_stats = cs.cs_decode_batch(model, kvb, prompts, new, 3, k, eos_id=eos)
     for b in range(B):
         want = toks[b][:toks[b].index(eos) + 1] if eos in toks[b] else toks[b]
         assert cut[b] == want, f"stream {b}"
+        # the steps the host did not wait for (the loop reads a burst of steps at a time) leave
+        # no trace: the cache ends before the stop token and the counters stop at its step
+        assert kvb.len(b) == len(prompts[b]) + len(cut[b]) - 1, f"stream {b}"
+        assert cut_stats[b] == _replay_stats(prompts[b], toks[b], 3, k, new, len(want)), f"stream {b}"
+        assert stats[b] == _replay_stats(prompts[b], toks[b], 3, k, new, new), f"stream {b}"
     assert len(cut[1]) <= new // 2 + 1
     # no budget: nothing is emitted, the caches hold the prompts
     none, _ = cs.cs_decode_batch(model, kvb, prompts, 0, 3, k)
