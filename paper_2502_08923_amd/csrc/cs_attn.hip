@@ -1272,8 +1272,14 @@ __global__ __launch_bounds__(FA_MERGE_THREADS) void k_attn_merge(const float* __
     const int col = (kvh * G + gq) * HD + d;
     const int64_t off = tiled ? cs_xt_index(r, col, H * HD) : (int64_t)r * H * HD + col;
     bool hit = false;
+    if constexpr (std::is_same<OT, f16_t>::value) {       // one 8-byte store
+        const f16x4 o = (f16x4){cs_f16_sat(num[0] * inv, hit), cs_f16_sat(num[1] * inv, hit),
+                                cs_f16_sat(num[2] * inv, hit), cs_f16_sat(num[3] * inv, hit)};
+        *reinterpret_cast<f16x4*>(out + off) = o;
+    } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fa_store_out(out, off + j, num[j] * inv, hit);
+        for (int j = 0; j < 4; ++j) fa_store_out(out, off + j, num[j] * inv, hit);
+    }
     cs_range_report(flags, hit, CS_RANGE_ATTN);
 }
 

@@ -214,7 +214,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int n = n_wave + mt * 16 + 4 * g;
-                if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
+                if (n < N) cs_store_stream(reinterpret_cast<f32x4*>(y + (int64_t)r * N + n), acc[mt][nt]);
             }
         }
     } else if (MODE == CS_GEMM_ARGMAX) {
