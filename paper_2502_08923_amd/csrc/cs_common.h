@@ -231,11 +231,12 @@ __device__ __forceinline__ void cs_load_to_lds(unsigned voff, const void* sbase,
 
 __device__ __forceinline__ float cs_ld(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float cs_ld(const bf16_t* p, int64_t i) { return (float)p[i]; }
-// Streaming store for the split-K partial tiles of the weight-streaming GEMM.  Their reader runs
-// on any XCD, so the lines are of no use in the writer's L2; sent on at once they leave the
-// end-of-kernel write-back nothing to flush (headline step 7.96 -> 7.88 ms).  Measured and not
-// adopted elsewhere: the many-row GEMM's larger partial tiles lose 4 % (they gain from being
-// combined in L2), normed rows, SwiGLU outputs and attention partials do not change.
+// Streaming store for the split-K partial tiles of the weight-streaming GEMM at 64 rows and more.
+// Their reader runs on any XCD, so the lines are of no use in the writer's L2; sent on at once
+// they leave the end-of-kernel write-back nothing to flush (headline step 7.96 -> 7.87 ms).
+// Measured and not adopted elsewhere: with few rows the readers find the tiles in the caches
+// (one stream +3 %), the many-row GEMM's larger tiles gain from being combined in L2 (+4 %),
+// normed rows, SwiGLU outputs and attention partials do not change.
 __device__ __forceinline__ void cs_store_stream(f32x4* p, f32x4 v) { __builtin_nontemporal_store(v, p); }
 __device__ __forceinline__ void cs_st(float* p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void cs_st(bf16_t* p, int64_t i, float v) { p[i] = (bf16_t)v; }

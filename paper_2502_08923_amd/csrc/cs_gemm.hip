@@ -63,6 +63,9 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const XT* __restrict__ X,
 // MT: 16-row W tiles per consumer wave.  NT: 16-row X tiles per workgroup.
 // grid.x: (W row tile of 64*MT, X row block of 16*NT) pairs, see the mapping below;
 // grid.y: K splits.
+// act_tiled by mode: SWIGLU - the output goes out in fragment order; ARGMAX - tiles per row of the
+// pair buffer.
+#define GEMM_STORE_STREAM 3   // CS_GEMM_STORE whose partial tiles leave through streaming stores
 template <int MT, int NT, int MODE>
 __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restrict__ X,
                                                             const f16_t* __restrict__ W,
@@ -205,16 +208,43 @@ __global__ __launch_bounds__(GEMM_THREADS) void k_gemm_mfma(const f16_t* __restr
     }
 
     // epilogue.  acc[mt][nt][j] = Y[row r_base + nt*16 + lrow][col n_wave + mt*16 + 4g + j]
-    if (MODE == CS_GEMM_STORE) {
+    if (MODE == CS_GEMM_STORE || MODE == GEMM_STORE_STREAM) {
         float* __restrict__ y = Y + (int64_t)blockIdx.y * R * N;
+        if constexpr (MT == 2) {
+            // The wave's two 16-column tiles are neighbours: lanes 8 rows apart swap one tile each, so
+            // that a store instruction covers 8 rows x 128 bytes (whole lines) instead of 16 rows x 64.
+            const bool low = lrow < 8;
+            const int n = n_wave + (low ? 0 : 16) + 4 * g;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int r = r_base + nt * 16 + lrow;
-            if (r >= R) continue;
+            for (int nt = 0; nt < NT; ++nt) {
+                f32x4 t0, t1;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int n = n_wave + mt * 16 + 4 * g;
-                if (n < N) cs_store_stream(reinterpret_cast<f32x4*>(y + (int64_t)r * N + n), acc[mt][nt]);
+                for (int j = 0; j < 4; ++j) {
+                    t0[j] = __shfl_xor(acc[0][nt][j], 8, 64);
+                    t1[j] = __shfl_xor(acc[1][nt][j], 8, 64);
+                }
+                const int ra = r_base + nt * 16 + (lrow & 7), rb = ra + 8;
+                f32x4* pa = reinterpret_cast<f32x4*>(y + (int64_t)ra * N + n);
+                f32x4* pb = reinterpret_cast<f32x4*>(y + (int64_t)rb * N + n);
+                const f32x4 va = low ? acc[0][nt] : t1, vb = low ? t0 : acc[1][nt];
+                if constexpr (MODE == GEMM_STORE_STREAM) {  // see the launcher
+                    if (ra < R && n < N) cs_store_stream(pa, va);
+                    if (rb < R && n < N) cs_store_stream(pb, vb);
+                } else {
+                    if (ra < R && n < N) *pa = va;
+                    if (rb < R && n < N) *pb = vb;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int r = r_base + nt * 16 + lrow;
+                if (r >= R) continue;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int n = n_wave + mt * 16 + 4 * g;
+                    if (n < N) *reinterpret_cast<f32x4*>(y + (int64_t)r * N + n) = acc[mt][nt];
+                }
             }
         }
     } else if (MODE == CS_GEMM_ARGMAX) {
@@ -572,7 +602,13 @@ static int launch_mfma(const f16_t* X, const f16_t* W, float* Y, f16_t* act, int
     dim3 grid((unsigned)(cs_round_up(cs_ceil_div(N, 64 * MT), 8) * RB), (unsigned)cs_ceil_div(K, Ks));
     const int pg = cs_prof_begin(CS_PROF_GEMM, s);
     if (mode == CS_GEMM_STORE) {
-        k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+        // From about 64 rows on the partial tiles are better sent on at once (88 rows: step -1 %,
+        // 168: -0.9 %, 264: -0.3 %); with few rows the readers find them in the caches and a plain
+        // store wins (48 rows +0.4 %, one stream of 11 rows +2.5 to +3.6 %).
+        if (R >= 64)
+            k_gemm_mfma<MT, NT, GEMM_STORE_STREAM><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
+        else
+            k_gemm_mfma<MT, NT, CS_GEMM_STORE><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     } else if (mode == CS_GEMM_ARGMAX) {
         k_gemm_mfma<MT, NT, CS_GEMM_ARGMAX><<<grid, GEMM_THREADS, 0, s>>>(X, W, Y, act, R, N, K, Ks, RB, act_tiled);
     } else {
