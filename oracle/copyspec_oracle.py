@@ -298,9 +298,10 @@ def forward_block(w: dict, kv: KVCache, tokens, store_dtype: str | None = None,
     x = _f64(w["embed"][tokens])                                  # [R][d]
     for l, lw in enumerate(w["layers"]):
         a = clip(rmsnorm(x, _f64(lw["norm1"]), sh.rms_eps))
-        q = (a @ _f64(lw["wq"]).T).reshape(R, H, hd)
-        kk = (a @ _f64(lw["wk"]).T).reshape(R, KVH, hd)
-        vv = (a @ _f64(lw["wv"]).T).reshape(R, KVH, hd)
+        q, kk, vv = a @ _f64(lw["wq"]).T, a @ _f64(lw["wk"]).T, a @ _f64(lw["wv"]).T
+        if "bq" in lw:      # model families whose q, k, v projections carry a bias (Sec. 4.1: Qwen2.5)
+            q, kk, vv = q + _f64(lw["bq"]), kk + _f64(lw["bk"]), vv + _f64(lw["bv"])
+        q, kk, vv = q.reshape(R, H, hd), kk.reshape(R, KVH, hd), vv.reshape(R, KVH, hd)
         q = rotary(q, pos, sh.rope_theta)
         kk = rotary(kk, pos, sh.rope_theta)
         if store == "bf16":

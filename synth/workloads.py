@@ -14,7 +14,7 @@ any search.
 from __future__ import annotations
 
 from concurrent.futures import ThreadPoolExecutor
-from dataclasses import dataclass
+from dataclasses import dataclass, replace
 import math
 
 import numpy as np
@@ -62,16 +62,16 @@ class ModelShape:
     rope_theta: float
     rms_eps: float
     dtype: str  # "f32" or "bf16": storage type of weights and KV cache
+    qkv_bias: bool = False  # additive biases on the q, k and v projections (the Qwen2.5 family)
 
     def with_layers(self, n_layers: int) -> "ModelShape":
-        return ModelShape(self.name, n_layers, self.d_model, self.n_heads, self.n_kv_heads,
-                          self.head_dim, self.d_ff, self.vocab, self.rope_theta, self.rms_eps,
-                          self.dtype)
+        return replace(self, n_layers=n_layers)
 
     def with_vocab(self, vocab: int) -> "ModelShape":
-        return ModelShape(self.name, self.n_layers, self.d_model, self.n_heads, self.n_kv_heads,
-                          self.head_dim, self.d_ff, vocab, self.rope_theta, self.rms_eps,
-                          self.dtype)
+        return replace(self, vocab=vocab)
+
+    def with_qkv_bias(self, on: bool = True) -> "ModelShape":
+        return replace(self, qkv_bias=on)
 
 
 TINY = ModelShape("tiny", 2, 256, 4, 4, 64, 1024, 1024, 10000.0, 1e-5, "f32")
@@ -121,7 +121,8 @@ def model_weights(shape: ModelShape, seed: int, threads: int = 8) -> dict:
     outputs for unit-variance inputs); embedding rows are N(0, 1); RMSNorm
     gains are 1 + 0.1 U(-1, 1) so that a dropped or mis-indexed gain shows.
     bf16 shapes return uint16 bit patterns for matrices; norm gains are always
-    float32.  Linear weights are stored [out_features][in_features].
+    float32.  Linear weights are stored [out_features][in_features].  Shapes with qkv_bias also
+    get float32 bias vectors bq, bk, bv per layer.
     """
     d, hd = shape.d_model, shape.head_dim
     H, KVH, F, V = shape.n_heads, shape.n_kv_heads, shape.d_ff, shape.vocab
@@ -142,6 +143,10 @@ def model_weights(shape: ModelShape, seed: int, threads: int = 8) -> dict:
         jobs[("layers", l, "wd")] = (s + 6, (d, F), "u", math.sqrt(3.0 / F), dt)
         jobs[("layers", l, "norm1")] = (s + 7, (d,), "g", 0.1, "f32")
         jobs[("layers", l, "norm2")] = (s + 8, (d,), "g", 0.1, "f32")
+        if shape.qkv_bias:      # float32, N(0, 0.5): of the size of the projected values themselves
+            jobs[("layers", l, "bq")] = (s + 9, (H * hd,), "n", 0.5, "f32")
+            jobs[("layers", l, "bk")] = (s + 10, (KVH * hd,), "n", 0.5, "f32")
+            jobs[("layers", l, "bv")] = (s + 11, (KVH * hd,), "n", 0.5, "f32")
 
     def run(job):
         sd, shp, kind, scale, dtype = job

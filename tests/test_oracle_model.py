@@ -74,6 +74,57 @@ def test_forward_matches_library_llama(small_w):
     assert np.abs(tail - got[20:]).max() < 1e-11
 
 
+def test_qkv_bias_matches_library_qwen2():
+    """The q/k/v biases of the Qwen2.5 family (Sec. 4.1 runs both families): same weights and
+    biases in the `transformers` Qwen2 implementation; a dropped, doubled or head-misplaced bias,
+    or one added after the rotary embedding, changes the logits by O(1)."""
+    from transformers import Qwen2Config, Qwen2ForCausalLM
+    sh = SMALL.with_qkv_bias()
+    w = synth.model_weights(sh, 4321, threads=1)
+    cfg = Qwen2Config(vocab_size=sh.vocab, hidden_size=sh.d_model, intermediate_size=sh.d_ff,
+                      num_hidden_layers=sh.n_layers, num_attention_heads=sh.n_heads,
+                      num_key_value_heads=sh.n_kv_heads, rms_norm_eps=sh.rms_eps,
+                      rope_theta=sh.rope_theta, tie_word_embeddings=False,
+                      max_position_embeddings=4096, hidden_act="silu", use_sliding_window=False)
+    m = Qwen2ForCausalLM(cfg).double().eval()
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    sd = {"model.embed_tokens.weight": t(w["embed"]), "model.norm.weight": t(w["final_norm"]),
+          "lm_head.weight": t(w["lm_head"])}
+    names = {"wq": "self_attn.q_proj.weight", "wk": "self_attn.k_proj.weight", "wv": "self_attn.v_proj.weight",
+             "bq": "self_attn.q_proj.bias", "bk": "self_attn.k_proj.bias", "bv": "self_attn.v_proj.bias",
+             "wo": "self_attn.o_proj.weight", "wg": "mlp.gate_proj.weight", "wu": "mlp.up_proj.weight",
+             "wd": "mlp.down_proj.weight", "norm1": "input_layernorm.weight",
+             "norm2": "post_attention_layernorm.weight"}
+    for l, lw in enumerate(w["layers"]):
+        assert set(lw) == set(names)
+        for k, n in names.items():
+            sd[f"model.layers.{l}.{n}"] = t(lw[k])
+    missing, unexpected = m.load_state_dict(sd, strict=False)
+    assert not [k for k in missing if "rotary" not in k], missing
+    assert not unexpected
+    rng = np.random.default_rng(5)
+    toks = rng.integers(0, sh.vocab, 33)
+    with torch.no_grad():
+        ref = m(torch.from_numpy(toks)[None]).logits[0].numpy()
+    kv = orc.KVCache(sh, 64)
+    got = orc.forward_block(w, kv, toks, store_dtype="f64")
+    assert np.abs(got - ref).max() < 5e-6
+    # the biases matter at this scale: without them the logits are far off
+    w0 = dict(w, layers=[{k: v for k, v in lw.items() if k not in ("bq", "bk", "bv")} for lw in w["layers"]])
+    plain = orc.forward_block(w0, orc.KVCache(sh, 64), toks, store_dtype="f64")
+    assert np.abs(plain - ref).max() > 0.1
+    # block over a non-empty cache and greedy == CopySpec with biases
+    kv2 = orc.KVCache(sh, 64)
+    orc.forward_block(w, kv2, toks[:20], store_dtype="f64")
+    kv2.truncate(20)
+    tail = orc.forward_block(w, kv2, toks[20:], store_dtype="f64")
+    assert np.abs(tail - got[20:]).max() < 1e-11
+    prompt = (list(toks[:12]) * 3)[:30]
+    g = orc.greedy_decode(w, prompt, 12)
+    c, _ = orc.copyspec_decode(w, prompt, 12, 3, 5)
+    assert g == c
+
+
 def test_act_clip_matches_library_llama_with_clamped_linear_inputs():
     """The optional input range of the projections (act_clip): the same weights in the library
     implementation, with a hook on every linear layer that clamps its input, give the same
