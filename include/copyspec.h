@@ -168,6 +168,9 @@ typedef struct cs_layer_weights {
     const void *wg, *wu;        /* [d_ff][d] gate and up projections */
     const void *wd;             /* [d][d_ff] */
     const float *norm1, *norm2; /* attention and FFN RMSNorm gains */
+    const float *bq, *bk, *bv;  /* float32 biases of the q, k, v projections ([n_heads*hd],
+                                   [n_kv_heads*hd] x 2; the Qwen2.5 family of Sec. 4.1), added
+                                   before the rotary embedding; all three NULL: none */
 } cs_layer_weights;
 
 typedef struct cs_weights {

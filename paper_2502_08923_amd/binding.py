@@ -50,7 +50,8 @@ class cs_model_cfg(C.Structure):
 
 
 class cs_layer_weights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "norm1", "norm2")]
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "norm1", "norm2",
+                                          "bq", "bk", "bv")]
 
 
 class cs_weights(C.Structure):
@@ -306,6 +307,9 @@ class Model:
                 setattr(layers[l], name, up(lw[name], bf16))
             layers[l].norm1 = up(lw["norm1"], False)
             layers[l].norm2 = up(lw["norm2"], False)
+            for name in ("bq", "bk", "bv"):           # optional float32 projection biases
+                if name in lw:
+                    setattr(layers[l], name, up(lw[name], False))
         w = cs_weights(up(weights["embed"], bf16), up(weights["lm_head"], bf16),
                        up(weights["final_norm"], False), layers)
         h = C.c_void_p()

@@ -169,7 +169,7 @@ static void model_free(cs_model* m) {
     if (m->layers) {
         for (int l = 0; l < m->cfg.n_layers; ++l) {
             cs_layer_dev& L = m->layers[l];
-            void* lp[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2};
+            void* lp[] = {L.wqkv, L.wo, L.wgu, L.wd, L.norm1, L.norm2, L.bqkv};
             for (void* p : lp)
                 if (p) (void)hipFree(p);
         }
@@ -207,6 +207,13 @@ static int model_build(cs_model* m, const cs_weights* w) {
         char* qkv = (char*)L.wqkv;
         CS_HIP(hipMemcpy(L.norm1, s.norm1, (size_t)d * 4, hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
+        if (s.bq || s.bk || s.bv) {
+            CS_REQUIRE(s.bq && s.bk && s.bv, CS_E_ARG, "layer %d: the q, k, v biases come all three or not at all", l);
+            DEV_ALLOC(L.bqkv, (size_t)nqkv * 4);
+            CS_HIP(hipMemcpy(L.bqkv, s.bq, (size_t)nq * 4, hipMemcpyDeviceToDevice));
+            CS_HIP(hipMemcpy(L.bqkv + nq, s.bk, (size_t)nkv * 4, hipMemcpyDeviceToDevice));
+            CS_HIP(hipMemcpy(L.bqkv + nq + nkv, s.bv, (size_t)nkv * 4, hipMemcpyDeviceToDevice));
+        }
         if (m->fast) {
             // the q, k and v blocks become row ranges of one tiled matrix
             CS_TRY(cs_tile_weights_launch(s.wq, nullptr, nq, d, 0, nqkv, 0, qkv, m->range_flags, nullptr));

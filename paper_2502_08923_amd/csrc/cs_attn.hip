@@ -153,6 +153,7 @@ struct fa_fused_rope {
     const float2* rope;      // [R][HD/2] (cos, sin)
     bf16_t* kc_w;            // this layer's caches, writable
     bf16_t* vc_w;
+    const float* bias;       // [(H + 2*KVH) * HD] biases of the q, k, v projections, or NULL
 };
 
 template <int HD>
@@ -233,6 +234,14 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                     a[4 + u] += a1[u];
                     cc[u] += c0[u];
                     cc[4 + u] += c1[u];
+                }
+            }
+            if (fr.bias) {                            // projection bias, before the rotation
+                const float* __restrict__ bp = fr.bias + head * HD + j0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    a[u] += bp[u];
+                    cc[u] += bp[HALF + u];
                 }
             }
 #pragma unroll
@@ -1388,7 +1397,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
     float* pml = m->attn_part + items * FA_QROWS * hd;
     dim3 grid(nsplit * nqg, KVH, B);
     const int pa = cs_prof_begin(CS_PROF_ATTN, s);
-    fa_fused_rope fr = {nullptr, 0, 0, nullptr, nullptr, nullptr};
+    fa_fused_rope fr = {nullptr, 0, 0, nullptr, nullptr, nullptr, nullptr};
     if (qkv_part) {
         fr.qkv = qkv_part;
         fr.nparts = qkv_nparts;
@@ -1396,6 +1405,7 @@ int cs_attention_launch(const cs_model* m, cs_kv* kv, int layer, int rows, int64
         fr.rope = m->rope;
         fr.kc_w = (bf16_t*)kv->k + layer * per_layer;
         fr.vc_w = (bf16_t*)kv->v + layer * per_layer;
+        fr.bias = m->layers[layer].bqkv;
     }
     if (hd == 128)
         k_attn_mfma<128><<<grid, 256, 0, s>>>((const bf16_t*)m->q, kc, vc, kv->d_len, rows, H, KVH,

@@ -71,6 +71,7 @@ struct cs_layer_dev {
     void* wd;      // [d][F]
     float* norm1;
     float* norm2;
+    float* bqkv;   // [(H+2KVH)*hd] biases of the q, k, v rows, or NULL
 };
 
 struct cs_model {

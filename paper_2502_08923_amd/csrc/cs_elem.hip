@@ -128,7 +128,8 @@ __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qk
                                                     const int32_t* __restrict__ kv_len, int rows,
                                                     int H, int KVH, int hd, int64_t cap,
                                                     WT* __restrict__ kc, WT* __restrict__ vc,
-                                                    QT* __restrict__ q) {
+                                                    QT* __restrict__ q,
+                                                    const float* __restrict__ bias) {
     const int r = blockIdx.y, head = blockIdx.x;     // head: q heads, then k heads, then v heads
     const int b = r / rows, i = r % rows;
     const int half = hd / 2;
@@ -141,6 +142,10 @@ __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qk
         for (int p = 0; p < nparts; ++p) {
             a += qkv[p * part_stride + i0];
             c += qkv[p * part_stride + i0 + half];
+        }
+        if (bias) {                                   // projection bias, before the rotation
+            a += bias[head * hd + j];
+            c += bias[head * hd + j + half];
         }
         if (head < H + KVH) {
             const float2 cs = rope[(int64_t)r * half + j];
@@ -175,7 +180,8 @@ __global__ __launch_bounds__(64) void k_rope_append(const float* __restrict__ qk
 __global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
     const float* __restrict__ qkv, int nparts, int64_t part_stride, const float2* __restrict__ rope,
     const int32_t* __restrict__ kv_len, int rows, int R, int H, int KVH, int hd, int64_t cap,
-    bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, bf16_t* __restrict__ q) {
+    bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, bf16_t* __restrict__ q,
+    const float* __restrict__ bias) {
     __shared__ bf16_t vt[256][RA_ROWS + 2];            // [d][row of the workgroup], hd <= 256
     __shared__ int64_t voff[RA_ROWS];                  // cache offset of each row's token (v heads)
     const int head = blockIdx.x;                       // q heads, then k heads, then v heads
@@ -195,6 +201,10 @@ __global__ __launch_bounds__(RA_THREADS) void k_rope_append_rows(
             for (int p = 0; p < nparts; ++p) {         // in order: the same sums as the other kernels
                 a += *reinterpret_cast<const f32x4*>(qkv + p * part_stride + i0);
                 c += *reinterpret_cast<const f32x4*>(qkv + p * part_stride + i0 + half);
+            }
+            if (bias) {                               // projection bias, before the rotation
+                a += *reinterpret_cast<const f32x4*>(bias + head * hd + j);
+                c += *reinterpret_cast<const f32x4*>(bias + head * hd + j + half);
             }
             if (!is_v) {
                 const f32x4 cs0 = *reinterpret_cast<const f32x4*>(rope + (int64_t)r * half + j);
@@ -450,6 +460,7 @@ int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* 
     const int64_t per_layer = (int64_t)kv->B * c.n_kv_heads * kv->cap * c.head_dim;
     const int64_t ps = (int64_t)R * (c.n_heads + 2 * c.n_kv_heads) * c.head_dim;
     const float2* rope = m->rope;
+    const float* bias = m->layers[layer].bqkv;
     dim3 rgrid(c.n_heads + 2 * c.n_kv_heads, R);
     if (c.dtype == CS_BF16) {
         bf16_t* kc = (bf16_t*)kv->k + layer * per_layer;
@@ -459,21 +470,21 @@ int cs_rope_append_launch(const cs_model* m, cs_kv* kv, int layer, const float* 
             dim3 grid(c.n_heads + 2 * c.n_kv_heads, (unsigned)cs_ceil_div(R, RA_ROWS));
             k_rope_append_rows<<<grid, RA_THREADS, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows, R, c.n_heads,
                                                           c.n_kv_heads, c.head_dim, kv->cap, kc, vc,
-                                                          (bf16_t*)m->q);
+                                                          (bf16_t*)m->q, bias);
         } else if (m->fast)
             k_rope_append<bf16_t, bf16_t><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                            c.n_heads, c.n_kv_heads, c.head_dim,
-                                                           kv->cap, kc, vc, (bf16_t*)m->q);
+                                                           kv->cap, kc, vc, (bf16_t*)m->q, bias);
         else
             k_rope_append<bf16_t, float><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                           c.n_heads, c.n_kv_heads, c.head_dim,
-                                                          kv->cap, kc, vc, (float*)m->q);
+                                                          kv->cap, kc, vc, (float*)m->q, bias);
     } else {
         float* kc = (float*)kv->k + layer * per_layer;
         float* vc = (float*)kv->v + layer * per_layer;
         k_rope_append<float, float><<<rgrid, 64, 0, s>>>(qkv, nparts, ps, rope, kv->d_len, rows,
                                                      c.n_heads, c.n_kv_heads, c.head_dim, kv->cap,
-                                                     kc, vc, (float*)m->q);
+                                                     kc, vc, (float*)m->q, bias);
     }
     return cs_launch_ok("k_rope_append");
 }

@@ -45,7 +45,7 @@ def test_binding_lists_every_declared_symbol():
 def test_struct_layouts_match_header():
     from paper_2502_08923_amd import binding
     assert ctypes.sizeof(binding.cs_model_cfg) == 12 * 4
-    assert ctypes.sizeof(binding.cs_layer_weights) == 9 * 8
+    assert ctypes.sizeof(binding.cs_layer_weights) == 12 * 8
     assert ctypes.sizeof(binding.cs_weights) == 4 * 8
     assert ctypes.sizeof(binding.cs_stats) == 4 * 8
     assert ctypes.sizeof(binding.cs_merged_stats) == 8 * 8

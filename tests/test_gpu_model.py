@@ -147,6 +147,60 @@ def test_verify_matches_oracle(shape, plain):
     model.destroy()
 
 
+@pytest.mark.parametrize("shape,plain", [(MINI64, False), (MINI64, True), (MINI128, False),
+                                         (SMALLF32, False)])
+def test_verify_and_decode_with_qkv_bias(shape, plain):
+    """Biases on the q, k, v projections (the Qwen2.5 family of Sec. 4.1): prompt blocks (the
+    many-row rotary kernel), the verify block (the attention kernel's own rotary stage for
+    narrow blocks, the small rotary kernel for the plain path) and the decode loop, against the
+    oracle with the same biases.  The biases are of the size of the projected values, so a bias
+    that is dropped, doubled, added after the rotation or given to the wrong head fails."""
+    shape = shape.with_qkv_bias()
+    w = synth.model_weights(shape, 777, threads=4)
+    model = cs.Model(w, max_batch=1, max_k=10, plain=plain)
+    rng = np.random.default_rng(22)
+    prompt = rng.integers(0, shape.vocab, 300).tolist()
+    truth = orc.greedy_decode(w, prompt, 12)
+    for j, m in [(0, 10), (5, 10), (10, 10), (0, 0)]:
+        draft = truth[:m]
+        if j < m:
+            draft = draft[:j] + [(draft[j] + 1) % shape.vocab] + draft[j + 1:]
+        kv, okv, err = _verify_case(w, model, prompt, draft, 10, cap=400)
+        for layer in range(shape.n_layers):
+            k_rows, v_rows = kv.read(layer, 0, 0, okv.length)
+            _cache_rows_close(k_rows, okv.k[layer, :, :okv.length], tol_for(shape))
+            _cache_rows_close(v_rows, okv.v[layer, :, :okv.length], tol_for(shape))
+        kv.destroy()
+    # the same model without its biases is a different model: the check above has teeth
+    w0 = dict(w, layers=[{k: v for k, v in lw.items() if k not in ("bq", "bk", "bv")} for lw in w["layers"]])
+    okv = orc.KVCache(shape, 400)
+    pending = orc.prefill(w, okv, prompt, chunk=32)
+    okv0 = orc.KVCache(shape, 400)
+    pending0 = orc.prefill(w0, okv0, prompt, chunk=32)
+    assert np.abs(orc.verify(w, okv, pending, truth[:3])[2] - orc.verify(w0, okv0, pending0, truth[:3])[2]).max() > 0.1
+    # decode loop: CopySpec == greedy, and both follow the oracle
+    rep = (prompt[:40] * 6)[:200]
+    kvd = cs.KV(model, 1, 300)
+    spec, _ = cs.cs_decode(model, kvd, rep, 32, 3, 10)
+    greedy = cs.cs_decode_greedy(model, kvd, rep, 32)
+    margin = FP32_MARGIN if shape.dtype == "f32" else MARGIN
+    n_spec = _follows_oracle(w, rep, spec, margin, 300)
+    n_greedy = _follows_oracle(w, rep, greedy, margin, 300)
+    assert spec[:min(n_spec, n_greedy)] == greedy[:min(n_spec, n_greedy)]
+    assert min(n_spec, n_greedy) >= 8
+    kvd.destroy()
+    model.destroy()
+
+
+def test_qkv_bias_comes_complete_or_not_at_all():
+    shape = SMALLF32.with_qkv_bias()
+    w = synth.model_weights(shape, 778, threads=1)
+    w["layers"][1] = {k: v for k, v in w["layers"][1].items() if k != "bk"}
+    with pytest.raises(cs.CopySpecError) as e:
+        cs.Model(w, max_batch=1, max_k=4)
+    assert e.value.code == -2                        # CS_E_ARG
+
+
 @pytest.mark.parametrize("shape", [MINI64, MINI128, SMALLF32])
 def test_long_prompt_goes_through_512_row_blocks(shape):
     """A 700-token prompt is ingested in blocks of 512 rows (a full block and a ragged one that

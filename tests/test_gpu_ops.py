@@ -363,3 +363,13 @@ def test_verify_llama8b_width_block_size_sweep(B, k):
     shape = synth.LLAMA_8B.with_layers(1)
     worst = _deep_verify(shape, B, 300, k, [B - 1], seed=synth.seed_for(5) + 10 * k + B)
     assert worst <= 2e-2, worst
+
+
+@pytest.mark.parametrize("B,k", [(8, 10), (16, 32), (1, 50)])
+def test_verify_llama8b_width_with_qkv_bias(B, k):
+    """Biases on the q, k, v projections at the 8B width, one layer: 88 rows (added in the attention
+    kernel's own rotary stage), 528 rows (the many-row rotary kernel), 51 rows of one stream (the
+    small rotary kernel), against the oracle with the same biases."""
+    shape = synth.LLAMA_8B.with_layers(1).with_qkv_bias()
+    worst = _deep_verify(shape, B, 300, k, [B - 1], seed=synth.seed_for(5) + 100 + k)
+    assert worst <= 2e-2, worst
