@@ -160,7 +160,8 @@ def bench_prefill(args):
     import torch
     import synth
     from paper_2502_08923_amd import binding as cs
-    shape = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B}[args.shape]
+    from paper_2502_08923_amd import workload as wl
+    shape = wl.SHAPES[args.shape]
     if args.layers:
         shape = shape.with_layers(args.layers)
     n = args.prefill
@@ -195,7 +196,7 @@ def bench_prefill(args):
         "value": rows / t, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1),
         "ms_per_step": t * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE, "data": "synthetic",
-        "config": {"workload": f"llama-{args.shape} shape x{shape.n_layers} layers, one stream, {n}-token prompt "
+        "config": {"workload": f"{shape.name} shape x{shape.n_layers} layers, one stream, {n}-token prompt "
                                f"ingested by cs_prefill (one whole prompt per step)", "prompt": n},
         "roofline": {"bound": "mfma", "kernel": "k_gemm_dma (all projections of the prompt blocks)",
                      "achieved": gemm_flops / gemm_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -313,7 +314,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--shape", default="8b", choices=["8b", "1b"])
+    ap.add_argument("--shape", default="8b", choices=["8b", "1b", "qwen7b"])
     ap.add_argument("--layers", type=int, default=0, help="override depth (debug only; invalid as a result)")
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--k", type=int, default=10)
@@ -443,7 +444,7 @@ def main():
         "data": "synthetic",
         "emitted_tokens_per_s": float((acc + 1).sum()) / t_step,
         "mean_accepted_per_attempt": float(acc.mean()),
-        "config": {"workload": f"llama-{args.shape} shape x{st['shape'].n_layers} layers, batch {B} streams, "
+        "config": {"workload": f"{st['shape'].name} shape x{st['shape'].n_layers} layers, batch {B} streams, "
                                f"{args.doc}-token document + {args.hist}-token history with planted "
                                f"document spans (KV length {st['L']} + pending), gamma={st['gamma']}, k={k}, "
                                f"drafts planted so that {acc.tolist()} of {k} are accepted, "

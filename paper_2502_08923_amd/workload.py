@@ -13,7 +13,7 @@ import torch
 import synth
 from . import binding as cs
 
-SHAPES = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B}
+SHAPES = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B, "qwen7b": synth.QWEN_7B}
 
 
 def log(*a):

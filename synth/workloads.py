@@ -77,6 +77,8 @@ class ModelShape:
 TINY = ModelShape("tiny", 2, 256, 4, 4, 64, 1024, 1024, 10000.0, 1e-5, "f32")
 LLAMA_1B = ModelShape("llama-1b", 16, 2048, 32, 8, 64, 8192, 32000, 10000.0, 1e-5, "bf16")
 LLAMA_8B = ModelShape("llama-8b", 32, 4096, 32, 8, 128, 14336, 128256, 500000.0, 1e-5, "bf16")
+# the 7B member of the other family the paper runs (Sec. 4.1): seven query heads per KV head, q/k/v biases
+QWEN_7B = ModelShape("qwen2.5-7b", 28, 3584, 28, 4, 128, 18944, 152064, 1000000.0, 1e-6, "bf16", True)
 
 
 # ----------------------------------------------------------------------------

@@ -21,6 +21,9 @@ MARGIN = 1e-2
 MINI64 = ModelShape("mini-hd64", 2, 256, 4, 2, 64, 512, 1024, 10000.0, 1e-5, "bf16")
 MINI128 = ModelShape("mini-hd128", 3, 512, 8, 2, 128, 1024, 2000, 500000.0, 1e-5, "bf16")
 SMALLF32 = ModelShape("small-f32", 2, 64, 4, 2, 16, 96, 97, 10000.0, 1e-5, "f32")
+# the Qwen2.5 conventions (Sec. 4.1 runs that family too): seven query heads per KV head, q/k/v
+# biases, rotary base 1e6, epsilon 1e-6
+MINIQWEN = ModelShape("mini-qwen", 2, 896, 14, 2, 64, 1152, 1504, 1000000.0, 1e-6, "bf16", True)
 
 
 def t32(a):
@@ -148,7 +151,7 @@ def test_verify_matches_oracle(shape, plain):
 
 
 @pytest.mark.parametrize("shape,plain", [(MINI64, False), (MINI64, True), (MINI128, False),
-                                         (SMALLF32, False)])
+                                         (SMALLF32, False), (MINIQWEN, False)])
 def test_verify_and_decode_with_qkv_bias(shape, plain):
     """Biases on the q, k, v projections (the Qwen2.5 family of Sec. 4.1): prompt blocks (the
     many-row rotary kernel), the verify block (the attention kernel's own rotary stage for

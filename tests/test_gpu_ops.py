@@ -373,3 +373,15 @@ def test_verify_llama8b_width_with_qkv_bias(B, k):
     shape = synth.LLAMA_8B.with_layers(1).with_qkv_bias()
     worst = _deep_verify(shape, B, 300, k, [B - 1], seed=synth.seed_for(5) + 100 + k)
     assert worst <= 2e-2, worst
+
+
+QWEN_7B = ModelShape("qwen2.5-7b-width", 1, 3584, 28, 4, 128, 18944, 152064, 1000000.0, 1e-6, "bf16", True)
+
+
+@pytest.mark.parametrize("B,k,L", [(8, 10, 300), (1, 10, 4000), (16, 32, 300)])
+def test_verify_qwen7b_width(B, k, L):
+    """The other model family of Sec. 4.1 at its 7B width, one layer: 28 query heads over 4 KV heads
+    (seven per KV head, so 11 block rows already need two 48-row query groups), d_model 3584,
+    d_ff 18944, 152064-token vocabulary, q/k/v biases; 88 and 528 block rows and one stream."""
+    worst = _deep_verify(QWEN_7B, B, L, k, [B - 1], seed=synth.seed_for(5) + 300 + k + B)
+    assert worst <= 2e-2, worst
