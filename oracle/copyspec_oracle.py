@@ -218,12 +218,18 @@ def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
     return x / np.sqrt(ms + eps) * gain
 
 
-def rotary(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+def rotary(x: np.ndarray, pos: np.ndarray, theta: float, inv_freq=None) -> np.ndarray:
     """x: [rows][heads][hd]; pos: [rows].  Pairs (j, j + hd/2) are rotated by the angle
-    pos * theta**(-2j/hd)  (rotate-half convention)."""
+    pos * theta**(-2j/hd)  (rotate-half convention), or by pos * inv_freq[j] when the model
+    brings its own frequencies (checkpoints with rescaled rotary frequencies, e.g. the
+    Llama-3.1 models of Sec. 4.1)."""
     hd = x.shape[-1]
     half = hd // 2
     inv = theta ** (-(np.arange(half, dtype=np.float64) * 2.0) / hd)
+    if inv_freq is not None:
+        inv = np.asarray(inv_freq, dtype=np.float64)
+        if inv.shape != (half,):
+            raise ValueError("inv_freq must hold head_dim/2 frequencies")
     ang = pos.astype(np.float64)[:, None] * inv[None, :]
     c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
     x1, x2 = x[..., :half], x[..., half:]
@@ -302,8 +308,8 @@ def forward_block(w: dict, kv: KVCache, tokens, store_dtype: str | None = None,
         if "bq" in lw:      # model families whose q, k, v projections carry a bias (Sec. 4.1: Qwen2.5)
             q, kk, vv = q + _f64(lw["bq"]), kk + _f64(lw["bk"]), vv + _f64(lw["bv"])
         q, kk, vv = q.reshape(R, H, hd), kk.reshape(R, KVH, hd), vv.reshape(R, KVH, hd)
-        q = rotary(q, pos, sh.rope_theta)
-        kk = rotary(kk, pos, sh.rope_theta)
+        q = rotary(q, pos, sh.rope_theta, w.get("rope_inv_freq"))
+        kk = rotary(kk, pos, sh.rope_theta, w.get("rope_inv_freq"))
         if store == "bf16":
             kk, vv = round_bf16(kk), round_bf16(vv)
         elif store == "f32":

@@ -74,6 +74,78 @@ def test_forward_matches_library_llama(small_w):
     assert np.abs(tail - got[20:]).max() < 1e-11
 
 
+def _llama3_inv_freq(hd, theta, factor, low, high, orig_len):
+    """Rescaled rotary frequencies of the Llama-3.1 checkpoints, from their published recipe:
+    wavelengths beyond orig_len/low are slowed down by `factor`, those below orig_len/high are kept,
+    the band between is blended linearly in orig_len/wavelength."""
+    inv = theta ** (-(np.arange(hd // 2, dtype=np.float64) * 2.0) / hd)
+    out = []
+    for f in inv:
+        wavelen = 2.0 * np.pi / f
+        if wavelen < orig_len / high:
+            out.append(f)
+        elif wavelen > orig_len / low:
+            out.append(f / factor)
+        else:
+            smooth = (orig_len / wavelen - low) / (high - low)
+            out.append((1.0 - smooth) * f / factor + smooth * f)
+    return np.array(out)
+
+
+def test_rescaled_rotary_frequencies_match_library_llama3():
+    """Models that bring their own rotary frequencies (the Llama-3.1 checkpoints of Sec. 4.1 rescale
+    theirs): the oracle rotates pair j at position p by p * inv_freq[j].  Pinned against the
+    `transformers` Llama with rope_type llama3, on a table written out from the published recipe;
+    the short original context (32) puts the three bands of the recipe inside this head size."""
+    from transformers import LlamaConfig, LlamaForCausalLM
+    sh = SMALL
+    w = dict(synth.model_weights(sh, 2468, threads=1))
+    scaling = {"rope_type": "llama3", "factor": 8.0, "low_freq_factor": 1.0, "high_freq_factor": 4.0,
+               "original_max_position_embeddings": 32, "rope_theta": sh.rope_theta}
+    inv = _llama3_inv_freq(sh.head_dim, sh.rope_theta, 8.0, 1.0, 4.0, 32)
+    plain = sh.rope_theta ** (-(np.arange(sh.head_dim // 2) * 2.0) / sh.head_dim)
+    kept, slowed = np.isclose(inv, plain), np.isclose(inv, plain / 8.0)
+    assert kept.any() and slowed.any() and (~kept & ~slowed).any()       # all three bands occur
+    try:
+        cfg = LlamaConfig(vocab_size=sh.vocab, hidden_size=sh.d_model, intermediate_size=sh.d_ff,
+                          num_hidden_layers=sh.n_layers, num_attention_heads=sh.n_heads,
+                          num_key_value_heads=sh.n_kv_heads, head_dim=sh.head_dim,
+                          rms_norm_eps=sh.rms_eps, rope_parameters=scaling,
+                          tie_word_embeddings=False, attention_bias=False, mlp_bias=False,
+                          max_position_embeddings=4096, hidden_act="silu")
+    except TypeError:                                    # older releases of the library
+        cfg = LlamaConfig(vocab_size=sh.vocab, hidden_size=sh.d_model, intermediate_size=sh.d_ff,
+                          num_hidden_layers=sh.n_layers, num_attention_heads=sh.n_heads,
+                          num_key_value_heads=sh.n_kv_heads, head_dim=sh.head_dim,
+                          rms_norm_eps=sh.rms_eps, rope_theta=sh.rope_theta, rope_scaling=scaling,
+                          tie_word_embeddings=False, attention_bias=False, mlp_bias=False,
+                          max_position_embeddings=4096, hidden_act="silu")
+    m = LlamaForCausalLM(cfg).double().eval()
+    lib_inv = m.model.rotary_emb.inv_freq.double().numpy()
+    assert np.abs(lib_inv - inv).max() < 1e-6 * inv.max()              # float32 table in the library
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    sd = {"model.embed_tokens.weight": t(w["embed"]), "model.norm.weight": t(w["final_norm"]),
+          "lm_head.weight": t(w["lm_head"])}
+    names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj",
+             "wo": "self_attn.o_proj", "wg": "mlp.gate_proj", "wu": "mlp.up_proj",
+             "wd": "mlp.down_proj", "norm1": "input_layernorm", "norm2": "post_attention_layernorm"}
+    for l, lw in enumerate(w["layers"]):
+        for k, n in names.items():
+            sd[f"model.layers.{l}.{n}.weight"] = t(lw[k])
+    missing, unexpected = m.load_state_dict(sd, strict=False)
+    assert not [k for k in missing if "rotary" not in k] and not unexpected
+    rng = np.random.default_rng(9)
+    toks = rng.integers(0, sh.vocab, 60)
+    with torch.no_grad():
+        ref = m(torch.from_numpy(toks)[None]).logits[0].numpy()
+    w["rope_inv_freq"] = inv
+    got = orc.forward_block(w, orc.KVCache(sh, 64), toks, store_dtype="f64")
+    assert np.abs(got - ref).max() < 2e-5
+    del w["rope_inv_freq"]
+    unscaled = orc.forward_block(w, orc.KVCache(sh, 64), toks, store_dtype="f64")
+    assert np.abs(unscaled - ref).max() > 1e-2           # the rescaling matters at these positions
+
+
 def test_qkv_bias_matches_library_qwen2():
     """The q/k/v biases of the Qwen2.5 family (Sec. 4.1 runs both families): same weights and
     biases in the `transformers` Qwen2 implementation; a dropped, doubled or head-misplaced bias,
