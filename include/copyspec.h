@@ -207,6 +207,13 @@ int cs_model_range_status(cs_model* m, int32_t* flags /*host*/, int32_t clear);
 int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_model** out);
 void cs_model_destroy(cs_model*);
 
+/* Rotary frequencies of the model's own (checkpoints that rescale them, e.g. the Llama-3.1 models
+ * of Sec. 4.1): pair (j, j + head_dim/2) at position p is rotated by p * inv_freq[j] instead of
+ * p * rope_theta^(-2j/head_dim).  inv_freq: host array of head_dim/2 finite values, copied; NULL
+ * goes back to rope_theta.  Synchronous (waits for the device); applies to the calls that
+ * follow, so set it before the first prompt goes into a cache of this model. */
+int cs_model_set_rope_inv_freq(cs_model* m, const double* inv_freq /*host [head_dim/2] or NULL*/);
+
 /* KV cache for `batch` independent streams of up to `capacity` positions each, all layers.
  * Lengths start at 0. */
 int cs_kv_create(const cs_model* m, int32_t batch, int64_t capacity, cs_kv** out);

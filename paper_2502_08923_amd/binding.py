@@ -25,7 +25,7 @@ POLICIES = {"rightmost": CS_POLICY_RIGHTMOST, "first": CS_POLICY_FIRST, "context
 
 EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev", "cs_find_match_batch_dev_noalloc",
-    "cs_model_create", "cs_model_destroy", "cs_model_range_status", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
+    "cs_model_create", "cs_model_destroy", "cs_model_range_status", "cs_model_set_rope_inv_freq", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
     "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_prefill_batch", "cs_decode_batch", "cs_index_create", "cs_index_destroy",
     "cs_index_reset", "cs_index_find_match_batch_dev", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
@@ -100,6 +100,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_model_destroy.argtypes = [vp]
     lib.cs_model_destroy.restype = None
     lib.cs_model_range_status.argtypes = [vp, C.POINTER(i32), i32]
+    lib.cs_model_set_rope_inv_freq.argtypes = [vp, C.POINTER(C.c_double)]
     lib.cs_kv_create.argtypes = [vp, i32, i64, C.POINTER(vp)]
     lib.cs_kv_destroy.argtypes = [vp]
     lib.cs_kv_destroy.restype = None
@@ -324,6 +325,19 @@ class Model:
         self.handle = h
         self.device = dev
         del keep
+        if weights.get("rope_inv_freq") is not None:      # the model brings its own rotary frequencies
+            self.set_rope_inv_freq(weights["rope_inv_freq"])
+
+    def set_rope_inv_freq(self, inv_freq):
+        """head_dim/2 rotary frequencies (angle of pair j at position p = p * inv_freq[j]); None
+        goes back to rope_theta."""
+        if inv_freq is None:
+            _check(load_library().cs_model_set_rope_inv_freq(self.handle, None))
+            return
+        a = np.ascontiguousarray(np.asarray(inv_freq, dtype=np.float64))
+        if a.shape != (self.shape.head_dim // 2,):
+            raise ValueError("inv_freq must hold head_dim/2 values")
+        _check(load_library().cs_model_set_rope_inv_freq(self.handle, a.ctypes.data_as(C.POINTER(C.c_double))))
 
     def range_status(self, clear: bool = True) -> int:
         """CS_RANGE_* bits raised since the last clear (waits for the device)."""

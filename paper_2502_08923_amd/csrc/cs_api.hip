@@ -2,6 +2,7 @@
 // Host logic only; every arithmetic step runs in the kernels of the other files.
 #include <stdarg.h>
 #include <stdlib.h>
+#include <cmath>
 
 #include <vector>
 
@@ -163,7 +164,8 @@ static void model_free(cs_model* m) {
     if (!m) return;
     void* ptrs[] = {m->embed, m->lm_head, m->final_norm, m->x, m->xn, m->q, m->gu, m->act,
                     m->logits, m->part, m->attn_part, m->rope, m->tok, m->am_val_idx,
-                    m->row_argmax, m->draft, m->draft_len, m->match_pos, m->pending, m->range_flags};
+                    m->row_argmax, m->draft, m->draft_len, m->match_pos, m->pending, m->range_flags,
+                    m->rope_inv_freq};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     if (m->layers) {
@@ -323,6 +325,23 @@ extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_
 extern "C" void cs_model_destroy(cs_model* m) {
     if (m) (void)hipDeviceSynchronize();
     model_free(m);
+}
+
+extern "C" int cs_model_set_rope_inv_freq(cs_model* m, const double* inv_freq) {
+    CS_REQUIRE(m, CS_E_ARG, "cs_model_set_rope_inv_freq: NULL model");
+    const int half = m->cfg.head_dim / 2;
+    if (inv_freq)
+        for (int j = 0; j < half; ++j)
+            CS_REQUIRE(std::isfinite(inv_freq[j]), CS_E_ARG, "rotary frequency %d is not finite", j);
+    CS_HIP(hipDeviceSynchronize());
+    if (!inv_freq) {
+        if (m->rope_inv_freq) (void)hipFree(m->rope_inv_freq);
+        m->rope_inv_freq = nullptr;
+        return CS_OK;
+    }
+    if (!m->rope_inv_freq) DEV_ALLOC(m->rope_inv_freq, (size_t)half * sizeof(double));
+    CS_HIP(hipMemcpy(m->rope_inv_freq, inv_freq, (size_t)half * sizeof(double), hipMemcpyHostToDevice));
+    return CS_OK;
 }
 
 extern "C" int cs_model_range_status(cs_model* m, int32_t* flags, int32_t clear) {

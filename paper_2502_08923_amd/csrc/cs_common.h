@@ -99,6 +99,7 @@ struct cs_model {
     float* attn_part;   // attention split partials
     size_t attn_part_floats;
     float2* rope;       // [R][hd/2] (cos, sin) of every block row's position
+    double* rope_inv_freq;   // [hd/2] rotary frequencies of the model's own (device), or NULL
     int32_t* tok;       // [R] token of every block row
     int32_t* am_val_idx;// argmax partials: [R][chunks] (float bits, idx) pairs
     int32_t* row_argmax;// [R]

@@ -24,12 +24,13 @@ __global__ void k_tokens(const int32_t* __restrict__ pending, const int32_t* __r
 }
 
 __global__ void k_rope_table(const int32_t* __restrict__ kv_len, int rows, int half, int hd,
-                             double theta, float2* __restrict__ rope) {
+                             double theta, const double* __restrict__ inv_freq,
+                             float2* __restrict__ rope) {
     const int r = blockIdx.x;
     const int b = r / rows, i = r % rows;
     const double pos = (double)(kv_len[b] + i);
     for (int j = threadIdx.x; j < half; j += blockDim.x) {
-        const double inv = pow(theta, -2.0 * (double)j / (double)hd);
+        const double inv = inv_freq ? inv_freq[j] : pow(theta, -2.0 * (double)j / (double)hd);
         double sn, cs;
         sincos(pos * inv, &sn, &cs);
         rope[(int64_t)r * half + j] = make_float2((float)cs, (float)sn);
@@ -427,7 +428,7 @@ int cs_tokens_launch(const cs_model* m, const int32_t* pending, const int32_t* d
 
 int cs_rope_table_launch(const cs_model* m, const int32_t* kv_len, int B, int rows, hipStream_t s) {
     k_rope_table<<<B * rows, 64, 0, s>>>(kv_len, rows, m->cfg.head_dim / 2, m->cfg.head_dim,
-                                         (double)m->cfg.rope_theta, m->rope);
+                                         (double)m->cfg.rope_theta, m->rope_inv_freq, m->rope);
     return cs_launch_ok("k_rope_table");
 }
 

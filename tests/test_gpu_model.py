@@ -195,6 +195,42 @@ def test_verify_and_decode_with_qkv_bias(shape, plain):
     model.destroy()
 
 
+@pytest.mark.parametrize("shape,plain", [(MINI128, False), (MINI64, True), (SMALLF32, False)])
+def test_model_supplied_rotary_frequencies(shape, plain):
+    """A model that brings its own rotary frequencies (rescaled tables as in the Llama-3.1
+    checkpoints of Sec. 4.1): prompt blocks, the verify block and the cache rows against the oracle
+    given the same table; taking the table away again gives the rope_theta results."""
+    w = dict(synth.model_weights(shape, 909, threads=4))
+    half = shape.head_dim // 2
+    rng = np.random.default_rng(31)
+    base = shape.rope_theta ** (-(np.arange(half) * 2.0) / shape.head_dim)
+    w["rope_inv_freq"] = base / rng.uniform(1.0, 8.0, half)
+    model = cs.Model(w, max_batch=1, max_k=10, plain=plain)
+    prompt = rng.integers(0, shape.vocab, 300).tolist()
+    truth = orc.greedy_decode(w, prompt, 12)
+    draft = truth[:6] + [(truth[6] + 1) % shape.vocab] + truth[7:10]
+    kv, okv, err = _verify_case(w, model, prompt, draft, 10, cap=400)
+    for layer in range(shape.n_layers):
+        k_rows, _ = kv.read(layer, 0, 0, okv.length)
+        _cache_rows_close(k_rows, okv.k[layer, :, :okv.length], tol_for(shape))
+    kv.destroy()
+    # the table matters: the oracle without it is far from the oracle with it
+    w0 = {k: v for k, v in w.items() if k != "rope_inv_freq"}
+    a = orc.KVCache(shape, 400)
+    b = orc.KVCache(shape, 400)
+    pa, pb = orc.prefill(w, a, prompt, chunk=32), orc.prefill(w0, b, prompt, chunk=32)
+    assert np.abs(orc.verify(w, a, pa, draft)[2] - orc.verify(w0, b, pb, draft)[2]).max() > 0.05
+    # without the table the library is the rope_theta model again
+    model.set_rope_inv_freq(None)
+    kv, okv, err = _verify_case(w0, model, prompt, draft, 10, cap=400)
+    kv.destroy()
+    with pytest.raises(ValueError):
+        model.set_rope_inv_freq(np.ones(half + 1))
+    with pytest.raises(cs.CopySpecError):
+        model.set_rope_inv_freq(np.full(half, np.inf))
+    model.destroy()
+
+
 def test_qkv_bias_comes_complete_or_not_at_all():
     shape = SMALLF32.with_qkv_bias()
     w = synth.model_weights(shape, 778, threads=1)
