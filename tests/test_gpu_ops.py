@@ -385,3 +385,14 @@ def test_verify_qwen7b_width(B, k, L):
     d_ff 18944, 152064-token vocabulary, q/k/v biases; 88 and 528 block rows and one stream."""
     worst = _deep_verify(QWEN_7B, B, L, k, [B - 1], seed=synth.seed_for(5) + 300 + k + B)
     assert worst <= 2e-2, worst
+
+
+LLAMA_70B_WIDTH = ModelShape("llama-70b-width", 1, 8192, 64, 8, 128, 28672, 128256, 500000.0, 1e-5, "bf16")
+
+
+@pytest.mark.parametrize("B,k", [(8, 10), (1, 10)])
+def test_verify_llama70b_width(B, k):
+    """The largest width the paper runs (Sec. 4.1: 70B / 72B models), one layer: d_model 8192 (the
+    widest row the norm kernel takes), 64 heads over 8 KV heads, d_ff 28672."""
+    worst = _deep_verify(LLAMA_70B_WIDTH, B, 300, k, [B - 1], seed=synth.seed_for(5) + 700 + B)
+    assert worst <= 2e-2, worst
