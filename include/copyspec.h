@@ -207,6 +207,18 @@ int cs_model_range_status(cs_model* m, int32_t* flags /*host*/, int32_t clear);
 int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_model** out);
 void cs_model_destroy(cs_model*);
 
+/* Staged creation, for models whose caller-side weights should not sit in device memory next to
+ * the library's copy all at once (the 70B-class models of Sec. 4.1 are 141 GB in bfloat16, half of
+ * one GPU's memory): cs_model_create_staged allocates the library's storage and workspace,
+ * cs_model_load_head and cs_model_load_layer then take the parts in any order, each call copying
+ * (and re-laying-out) what it is given and returning when the caller's buffers may be freed.  A
+ * layer may be loaded again (new weights).  Until the head and every layer have been loaded,
+ * calls that run the model fail with CS_E_STATE.  cs_model_create is the same thing in one call.
+ * Pointers are device pointers with the layouts of cs_weights / cs_layer_weights.  Synchronous. */
+int cs_model_create_staged(const cs_model_cfg* cfg, cs_model** out);
+int cs_model_load_head(cs_model* m, const void* embed, const void* lm_head, const float* final_norm);
+int cs_model_load_layer(cs_model* m, int32_t layer, const cs_layer_weights* w);
+
 /* Rotary frequencies of the model's own (checkpoints that rescale them, e.g. the Llama-3.1 models
  * of Sec. 4.1): pair (j, j + head_dim/2) at position p is rotated by p * inv_freq[j] instead of
  * p * rope_theta^(-2j/head_dim).  inv_freq: host array of head_dim/2 finite values, copied; NULL

@@ -25,7 +25,8 @@ POLICIES = {"rightmost": CS_POLICY_RIGHTMOST, "first": CS_POLICY_FIRST, "context
 
 EXPORTS = [
     "cs_last_error", "cs_version", "cs_find_match", "cs_find_match_ex", "cs_find_match_batch_dev", "cs_find_match_batch_dev_noalloc",
-    "cs_model_create", "cs_model_destroy", "cs_model_range_status", "cs_model_set_rope_inv_freq", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
+    "cs_model_create", "cs_model_create_staged", "cs_model_load_head", "cs_model_load_layer", "cs_model_destroy",
+    "cs_model_range_status", "cs_model_set_rope_inv_freq", "cs_kv_create", "cs_kv_destroy", "cs_kv_set_len",
     "cs_kv_len", "cs_kv_load", "cs_kv_read", "cs_verify", "cs_step", "cs_decode",
     "cs_decode_greedy", "cs_decode_merged", "cs_prefill", "cs_prefill_batch", "cs_decode_batch", "cs_index_create", "cs_index_destroy",
     "cs_index_reset", "cs_index_find_match_batch_dev", "cs_op_gemm", "cs_op_attention", "cs_op_argmax_accept",
@@ -97,6 +98,9 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.cs_index_reset.argtypes = [vp, vp]
     lib.cs_index_find_match_batch_dev.argtypes = [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.cs_model_create.argtypes = [C.POINTER(cs_model_cfg), C.POINTER(cs_weights), C.POINTER(vp)]
+    lib.cs_model_create_staged.argtypes = [C.POINTER(cs_model_cfg), C.POINTER(vp)]
+    lib.cs_model_load_head.argtypes = [vp, vp, vp, vp]
+    lib.cs_model_load_layer.argtypes = [vp, i32, C.POINTER(cs_layer_weights)]
     lib.cs_model_destroy.argtypes = [vp]
     lib.cs_model_destroy.restype = None
     lib.cs_model_range_status.argtypes = [vp, C.POINTER(i32), i32]
@@ -282,7 +286,11 @@ def _to_dev(a, bf16: bool, device) -> torch.Tensor:
 class Model:
     """cs_model handle.  `weights` is a dict like synth.model_weights returns (numpy or torch
     arrays; uint16 = bfloat16 bits); they are uploaded, handed to cs_model_create (which copies
-    them into library-owned memory) and released."""
+    them into library-owned memory) and released.  If weights["layers"] is a function of the
+    layer index (and weights["head"] a function returning embed, lm_head, final_norm), as
+    synth.model_weights_lazy returns, the model is created in stages: one part at a time is
+    drawn, uploaded, handed to cs_model_load_layer / cs_model_load_head and released, so the
+    caller-side copy never exceeds one layer."""
 
     def __init__(self, weights: dict, max_batch: int, max_k: int, plain: bool = False,
                  device="cuda:0", prompt_block_rows: int = 0):
@@ -302,29 +310,52 @@ class Model:
             keep.append(t)
             return t.data_ptr()
 
-        layers = (cs_layer_weights * sh.n_layers)()
-        for l, lw in enumerate(weights["layers"]):
+        def fill_layer(dst, lw):
             for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
-                setattr(layers[l], name, up(lw[name], bf16))
-            layers[l].norm1 = up(lw["norm1"], False)
-            layers[l].norm2 = up(lw["norm2"], False)
+                setattr(dst, name, up(lw[name], bf16))
+            dst.norm1 = up(lw["norm1"], False)
+            dst.norm2 = up(lw["norm2"], False)
             for name in ("bq", "bk", "bv"):           # optional float32 projection biases
                 if name in lw:
-                    setattr(layers[l], name, up(lw[name], False))
-        w = cs_weights(up(weights["embed"], bf16), up(weights["lm_head"], bf16),
-                       up(weights["final_norm"], False), layers)
+                    setattr(dst, name, up(lw[name], False))
+
+        staged = callable(weights["layers"])
         h = C.c_void_p()
         lib.cs_set_plain_kernels(1 if plain else 0)
         lib.cs_set_prompt_block_rows(prompt_block_rows)
         try:
             torch.cuda.synchronize(dev)
-            _check(lib.cs_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
+            if staged:
+                _check(lib.cs_model_create_staged(C.byref(cfg), C.byref(h)))
+            else:
+                layers = (cs_layer_weights * sh.n_layers)()
+                for l, lw in enumerate(weights["layers"]):
+                    fill_layer(layers[l], lw)
+                w = cs_weights(up(weights["embed"], bf16), up(weights["lm_head"], bf16),
+                               up(weights["final_norm"], False), layers)
+                _check(lib.cs_model_create(C.byref(cfg), C.byref(w), C.byref(h)))
         finally:
             lib.cs_set_plain_kernels(0)
             lib.cs_set_prompt_block_rows(0)
         self.handle = h
         self.device = dev
-        del keep
+        del keep[:]
+        if staged:
+            try:
+                head = weights["head"]()
+                _check(lib.cs_model_load_head(h, up(head["embed"], bf16), up(head["lm_head"], bf16),
+                                              up(head["final_norm"], False)))
+                del head, keep[:]
+                for l in range(sh.n_layers):
+                    one = cs_layer_weights()
+                    lw = weights["layers"](l)
+                    fill_layer(one, lw)
+                    torch.cuda.synchronize(dev)
+                    _check(lib.cs_model_load_layer(h, l, C.byref(one)))
+                    del lw, keep[:]
+            except Exception:
+                self.destroy()
+                raise
         if weights.get("rope_inv_freq") is not None:      # the model brings its own rotary frequencies
             self.set_rope_inv_freq(weights["rope_inv_freq"])
 

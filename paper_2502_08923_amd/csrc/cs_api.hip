@@ -177,55 +177,68 @@ static void model_free(cs_model* m) {
         }
         free(m->layers);
     }
+    free(m->layer_loaded);
     free(m);
 }
 
-static int model_build(cs_model* m, const cs_weights* w) {
+// the float16 matrix cores cannot hold every bfloat16 weight: checked after every load
+static int weight_range_check(cs_model* m) {
+    CS_HIP(hipDeviceSynchronize());
+    if (!m->fast) return CS_OK;
+    int32_t flags = 0;
+    CS_HIP(hipMemcpy(&flags, m->range_flags, 4, hipMemcpyDeviceToHost));
+    CS_REQUIRE(!(flags & CS_RANGE_WEIGHT), CS_E_UNSUPPORTED,
+               "a projection weight is not finite or exceeds 65504 in magnitude: the float16 matrix "
+               "cores cannot hold it (cs_set_plain_kernels(1) selects kernels without this limit)");
+    return CS_OK;
+}
+
+// embedding, final norm gain and lm_head into the library's own storage
+static int model_load_head(cs_model* m, const void* embed, const void* lm_head, const float* final_norm) {
     const cs_model_cfg& c = m->cfg;
     const size_t e = m->esz;
-    const int d = c.d_model, hd = c.head_dim, H = c.n_heads, KVH = c.n_kv_heads, F = c.d_ff,
-              V = c.vocab;
+    const int d = c.d_model, V = c.vocab;
+    CS_REQUIRE(embed && lm_head && final_norm, CS_E_ARG, "NULL weight pointer");
+    CS_HIP(hipMemcpy(m->embed, embed, (size_t)V * d * e, hipMemcpyDeviceToDevice));
+    CS_HIP(hipMemcpy(m->final_norm, final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice));
+    if (m->fast) CS_TRY(cs_tile_weights_launch(lm_head, nullptr, V, d, 0, V, 0, m->lm_head, m->range_flags, nullptr));
+    else CS_HIP(hipMemcpy(m->lm_head, lm_head, (size_t)V * d * e, hipMemcpyDeviceToDevice));
+    CS_TRY(weight_range_check(m));
+    m->head_loaded = 1;
+    return CS_OK;
+}
+
+// one layer's weights into the library's own storage (re-laid-out for the tuned kernels)
+static int model_load_layer(cs_model* m, int l, const cs_layer_weights& s) {
+    const cs_model_cfg& c = m->cfg;
+    const size_t e = m->esz;
+    const int d = c.d_model, hd = c.head_dim, H = c.n_heads, KVH = c.n_kv_heads, F = c.d_ff;
     const int nq = H * hd, nkv = KVH * hd, nqkv = nq + 2 * nkv;
-    DEV_ALLOC(m->embed, (size_t)V * d * e);
-    DEV_ALLOC(m->lm_head, (size_t)V * d * e);
-    DEV_ALLOC(m->final_norm, (size_t)d * 4);
-    DEV_ALLOC(m->range_flags, 4);
-    CS_HIP(hipMemset(m->range_flags, 0, 4));
-    CS_HIP(hipMemcpy(m->embed, w->embed, (size_t)V * d * e, hipMemcpyDeviceToDevice));
-    CS_HIP(hipMemcpy(m->final_norm, w->final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice));
-    if (m->fast) CS_TRY(cs_tile_weights_launch(w->lm_head, nullptr, V, d, 0, V, 0, m->lm_head, m->range_flags, nullptr));
-    else CS_HIP(hipMemcpy(m->lm_head, w->lm_head, (size_t)V * d * e, hipMemcpyDeviceToDevice));
-    for (int l = 0; l < c.n_layers; ++l) {
-        const cs_layer_weights& s = w->layers[l];
-        CS_REQUIRE(s.wq && s.wk && s.wv && s.wo && s.wg && s.wu && s.wd && s.norm1 && s.norm2,
-                   CS_E_ARG, "layer %d has a NULL weight pointer", l);
-        cs_layer_dev& L = m->layers[l];
-        DEV_ALLOC(L.wqkv, (size_t)nqkv * d * e);
-        DEV_ALLOC(L.wo, (size_t)d * nq * e);
-        DEV_ALLOC(L.wgu, (size_t)2 * F * d * e);
-        DEV_ALLOC(L.wd, (size_t)d * F * e);
-        DEV_ALLOC(L.norm1, (size_t)d * 4);
-        DEV_ALLOC(L.norm2, (size_t)d * 4);
-        char* qkv = (char*)L.wqkv;
-        CS_HIP(hipMemcpy(L.norm1, s.norm1, (size_t)d * 4, hipMemcpyDeviceToDevice));
-        CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
-        if (s.bq || s.bk || s.bv) {
-            CS_REQUIRE(s.bq && s.bk && s.bv, CS_E_ARG, "layer %d: the q, k, v biases come all three or not at all", l);
-            DEV_ALLOC(L.bqkv, (size_t)nqkv * 4);
-            CS_HIP(hipMemcpy(L.bqkv, s.bq, (size_t)nq * 4, hipMemcpyDeviceToDevice));
-            CS_HIP(hipMemcpy(L.bqkv + nq, s.bk, (size_t)nkv * 4, hipMemcpyDeviceToDevice));
-            CS_HIP(hipMemcpy(L.bqkv + nq + nkv, s.bv, (size_t)nkv * 4, hipMemcpyDeviceToDevice));
-        }
-        if (m->fast) {
-            // the q, k and v blocks become row ranges of one tiled matrix
-            CS_TRY(cs_tile_weights_launch(s.wq, nullptr, nq, d, 0, nqkv, 0, qkv, m->range_flags, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wk, nullptr, nkv, d, 0, nqkv, nq, qkv, m->range_flags, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wv, nullptr, nkv, d, 0, nqkv, nq + nkv, qkv, m->range_flags, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wo, nullptr, d, nq, 0, d, 0, L.wo, m->range_flags, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wg, s.wu, 2 * F, d, 1, 2 * F, 0, L.wgu, m->range_flags, nullptr));
-            CS_TRY(cs_tile_weights_launch(s.wd, nullptr, d, F, 0, d, 0, L.wd, m->range_flags, nullptr));
-            continue;
-        }
+    CS_REQUIRE(s.wq && s.wk && s.wv && s.wo && s.wg && s.wu && s.wd && s.norm1 && s.norm2,
+               CS_E_ARG, "layer %d has a NULL weight pointer", l);
+    cs_layer_dev& L = m->layers[l];
+    char* qkv = (char*)L.wqkv;
+    CS_HIP(hipMemcpy(L.norm1, s.norm1, (size_t)d * 4, hipMemcpyDeviceToDevice));
+    CS_HIP(hipMemcpy(L.norm2, s.norm2, (size_t)d * 4, hipMemcpyDeviceToDevice));
+    if (s.bq || s.bk || s.bv) {
+        CS_REQUIRE(s.bq && s.bk && s.bv, CS_E_ARG, "layer %d: the q, k, v biases come all three or not at all", l);
+        if (!L.bqkv) DEV_ALLOC(L.bqkv, (size_t)nqkv * 4);
+        CS_HIP(hipMemcpy(L.bqkv, s.bq, (size_t)nq * 4, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.bqkv + nq, s.bk, (size_t)nkv * 4, hipMemcpyDeviceToDevice));
+        CS_HIP(hipMemcpy(L.bqkv + nq + nkv, s.bv, (size_t)nkv * 4, hipMemcpyDeviceToDevice));
+    } else if (L.bqkv) {
+        (void)hipFree(L.bqkv);
+        L.bqkv = nullptr;
+    }
+    if (m->fast) {
+        // the q, k and v blocks become row ranges of one tiled matrix
+        CS_TRY(cs_tile_weights_launch(s.wq, nullptr, nq, d, 0, nqkv, 0, qkv, m->range_flags, nullptr));
+        CS_TRY(cs_tile_weights_launch(s.wk, nullptr, nkv, d, 0, nqkv, nq, qkv, m->range_flags, nullptr));
+        CS_TRY(cs_tile_weights_launch(s.wv, nullptr, nkv, d, 0, nqkv, nq + nkv, qkv, m->range_flags, nullptr));
+        CS_TRY(cs_tile_weights_launch(s.wo, nullptr, d, nq, 0, d, 0, L.wo, m->range_flags, nullptr));
+        CS_TRY(cs_tile_weights_launch(s.wg, s.wu, 2 * F, d, 1, 2 * F, 0, L.wgu, m->range_flags, nullptr));
+        CS_TRY(cs_tile_weights_launch(s.wd, nullptr, d, F, 0, d, 0, L.wd, m->range_flags, nullptr));
+    } else {
         CS_HIP(hipMemcpy(qkv, s.wq, (size_t)nq * d * e, hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(qkv + (size_t)nq * d * e, s.wk, (size_t)nkv * d * e, hipMemcpyDeviceToDevice));
         CS_HIP(hipMemcpy(qkv + (size_t)(nq + nkv) * d * e, s.wv, (size_t)nkv * d * e,
@@ -239,6 +252,32 @@ static int model_build(cs_model* m, const cs_weights* w) {
             k_pack_gu<float><<<2 * F, 256>>>((const float*)s.wg, (const float*)s.wu, F, d,
                                             (float*)L.wgu);
         CS_TRY(cs_launch_ok("k_pack_gu"));
+    }
+    CS_TRY(weight_range_check(m));          // also waits: the caller's buffers are free again
+    if (!m->layer_loaded[l]) { m->layer_loaded[l] = 1; m->layers_loaded += 1; }
+    return CS_OK;
+}
+
+// storage for the weights and the workspace; the weights come afterwards
+static int model_alloc(cs_model* m) {
+    const cs_model_cfg& c = m->cfg;
+    const size_t e = m->esz;
+    const int d = c.d_model, hd = c.head_dim, H = c.n_heads, KVH = c.n_kv_heads, F = c.d_ff,
+              V = c.vocab;
+    const int nq = H * hd, nkv = KVH * hd, nqkv = nq + 2 * nkv;
+    DEV_ALLOC(m->embed, (size_t)V * d * e);
+    DEV_ALLOC(m->lm_head, (size_t)V * d * e);
+    DEV_ALLOC(m->final_norm, (size_t)d * 4);
+    DEV_ALLOC(m->range_flags, 4);
+    CS_HIP(hipMemset(m->range_flags, 0, 4));
+    for (int l = 0; l < c.n_layers; ++l) {
+        cs_layer_dev& L = m->layers[l];
+        DEV_ALLOC(L.wqkv, (size_t)nqkv * d * e);
+        DEV_ALLOC(L.wo, (size_t)d * nq * e);
+        DEV_ALLOC(L.wgu, (size_t)2 * F * d * e);
+        DEV_ALLOC(L.wd, (size_t)d * F * e);
+        DEV_ALLOC(L.norm1, (size_t)d * 4);
+        DEV_ALLOC(L.norm2, (size_t)d * 4);
     }
     // verify blocks have up to R_max rows; prompt blocks of a single stream up to prefill_rows
     const size_t R = (size_t)(m->R_max > m->prefill_rows ? m->R_max : m->prefill_rows);
@@ -273,21 +312,11 @@ static int model_build(cs_model* m, const cs_weights* w) {
     DEV_ALLOC(m->match_pos, (size_t)c.max_batch * 4);
     DEV_ALLOC(m->pending, (size_t)c.max_batch * 4);
     CS_HIP(hipDeviceSynchronize());
-    if (m->fast) {
-        // the tuned projections multiply in float16: a weight beyond its range cannot be represented
-        int32_t flags = 0;
-        CS_HIP(hipMemcpy(&flags, m->range_flags, 4, hipMemcpyDeviceToHost));
-        CS_REQUIRE(!(flags & CS_RANGE_WEIGHT), CS_E_UNSUPPORTED,
-                   "a projection weight is not finite or exceeds 65504 in magnitude: the float16 matrix "
-                   "cores cannot hold it (cs_set_plain_kernels(1) selects kernels without this limit)");
-    }
     return CS_OK;
 }
 
-extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_model** out) {
-    CS_REQUIRE(cfg && w && out, CS_E_ARG, "cs_model_create: NULL argument");
-    CS_REQUIRE(w->embed && w->lm_head && w->final_norm && w->layers, CS_E_ARG,
-               "cs_model_create: NULL weight pointer");
+extern "C" int cs_model_create_staged(const cs_model_cfg* cfg, cs_model** out) {
+    CS_REQUIRE(cfg && out, CS_E_ARG, "cs_model_create: NULL argument");
     const cs_model_cfg& c = *cfg;
     CS_REQUIRE(c.n_layers >= 1 && c.d_model >= 1 && c.n_heads >= 1 && c.n_kv_heads >= 1 &&
                    c.head_dim >= 2 && c.d_ff >= 1 && c.vocab >= 1,
@@ -315,8 +344,33 @@ extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_
               c.d_model % 128 == 0 && c.d_ff % 128 == 0 && nq % 128 == 0 && c.vocab % 16 == 0;
     m->asz = m->fast ? 2 : 4;
     m->layers = (cs_layer_dev*)calloc(c.n_layers, sizeof(cs_layer_dev));
-    if (!m->layers) { free(m); cs_set_error("out of host memory"); return CS_E_DEVICE; }
-    const int rc = model_build(m, w);
+    m->layer_loaded = (unsigned char*)calloc(c.n_layers, 1);
+    if (!m->layers || !m->layer_loaded) { model_free(m); cs_set_error("out of host memory"); return CS_E_DEVICE; }
+    const int rc = model_alloc(m);
+    if (rc != CS_OK) { model_free(m); return rc; }
+    *out = m;
+    return CS_OK;
+}
+
+extern "C" int cs_model_load_head(cs_model* m, const void* embed, const void* lm_head, const float* final_norm) {
+    CS_REQUIRE(m, CS_E_ARG, "cs_model_load_head: NULL model");
+    return model_load_head(m, embed, lm_head, final_norm);
+}
+
+extern "C" int cs_model_load_layer(cs_model* m, int32_t layer, const cs_layer_weights* w) {
+    CS_REQUIRE(m && w, CS_E_ARG, "cs_model_load_layer: NULL argument");
+    CS_REQUIRE(layer >= 0 && layer < m->cfg.n_layers, CS_E_ARG, "layer %d outside 0..%d", layer, m->cfg.n_layers - 1);
+    return model_load_layer(m, layer, *w);
+}
+
+extern "C" int cs_model_create(const cs_model_cfg* cfg, const cs_weights* w, cs_model** out) {
+    CS_REQUIRE(cfg && w && out, CS_E_ARG, "cs_model_create: NULL argument");
+    CS_REQUIRE(w->embed && w->lm_head && w->final_norm && w->layers, CS_E_ARG,
+               "cs_model_create: NULL weight pointer");
+    cs_model* m = nullptr;
+    CS_TRY(cs_model_create_staged(cfg, &m));
+    int rc = model_load_head(m, w->embed, w->lm_head, w->final_norm);
+    for (int l = 0; l < cfg->n_layers && rc == CS_OK; ++l) rc = model_load_layer(m, l, w->layers[l]);
     if (rc != CS_OK) { model_free(m); return rc; }
     *out = m;
     return CS_OK;
@@ -612,6 +666,9 @@ static int forward_layers(cs_model* m, cs_kv* kv, int rows, hipStream_t s) {
     const int B = kv->B, R = B * rows;
     const int d = c.d_model, nq = c.n_heads * c.head_dim, nqkv = nq + 2 * c.n_kv_heads * c.head_dim;
     const int64_t len_ub = kv_max_ub(kv);
+    CS_REQUIRE(m->head_loaded && m->layers_loaded == c.n_layers, CS_E_STATE,
+               "the model is not complete: %d of %d layers loaded, embedding and lm_head %s", m->layers_loaded,
+               c.n_layers, m->head_loaded ? "loaded" : "missing");
     CS_TRY(cs_rope_table_launch(m, kv->d_len, B, rows, s));
     CS_TRY(cs_embed_launch(m, m->tok, R, s));
     int np_prev = 0, np = 1;

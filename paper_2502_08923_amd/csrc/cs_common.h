@@ -87,6 +87,8 @@ struct cs_model {
     void* lm_head;
     float* final_norm;
     cs_layer_dev* layers;   // host array
+    unsigned char* layer_loaded;   // host array: the layer's weights have been given
+    int layers_loaded, head_loaded;
     // workspace (device)
     float* x;           // [R][d] residual stream
     void* xn;           // [R][max(d, H*hd)] GEMM input (normed rows / attention output)

@@ -13,7 +13,7 @@ import torch
 import synth
 from . import binding as cs
 
-SHAPES = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B, "qwen7b": synth.QWEN_7B}
+SHAPES = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B, "qwen7b": synth.QWEN_7B, "70b": synth.LLAMA_70B}
 
 
 def log(*a):
@@ -25,6 +25,15 @@ def build_model(shape_name: str, layers: int, max_batch: int, max_k: int, dev="c
     if layers:
         shape = shape.with_layers(layers)
     t0 = time.time()
+    params = shape.n_layers * (shape.d_model * (shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim
+                               + shape.n_heads * shape.head_dim * shape.d_model + 3 * shape.d_model * shape.d_ff) \
+        + 2 * shape.vocab * shape.d_model
+    if params > 20e9:
+        # too large to hold next to the library's copy: drawn, uploaded and handed over layer by layer
+        model = cs.Model(synth.model_weights_lazy(shape, synth.seed_for(4), threads=16), max_batch=max_batch,
+                         max_k=max_k, device=dev)
+        log(f"[workload] {params / 1e9:.1f} G weights generated and loaded in stages in {time.time() - t0:.1f}s")
+        return shape, model
     w = synth.model_weights(shape, synth.seed_for(4), threads=16)
     log(f"[workload] weights generated in {time.time() - t0:.1f}s")
     t0 = time.time()

@@ -79,6 +79,8 @@ LLAMA_1B = ModelShape("llama-1b", 16, 2048, 32, 8, 64, 8192, 32000, 10000.0, 1e-
 LLAMA_8B = ModelShape("llama-8b", 32, 4096, 32, 8, 128, 14336, 128256, 500000.0, 1e-5, "bf16")
 # the 7B member of the other family the paper runs (Sec. 4.1): seven query heads per KV head, q/k/v biases
 QWEN_7B = ModelShape("qwen2.5-7b", 28, 3584, 28, 4, 128, 18944, 152064, 1000000.0, 1e-6, "bf16", True)
+# the largest model of the paper's tables in the 8B shape's family: 141 GB of bfloat16 weights
+LLAMA_70B = ModelShape("llama-70b", 80, 8192, 64, 8, 128, 28672, 128256, 500000.0, 1e-5, "bf16")
 
 
 # ----------------------------------------------------------------------------
@@ -116,6 +118,49 @@ def _draw(seed: int, shape, kind: str, scale: float, dtype: str) -> np.ndarray:
     return v.reshape(shape)
 
 
+def _head_jobs(shape: ModelShape, seed: int) -> dict:
+    d, V, dt = shape.d_model, shape.vocab, shape.dtype
+    return {("embed",): (seed * 1000 + 1, (V, d), "n", 1.0, dt),
+            ("lm_head",): (seed * 1000 + 2, (V, d), "u", math.sqrt(3.0 / d), dt),
+            ("final_norm",): (seed * 1000 + 3, (d,), "g", 0.1, "f32")}
+
+
+def _layer_jobs(shape: ModelShape, seed: int, l: int) -> dict:
+    d, hd = shape.d_model, shape.head_dim
+    H, KVH, F = shape.n_heads, shape.n_kv_heads, shape.d_ff
+    dt = shape.dtype
+    a_d = math.sqrt(3.0 / d)
+    s = seed * 1000 + 100 + 16 * l
+    jobs = {}
+    jobs[("layers", l, "wq")] = (s + 0, (H * hd, d), "u", a_d, dt)
+    jobs[("layers", l, "wk")] = (s + 1, (KVH * hd, d), "u", a_d, dt)
+    jobs[("layers", l, "wv")] = (s + 2, (KVH * hd, d), "u", a_d, dt)
+    jobs[("layers", l, "wo")] = (s + 3, (d, H * hd), "u", math.sqrt(3.0 / (H * hd)), dt)
+    jobs[("layers", l, "wg")] = (s + 4, (F, d), "u", a_d, dt)
+    jobs[("layers", l, "wu")] = (s + 5, (F, d), "u", a_d, dt)
+    jobs[("layers", l, "wd")] = (s + 6, (d, F), "u", math.sqrt(3.0 / F), dt)
+    jobs[("layers", l, "norm1")] = (s + 7, (d,), "g", 0.1, "f32")
+    jobs[("layers", l, "norm2")] = (s + 8, (d,), "g", 0.1, "f32")
+    if shape.qkv_bias:      # float32, N(0, 0.5): of the size of the projected values themselves
+        jobs[("layers", l, "bq")] = (s + 9, (H * hd,), "n", 0.5, "f32")
+        jobs[("layers", l, "bk")] = (s + 10, (KVH * hd,), "n", 0.5, "f32")
+        jobs[("layers", l, "bv")] = (s + 11, (KVH * hd,), "n", 0.5, "f32")
+    return jobs
+
+
+def _run_jobs(jobs: dict, threads: int) -> dict:
+    def run(job):
+        sd, shp, kind, scale, dtype = job
+        if kind == "g":
+            return (np.float32(1.0) + _draw(sd, shp, "u", scale, "f32")).astype(np.float32)
+        return _draw(sd, shp, kind, scale, dtype)
+
+    keys = list(jobs)
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
+        vals = list(ex.map(run, [jobs[k] for k in keys]))
+    return dict(zip(keys, vals))
+
+
 def model_weights(shape: ModelShape, seed: int, threads: int = 8) -> dict:
     """Random-init decoder weights.
 
@@ -126,46 +171,30 @@ def model_weights(shape: ModelShape, seed: int, threads: int = 8) -> dict:
     float32.  Linear weights are stored [out_features][in_features].  Shapes with qkv_bias also
     get float32 bias vectors bq, bk, bv per layer.
     """
-    d, hd = shape.d_model, shape.head_dim
-    H, KVH, F, V = shape.n_heads, shape.n_kv_heads, shape.d_ff, shape.vocab
-    dt = shape.dtype
-    a_d = math.sqrt(3.0 / d)
-    jobs = {}
-    jobs[("embed",)] = (seed * 1000 + 1, (V, d), "n", 1.0, dt)
-    jobs[("lm_head",)] = (seed * 1000 + 2, (V, d), "u", a_d, dt)
-    jobs[("final_norm",)] = (seed * 1000 + 3, (d,), "g", 0.1, "f32")
+    jobs = _head_jobs(shape, seed)
     for l in range(shape.n_layers):
-        s = seed * 1000 + 100 + 16 * l
-        jobs[("layers", l, "wq")] = (s + 0, (H * hd, d), "u", a_d, dt)
-        jobs[("layers", l, "wk")] = (s + 1, (KVH * hd, d), "u", a_d, dt)
-        jobs[("layers", l, "wv")] = (s + 2, (KVH * hd, d), "u", a_d, dt)
-        jobs[("layers", l, "wo")] = (s + 3, (d, H * hd), "u", math.sqrt(3.0 / (H * hd)), dt)
-        jobs[("layers", l, "wg")] = (s + 4, (F, d), "u", a_d, dt)
-        jobs[("layers", l, "wu")] = (s + 5, (F, d), "u", a_d, dt)
-        jobs[("layers", l, "wd")] = (s + 6, (d, F), "u", math.sqrt(3.0 / F), dt)
-        jobs[("layers", l, "norm1")] = (s + 7, (d,), "g", 0.1, "f32")
-        jobs[("layers", l, "norm2")] = (s + 8, (d,), "g", 0.1, "f32")
-        if shape.qkv_bias:      # float32, N(0, 0.5): of the size of the projected values themselves
-            jobs[("layers", l, "bq")] = (s + 9, (H * hd,), "n", 0.5, "f32")
-            jobs[("layers", l, "bk")] = (s + 10, (KVH * hd,), "n", 0.5, "f32")
-            jobs[("layers", l, "bv")] = (s + 11, (KVH * hd,), "n", 0.5, "f32")
-
-    def run(job):
-        sd, shp, kind, scale, dtype = job
-        if kind == "g":
-            return (np.float32(1.0) + _draw(sd, shp, "u", scale, "f32")).astype(np.float32)
-        return _draw(sd, shp, kind, scale, dtype)
-
-    keys = list(jobs)
-    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
-        vals = list(ex.map(run, [jobs[k] for k in keys]))
+        jobs.update(_layer_jobs(shape, seed, l))
+    vals = _run_jobs(jobs, threads)
     out = {"shape": shape, "layers": [dict() for _ in range(shape.n_layers)]}
-    for k, v in zip(keys, vals):
+    for k, v in vals.items():
         if k[0] == "layers":
             out["layers"][k[1]][k[2]] = v
         else:
             out[k[0]] = v
     return out
+
+
+def model_weights_lazy(shape: ModelShape, seed: int, threads: int = 8) -> dict:
+    """The same weights as model_weights, drawn one part at a time: "layers" is a function of the
+    layer index and "head" a function without arguments (embed, lm_head, final_norm), so that a
+    model too large to hold twice can be handed over piece by piece."""
+    def layer(l: int) -> dict:
+        return {k[2]: v for k, v in _run_jobs(_layer_jobs(shape, seed, l), threads).items()}
+
+    def head() -> dict:
+        return {k[0]: v for k, v in _run_jobs(_head_jobs(shape, seed), threads).items()}
+
+    return {"shape": shape, "layers": layer, "head": head}
 
 
 def random_kv(shape: ModelShape, n_tokens: int, seed: int, layer: int, stream: int):

@@ -231,6 +231,44 @@ def test_model_supplied_rotary_frequencies(shape, plain):
     model.destroy()
 
 
+def test_staged_creation_gives_the_same_model():
+    """A model handed over part by part (cs_model_create_staged, cs_model_load_head,
+    cs_model_load_layer) computes bit for bit what the one-call model computes, refuses to run
+    before it is complete, and takes new weights for a layer."""
+    shape = MINI64.with_qkv_bias()
+    w = synth.model_weights(shape, 515, threads=4)
+    lazy = synth.model_weights_lazy(shape, 515, threads=4)
+    whole = cs.Model(w, max_batch=1, max_k=10)
+    parts = cs.Model(lazy, max_batch=1, max_k=10)
+    rng = np.random.default_rng(8)
+    prompt = rng.integers(0, shape.vocab, 120).tolist()
+    draft = rng.integers(0, shape.vocab, 10).tolist()
+    outs = []
+    for model in (whole, parts):
+        kv = cs.KV(model, 1, 200)
+        cs.cs_prefill(model, kv, 0, prompt)
+        acc, nx, logits = cs.cs_verify(model, kv, t32([prompt[-1]]), t32([draft]), t32([10]), 10, want_logits=True)
+        torch.cuda.synchronize()
+        outs.append((int(acc[0]), int(nx[0]), logits.cpu().numpy().copy()))
+        kv.destroy()
+    assert outs[0][:2] == outs[1][:2] and np.array_equal(outs[0][2], outs[1][2])
+    # an incomplete model refuses to run
+    lib = cs.load_library()
+    import ctypes as C
+    cfg = cs.cs_model_cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
+                          shape.d_ff, shape.vocab, cs.CS_BF16, shape.rope_theta, shape.rms_eps, 1, 10)
+    h = C.c_void_p()
+    assert lib.cs_model_create_staged(C.byref(cfg), C.byref(h)) == 0
+    kvh = C.c_void_p()
+    assert lib.cs_kv_create(h, 1, 64, C.byref(kvh)) == 0
+    tok = np.array([1, 2, 3], dtype=np.int32)
+    assert lib.cs_prefill(h, kvh, 0, tok.ctypes.data_as(C.c_void_p), 3) == -5          # CS_E_STATE
+    lib.cs_kv_destroy(kvh)
+    lib.cs_model_destroy(h)
+    whole.destroy()
+    parts.destroy()
+
+
 def test_qkv_bias_comes_complete_or_not_at_all():
     shape = SMALLF32.with_qkv_bias()
     w = synth.model_weights(shape, 778, threads=1)
