@@ -314,7 +314,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--shape", default="8b", choices=["8b", "1b", "qwen7b", "70b"])
+    ap.add_argument("--shape", default="8b", choices=["8b", "1b", "qwen7b", "70b", "qwen72b"])
     ap.add_argument("--layers", type=int, default=0, help="override depth (debug only; invalid as a result)")
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--k", type=int, default=10)

@@ -13,7 +13,8 @@ import torch
 import synth
 from . import binding as cs
 
-SHAPES = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B, "qwen7b": synth.QWEN_7B, "70b": synth.LLAMA_70B}
+SHAPES = {"8b": synth.LLAMA_8B, "1b": synth.LLAMA_1B, "qwen7b": synth.QWEN_7B, "70b": synth.LLAMA_70B,
+          "qwen72b": synth.QWEN_72B}
 
 
 def log(*a):

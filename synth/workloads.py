@@ -81,6 +81,8 @@ LLAMA_8B = ModelShape("llama-8b", 32, 4096, 32, 8, 128, 14336, 128256, 500000.0,
 QWEN_7B = ModelShape("qwen2.5-7b", 28, 3584, 28, 4, 128, 18944, 152064, 1000000.0, 1e-6, "bf16", True)
 # the largest model of the paper's tables in the 8B shape's family: 141 GB of bfloat16 weights
 LLAMA_70B = ModelShape("llama-70b", 80, 8192, 64, 8, 128, 28672, 128256, 500000.0, 1e-5, "bf16")
+# the model of the paper's largest speed-up (Table 1, Sec. 5): 145 GB of bfloat16 weights
+QWEN_72B = ModelShape("qwen2.5-72b", 80, 8192, 64, 8, 128, 29568, 152064, 1000000.0, 1e-6, "bf16", True)
 
 
 # ----------------------------------------------------------------------------
