@@ -360,6 +360,10 @@ def main():
 
     from paper_2502_08923_amd import workload as wl
     B, k = args.batch, args.k
+    if args.shape in ("70b", "qwen72b") and not args.no_cpu:
+        # the oracle would need these 140 GB of weights on the host, and minutes per stream
+        log("[bench] shapes of 70 G weights: the CPU baseline is left out (as with --no-cpu)")
+        args.no_cpu = True
     default_workload = (args.shape, B, k, args.doc, args.hist, args.layers) == ("8b", 8, 10, 2048, 16384, 0)
     run_cfg5 = default_workload and not args.no_cfg5
     # one model serves the headline workload and the long multi-turn configuration
