@@ -359,6 +359,21 @@ class Model:
         if weights.get("rope_inv_freq") is not None:      # the model brings its own rotary frequencies
             self.set_rope_inv_freq(weights["rope_inv_freq"])
 
+    def load_layer(self, layer: int, lw: dict):
+        """New weights for one layer (cs_model_load_layer): the dict of one entry of weights["layers"]."""
+        bf16 = self.dtype == CS_BF16
+        keep = []
+        one = cs_layer_weights()
+        for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            keep.append(_to_dev(lw[name], bf16, self.device))
+            setattr(one, name, keep[-1].data_ptr())
+        for name in ("norm1", "norm2", "bq", "bk", "bv"):
+            if name in lw:
+                keep.append(_to_dev(lw[name], False, self.device))
+                setattr(one, name, keep[-1].data_ptr())
+        torch.cuda.synchronize(self.device)
+        _check(load_library().cs_model_load_layer(self.handle, layer, C.byref(one)))
+
     def set_rope_inv_freq(self, inv_freq):
         """head_dim/2 rotary frequencies (angle of pair j at position p = p * inv_freq[j]); None
         goes back to rope_theta."""

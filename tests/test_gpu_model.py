@@ -252,6 +252,17 @@ def test_staged_creation_gives_the_same_model():
         outs.append((int(acc[0]), int(nx[0]), logits.cpu().numpy().copy()))
         kv.destroy()
     assert outs[0][:2] == outs[1][:2] and np.array_equal(outs[0][2], outs[1][2])
+    # new weights for a layer: the other layer's weights in layer 0 change the result, the old ones restore it
+    def logits_of(model):
+        kv = cs.KV(model, 1, 200)
+        cs.cs_prefill(model, kv, 0, prompt)
+        out = cs.cs_verify(model, kv, t32([prompt[-1]]), t32([draft]), t32([10]), 10, want_logits=True)[2].cpu().numpy().copy()
+        kv.destroy()
+        return out
+    parts.load_layer(0, w["layers"][1])
+    assert np.abs(logits_of(parts) - outs[0][2]).max() > 0.05
+    parts.load_layer(0, w["layers"][0])
+    assert np.array_equal(logits_of(parts), outs[0][2])
     # an incomplete model refuses to run
     lib = cs.load_library()
     import ctypes as C
