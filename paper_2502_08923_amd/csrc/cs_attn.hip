@@ -566,8 +566,6 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     __shared__ __attribute__((aligned(16))) unsigned char qs[FA_QG][FA_QROWS * QROW];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int team = (tid >> 6) / (FA_QG + 1), wave = (tid >> 6) % (FA_QG + 1);
-    unsigned char (*stage)[STAGE_BYTES] = stage_all[team];
     const int c = lane & 15, g = lane >> 4;
     // Workgroup -> (stream, KV head, token range pair, group of query groups).  The nqgw
     // workgroups that walk the same K/V range (long blocks, e.g. prompt ingestion) get ids 8
@@ -580,6 +578,18 @@ __global__ __launch_bounds__(FA_LDS_THREADS) void k_attn_lds(const bf16_t* __res
     // which group of FA_QG query groups: the last rows of a block see the most tokens (see n_lim
     // below), so they are dispatched first and the short ones fill the tail of the launch
     const int qgw = nqgw - 1 - slot % nqgw;
+    // Roles of the eight waves (hardware waves go to the four SIMDs in turn: wave w runs on SIMD
+    // w % 4).  With three live query groups per team: waves 0-2 and 4-6 are the consumers of teams 0
+    // and 1, waves 3 and 7 the producers, so every consumer SIMD carries one consumer of each team.
+    // With at most two live groups (e.g. 11 block rows of seven or eight query heads per KV head)
+    // the four live consumers get a SIMD each: waves 0-3 = (team 0, group 0), (0, 1), (1, 0), (1, 1),
+    // waves 4 and 5 the producers, waves 6 and 7 the dead third groups.
+    const int hw = tid >> 6;
+    const int live_groups = min(FA_QG, nqg - qgw * FA_QG);
+    const bool spread = live_groups <= 2;
+    const int team = spread ? (hw < 4 ? hw >> 1 : (hw & 1)) : hw / (FA_QG + 1);
+    const int wave = spread ? (hw < 4 ? (hw & 1) : (hw < 6 ? FA_QG : 2)) : hw % (FA_QG + 1);
+    unsigned char (*stage)[STAGE_BYTES] = stage_all[team];
     const int split = (range % nsp) * FA_TEAMS + team;  // number of this team's partial result
     const int kvh = (range / nsp) % KVH, b = range / (nsp * KVH);
     const int G = H / KVH;
